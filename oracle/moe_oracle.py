@@ -1,0 +1,441 @@
+"""CPU oracle for one GPU's share of an MoE FFN layer, forward and backward.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+layer computes, in float64 numpy.  Only the tests, the smoke check and the
+benchmark's cpu_baseline leg may import it; the product path never does, and it
+shares no code, tables or helpers with the HIP kernels.
+
+What the paper fixes and what is read into it
+---------------------------------------------
+The paper treats the layer's mathematics as background (Section 2.1: a trainable
+gate routes each token to its top-k experts, Fig. 2) and describes the operators
+and their order (Section 3.2 "Efficient operators": a row map computed from the
+routing result drives scatter and gather; Section 4.1: FC1 GroupedGEMM -> SwiGLU
+-> weighted sum -> FC2 GroupedGEMM, and which tensors the FC2 backward needs;
+Section 4.2: tokens ordered by expert, then by source rank, which on one rank is
+plain token order; Section 5 and Section 7 "FP8 training": E4M3 everywhere,
+per-token quantisation forward, per-channel quantisation in 128-token groups
+backward, gate weight applied after FC2 in the FP8 variant).  The method reaches
+exactly the plain layer result, so every function below is the plain definition
+written out.  Readings where the paper is silent (softmax gate over the selected
+logits, ties toward the lower expert id, slot order by descending logit, stable
+order inside an expert's segment, dropless, scale = amax/448) are stated where
+they are used.
+
+Parity pins: every function here is pinned by tests/test_oracle_*.py against
+brute force, closed forms, finite differences or an independent library routine.
+Nothing in this file is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# Routing: Section 2.1 (top-k gate), Section 3.2 (row map), Section 4.2 (order)
+# --------------------------------------------------------------------------
+
+def topk_select(logits: np.ndarray, k: int) -> np.ndarray:
+    """Experts chosen per token, as int32 [T, k].
+
+    Reading: the k largest *logits* win; equal logits go to the lower expert id
+    (so -0.0 and +0.0 tie); slot j holds the (j+1)-th largest.
+    """
+    z = np.asarray(logits)
+    assert z.dtype == np.float32 and z.ndim == 2
+    assert np.all(np.isfinite(z)), "routing is defined for finite logits only"
+    T, E = z.shape
+    assert 1 <= k <= E
+    # A stable ascending sort of -z keeps equal logits in ascending expert id.
+    order = np.argsort(-z.astype(F64), axis=1, kind="stable")
+    return order[:, :k].astype(np.int32)
+
+
+def gate_weights(logits: np.ndarray, idx: np.ndarray, renorm: int = 1) -> np.ndarray:
+    """Gate weights float64 [T, k].
+
+    renorm=1: softmax over the k selected logits (equals softmax over all experts
+    followed by renormalising the selected ones).  renorm=0: softmax over all E
+    experts, read at the selected ones.
+    """
+    z = np.asarray(logits).astype(F64)
+    sel = np.take_along_axis(z, idx.astype(np.int64), axis=1)
+    m = z.max(axis=1, keepdims=True)          # the row maximum is always selected
+    if renorm:
+        e = np.exp(sel - m)
+        return e / e.sum(axis=1, keepdims=True)
+    den = np.exp(z - m).sum(axis=1, keepdims=True)
+    return np.exp(sel - m) / den
+
+
+def row_map(idx: np.ndarray, E: int):
+    """counts [E], offsets [E+1], perm [M], inv_perm [M] (all int32).
+
+    Assignment id a = t*k + j.  Expert e owns rows offsets[e] .. offsets[e+1]-1 and
+    inside that segment assignments keep ascending id (Section 4.2: by expert, then
+    by source; one source here, so by token, then slot).  perm[row] = a,
+    inv_perm[a] = row.  Dropless and unpadded: offsets is the plain prefix sum.
+    """
+    e_of_a = np.asarray(idx).reshape(-1).astype(np.int64)
+    M = e_of_a.size
+    counts = np.zeros(E, dtype=np.int64)
+    for e in range(E):
+        counts[e] = int(np.count_nonzero(e_of_a == e))
+    offsets = np.zeros(E + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(counts)
+    perm = np.argsort(e_of_a, kind="stable")
+    inv_perm = np.empty(M, dtype=np.int64)
+    inv_perm[perm] = np.arange(M)
+    return (counts.astype(np.int32), offsets.astype(np.int32),
+            perm.astype(np.int32), inv_perm.astype(np.int32))
+
+
+def route(logits: np.ndarray, k: int, renorm: int = 1) -> dict:
+    idx = topk_select(logits, k)
+    w = gate_weights(logits, idx, renorm)
+    counts, offsets, perm, inv_perm = row_map(idx, logits.shape[1])
+    return dict(idx=idx, w=w, counts=counts, offsets=offsets, perm=perm, inv_perm=inv_perm)
+
+
+def route_bwd(logits, idx, w, dw, renorm: int = 1) -> np.ndarray:
+    """d(loss)/d(logits) float64 [T, E] given d(loss)/d(w); the selection is constant."""
+    T, E = np.asarray(logits).shape
+    idx64 = idx.astype(np.int64)
+    w = np.asarray(w, F64)
+    dw = np.asarray(dw, F64)
+    dz = np.zeros((T, E), dtype=F64)
+    if renorm:
+        inner = (w * dw).sum(axis=1, keepdims=True)
+        np.put_along_axis(dz, idx64, w * (dw - inner), axis=1)
+        return dz
+    z = np.asarray(logits).astype(F64)
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    inner = (w * dw).sum(axis=1, keepdims=True)      # w_j = p[e_j]
+    dz = -p * inner
+    sel = np.take_along_axis(dz, idx64, axis=1) + w * dw
+    np.put_along_axis(dz, idx64, sel, axis=1)
+    return dz
+
+
+# --------------------------------------------------------------------------
+# Router matmul (the "routing scores" operator of Section 7)
+# --------------------------------------------------------------------------
+
+def router_logits(x, W_r, bias=None) -> np.ndarray:
+    """z = x W_r (+ b) in float64; x [T,d], W_r [d,E]."""
+    z = np.asarray(x, F64) @ np.asarray(W_r, F64)
+    if bias is not None:
+        z = z + np.asarray(bias, F64)[None, :]
+    return z
+
+
+def router_bwd(x, W_r, dz):
+    """dW_r = x^T dz,  dx_r = dz W_r^T."""
+    x = np.asarray(x, F64)
+    dz = np.asarray(dz, F64)
+    return x.T @ dz, dz @ np.asarray(W_r, F64).T
+
+
+# --------------------------------------------------------------------------
+# Dispatch / combine: Section 3.2 (scatter and gather by a precomputed row map)
+# --------------------------------------------------------------------------
+
+def dispatch(x, perm, k: int, row_mul=None) -> np.ndarray:
+    """xp[r,:] = x[perm[r] div k, :]  (times row_mul[perm[r]] when given)."""
+    x = np.asarray(x, F64)
+    a = perm.astype(np.int64)
+    xp = x[a // k, :]
+    if row_mul is not None:
+        xp = xp * np.asarray(row_mul, F64).reshape(-1)[a][:, None]
+    return xp
+
+
+def combine(Y, inv_perm, w, T: int, k: int) -> np.ndarray:
+    """y[t,:] = sum_j w[t,j] * Y[inv_perm[t*k+j], :], slots in ascending j.  w=None: unweighted."""
+    Y = np.asarray(Y, F64)
+    rows = inv_perm.astype(np.int64).reshape(T, k)
+    y = np.zeros((T, Y.shape[1]), dtype=F64)
+    for j in range(k):
+        term = Y[rows[:, j], :]
+        if w is not None:
+            term = term * np.asarray(w, F64)[:, j][:, None]
+        y += term
+    return y
+
+
+def gate_grad(dy, Y, inv_perm, T: int, k: int) -> np.ndarray:
+    """dw[t,j] = <dy[t,:], Y[inv_perm[t*k+j], :]>  (derivative of combine w.r.t. the gate weight)."""
+    dy = np.asarray(dy, F64)
+    Y = np.asarray(Y, F64)
+    rows = inv_perm.astype(np.int64).reshape(T, k)
+    dw = np.empty((T, k), dtype=F64)
+    for j in range(k):
+        dw[:, j] = np.einsum("td,td->t", dy, Y[rows[:, j], :])
+    return dw
+
+
+# --------------------------------------------------------------------------
+# Expert FFN: Section 4.1 (FC1 GroupedGEMM -> SwiGLU -> FC2 GroupedGEMM)
+# --------------------------------------------------------------------------
+
+def silu(g):
+    return g / (1.0 + np.exp(-g))
+
+
+def expert_ffn_fwd(xp, offsets, W1, W2):
+    """Per expert e over its rows: G = X Wg^T, U = X Wu^T, A = silu(G)*U, Y = A Wd^T.
+
+    W1 [E, 2f, d] holds the gate projection in rows 0..f-1 and the up projection in
+    rows f..2f-1; W2 [E, d, f] is the down projection.  Returns H=[G|U], A, Y.
+    """
+    xp = np.asarray(xp, F64)
+    E, two_f, d = W1.shape
+    f = two_f // 2
+    M = xp.shape[0]
+    H = np.zeros((M, two_f), dtype=F64)
+    A = np.zeros((M, f), dtype=F64)
+    Y = np.zeros((M, d), dtype=F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo:
+            continue
+        X = xp[lo:hi]
+        G = X @ np.asarray(W1[e, :f, :], F64).T
+        U = X @ np.asarray(W1[e, f:, :], F64).T
+        H[lo:hi, :f] = G
+        H[lo:hi, f:] = U
+        A[lo:hi] = silu(G) * U
+        Y[lo:hi] = A[lo:hi] @ np.asarray(W2[e], F64).T
+    return H, A, Y
+
+
+def swiglu_bwd(G, U, dA):
+    """dG = dA*U*s*(1+G*(1-s)), dU = dA*G*s with s = sigmoid(G)."""
+    s = 1.0 / (1.0 + np.exp(-G))
+    return dA * U * s * (1.0 + G * (1.0 - s)), dA * G * s
+
+
+def expert_ffn_bwd(xp, H, dY, offsets, W1, W2, A=None):
+    """Gradients of expert_ffn_fwd: returns dxp [M,d], dW1 [E,2f,d], dW2 [E,d,f], dH [M,2f].
+
+    A (the FC2 input) is recomputed from the saved H unless given (the fp8 path
+    passes the quantised-dequantised A that FC2 actually consumed).  Experts with
+    no rows get exactly-zero weight gradients.
+    """
+    xp = np.asarray(xp, F64)
+    H = np.asarray(H, F64)
+    dY = np.asarray(dY, F64)
+    E, two_f, d = W1.shape
+    f = two_f // 2
+    M = xp.shape[0]
+    dxp = np.zeros((M, d), dtype=F64)
+    dH = np.zeros((M, two_f), dtype=F64)
+    dW1 = np.zeros((E, two_f, d), dtype=F64)
+    dW2 = np.zeros((E, d, f), dtype=F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo:
+            continue
+        G, U = H[lo:hi, :f], H[lo:hi, f:]
+        Ae = silu(G) * U if A is None else np.asarray(A[lo:hi], F64)
+        dYe = dY[lo:hi]
+        dA = dYe @ np.asarray(W2[e], F64)
+        dW2[e] = dYe.T @ Ae
+        dG, dU = swiglu_bwd(G, U, dA)
+        dH[lo:hi, :f] = dG
+        dH[lo:hi, f:] = dU
+        dW1[e] = dH[lo:hi].T @ xp[lo:hi]
+        dxp[lo:hi] = dH[lo:hi] @ np.asarray(W1[e], F64)
+    return dxp, dW1, dW2, dH
+
+
+# --------------------------------------------------------------------------
+# Whole layer
+# --------------------------------------------------------------------------
+
+def layer_fwd(x, logits, W1, W2, k: int, renorm: int = 1) -> dict:
+    """Forward of the whole path from fp32 logits: route, dispatch, expert FFN, combine."""
+    T = x.shape[0]
+    r = route(logits, k, renorm)
+    xp = dispatch(x, r["perm"], k)
+    H, A, Y = expert_ffn_fwd(xp, r["offsets"], W1, W2)
+    y = combine(Y, r["inv_perm"], r["w"], T, k)
+    r.update(xp=xp, H=H, A=A, Y=Y, y=y)
+    return r
+
+
+def layer_bwd(x, logits, W1, W2, k: int, dy, fwd: dict, renorm: int = 1, W_r=None) -> dict:
+    """Backward of the whole path.  The top-k selection is treated as a constant.
+
+    dY[r] = w[a]*dy[t];  dw = <dy, Y>;  expert-FFN gradients;  dx[t] = sum_j dxp[row(t,j)];
+    dz from the gate; with W_r given the router matmul's gradients are added too.
+    """
+    T = x.shape[0]
+    dYp = dispatch(dy, fwd["perm"], k, row_mul=fwd["w"])
+    dw = gate_grad(dy, fwd["Y"], fwd["inv_perm"], T, k)
+    dxp, dW1, dW2, dH = expert_ffn_bwd(fwd["xp"], fwd["H"], dYp, fwd["offsets"], W1, W2)
+    dx = combine(dxp, fwd["inv_perm"], None, T, k)
+    dz = route_bwd(logits, fwd["idx"], fwd["w"], dw, renorm)
+    out = dict(dYp=dYp, dw=dw, dxp=dxp, dW1=dW1, dW2=dW2, dH=dH, dx=dx, dz=dz)
+    if W_r is not None:
+        dWr, dx_r = router_bwd(x, W_r, dz)
+        out["dW_r"] = dWr
+        out["dx"] = dx + dx_r
+    return out
+
+
+# --------------------------------------------------------------------------
+# FP8 E4M3 cast (Section 5 "Communication compression for FP8 training", Section 7)
+# --------------------------------------------------------------------------
+# Reading: OCP e4m3fn -- 1 sign, 4 exponent (bias 7), 3 mantissa bits, subnormals
+# down to 2^-9, largest finite 448, no infinity, NaN = S.1111.111.
+
+E4M3_MAX = 448.0
+
+
+def e4m3_decode(codes) -> np.ndarray:
+    """Value of each 8-bit code as float64."""
+    c = np.asarray(codes).astype(np.int64)
+    s = np.where((c >> 7) & 1, -1.0, 1.0)
+    e = (c >> 3) & 15
+    m = (c & 7).astype(F64)
+    sub = m / 8.0 * 2.0 ** -6
+    nor = (1.0 + m / 8.0) * np.exp2((e - 7).astype(F64))
+    v = s * np.where(e == 0, sub, nor)
+    return np.where((e == 15) & ((c & 7) == 7), np.nan, v)
+
+
+def e4m3_encode(v) -> np.ndarray:
+    """Nearest code (ties to even mantissa), magnitudes above 448 saturate to 448; uint8."""
+    v = np.asarray(v, F64)
+    sign = np.signbit(v)
+    a = np.minimum(np.abs(np.where(np.isnan(v), 0.0, v)), E4M3_MAX)
+    # subnormal range and the first binade share the spacing 2^-9
+    _, ex = np.frexp(np.where(a > 0, a, 1.0))       # a = mant * 2^ex, mant in [0.5, 1)
+    e = np.maximum(ex - 1, -6)                       # unbiased exponent, clamped at the subnormal scale
+    q = np.rint(a / np.exp2((e - 3).astype(F64)))    # multiples of 2^(e-3); rint = ties to even
+    # q in [0, 16]: q < 8 subnormal (mantissa q), 8..15 normal, 16 carries into the next binade
+    carry = q >= 16
+    e = np.where(carry, e + 1, e)
+    q = np.where(carry, 8.0, q)
+    code = np.where(q < 8, q, ((e + 7) * 8 + (q - 8))).astype(np.int64)
+    code = np.where(np.isnan(v), 0x7F, code)
+    return (code | (sign.astype(np.int64) << 7)).astype(np.uint8)
+
+
+def _f32(a):
+    return np.asarray(a, dtype=np.float32)
+
+
+def _scale_and_codes(v32: np.ndarray, amax32: np.ndarray):
+    """Reading: amax = 0 gives scale 1; inv = 448/amax and scale = amax/448 are single fp32
+    divisions; the product v*inv is rounded to fp32, clamped to +-448, then encoded."""
+    safe = np.where(amax32 > 0, amax32, np.float32(1.0)).astype(np.float32)
+    inv = np.where(amax32 > 0, np.float32(E4M3_MAX) / safe, np.float32(1.0)).astype(np.float32)
+    scale = np.where(amax32 > 0, safe / np.float32(E4M3_MAX), np.float32(1.0)).astype(np.float32)
+    p = (v32 * inv).astype(np.float32)
+    p = np.clip(p, np.float32(-E4M3_MAX), np.float32(E4M3_MAX))
+    return e4m3_encode(p), scale
+
+
+def quant_rows(v):
+    """Per-token (1 x cols) quantisation: codes uint8 [rows, cols], scales float32 [rows]."""
+    v32 = _f32(v)
+    amax = np.abs(v32).max(axis=1, keepdims=True) if v32.shape[1] else np.zeros((v32.shape[0], 1), np.float32)
+    codes, scale = _scale_and_codes(v32, amax.astype(np.float32))
+    return codes, scale.reshape(-1)
+
+
+def quant_colgroup128(v, group: int = 128):
+    """Per-channel quantisation inside groups of 128 consecutive rows (tokens):
+    codes uint8 [rows, cols], scales float32 [ceil(rows/128), cols]."""
+    v32 = _f32(v)
+    rows, cols = v32.shape
+    ng = (rows + group - 1) // group
+    codes = np.zeros((rows, cols), dtype=np.uint8)
+    scales = np.ones((ng, cols), dtype=np.float32)
+    for g in range(ng):
+        blk = v32[g * group:(g + 1) * group]
+        amax = np.abs(blk).max(axis=0, keepdims=True).astype(np.float32)
+        c, s = _scale_and_codes(blk, amax)
+        codes[g * group:(g + 1) * group] = c
+        scales[g] = s.reshape(-1)
+    return codes, scales
+
+
+def dequant_rows(codes, scales) -> np.ndarray:
+    return e4m3_decode(codes) * np.asarray(scales, F64).reshape(-1, 1)
+
+
+def dequant_colgroup128(codes, scales, group: int = 128) -> np.ndarray:
+    rows = codes.shape[0]
+    s = np.repeat(np.asarray(scales, F64), group, axis=0)[:rows]
+    return e4m3_decode(codes) * s
+
+
+def fake_quant_rows(v) -> np.ndarray:
+    return dequant_rows(*quant_rows(v))
+
+
+def quant_weights(W1, W2):
+    """Per-output-channel weight quantisation: each row of W1[e] (2f rows of length d) and of
+    W2[e] (d rows of length f) gets one scale.  Returns (W1_hat, W2_hat) dequantised, float64."""
+    E, two_f, d = W1.shape
+    f = W2.shape[2]
+    W1h = fake_quant_rows(_f32(W1).reshape(E * two_f, d)).reshape(E, two_f, d)
+    W2h = fake_quant_rows(_f32(W2).reshape(E * d, f)).reshape(E, d, f)
+    return W1h, W2h
+
+
+def layer_fwd_fp8(x, logits, W1, W2, k: int, renorm: int = 1) -> dict:
+    """Forward with the FP8 casts as part of the function (float64 in between).
+
+    Quantisation points: x per token before dispatch; W1, W2 per output channel; the
+    SwiGLU output A per token; the FC2 output Y per token; the gate weight is applied
+    after FC2 on the dequantised Y (Section 7's placement for FP8).
+    """
+    T = x.shape[0]
+    r = route(logits, k, renorm)
+    x_hat = fake_quant_rows(x)
+    xp = dispatch(x_hat, r["perm"], k)
+    W1h, W2h = quant_weights(W1, W2)
+    E, two_f, d = W1.shape
+    f = two_f // 2
+    M = xp.shape[0]
+    H = np.zeros((M, two_f), F64)
+    A_hat = np.zeros((M, f), F64)
+    Y = np.zeros((M, d), F64)
+    for e in range(E):
+        lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
+        if hi == lo:
+            continue
+        G = xp[lo:hi] @ W1h[e, :f].T
+        U = xp[lo:hi] @ W1h[e, f:].T
+        H[lo:hi, :f], H[lo:hi, f:] = G, U
+        A_hat[lo:hi] = fake_quant_rows(silu(G) * U)
+        Y[lo:hi] = A_hat[lo:hi] @ W2h[e].T
+    Y_hat = fake_quant_rows(Y)
+    y = combine(Y_hat, r["inv_perm"], r["w"], T, k)
+    r.update(x_hat=x_hat, xp=xp, H=H, A=A_hat, Y=Y_hat, y=y)
+    return r
+
+
+def layer_bwd_fp8(x, logits, W1, W2, k: int, dy, fwd: dict, renorm: int = 1) -> dict:
+    """Backward of layer_fwd_fp8, straight-through (each cast has derivative 1).
+
+    Reading: dy is quantised per channel in 128-token groups in token order, and its
+    dequantised value is what every later step sees.  The four backward GEMMs use the
+    unquantised master weights, the saved H, the quantised-dequantised A and xp that
+    the forward GEMMs consumed.
+    """
+    T = x.shape[0]
+    dy_hat = dequant_colgroup128(*quant_colgroup128(dy))
+    dYp = dispatch(dy_hat, fwd["perm"], k, row_mul=fwd["w"])
+    dw = gate_grad(dy_hat, fwd["Y"], fwd["inv_perm"], T, k)
+    dxp, dW1, dW2, dH = expert_ffn_bwd(fwd["xp"], fwd["H"], dYp, fwd["offsets"], W1, W2, A=fwd["A"])
+    dx = combine(dxp, fwd["inv_perm"], None, T, k)
+    dz = route_bwd(logits, fwd["idx"], fwd["w"], dw, renorm)
+    return dict(dy_hat=dy_hat, dYp=dYp, dw=dw, dxp=dxp, dW1=dW1, dW2=dW2, dH=dH, dx=dx, dz=dz)

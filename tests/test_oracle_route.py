@@ -1,0 +1,201 @@
+"""Pins for the oracle's routing functions: brute force on tiny inputs, constructed ties,
+closed forms and library routines.  No GPU."""
+import numpy as np
+import pytest
+from scipy.special import softmax as scipy_softmax
+
+from oracle import moe_oracle as O
+from synth.moe_inputs import random_logits
+
+
+def brute_topk(z_row, k):
+    """Full ordering of one token's experts by (logit descending, id ascending), pure Python."""
+    order = sorted(range(len(z_row)), key=lambda e: (-float(z_row[e]), e))
+    return order[:k]
+
+
+def brute_row_map(idx, E):
+    """Definition of the row map with explicit loops: row(a) = offset[e(a)] + #{a' < a : e(a') = e(a)}."""
+    e_of_a = [int(v) for v in idx.reshape(-1)]
+    M = len(e_of_a)
+    counts = [0] * E
+    for e in e_of_a:
+        counts[e] += 1
+    offsets = [0] * (E + 1)
+    for e in range(E):
+        offsets[e + 1] = offsets[e] + counts[e]
+    perm = [None] * M
+    inv = [None] * M
+    for a in range(M):
+        earlier = sum(1 for b in range(a) if e_of_a[b] == e_of_a[a])
+        r = offsets[e_of_a[a]] + earlier
+        perm[r] = a
+        inv[a] = r
+    return counts, offsets, perm, inv
+
+
+@pytest.mark.parametrize("T,E,k,quantum", [(37, 8, 2, None), (64, 8, 2, 0.5), (50, 5, 5, 1.0),
+                                           (33, 16, 1, 0.25), (20, 64, 8, 0.5), (9, 3, 2, 2.0)])
+def test_topk_matches_brute_force(T, E, k, quantum):
+    z = random_logits(T, E, seed=T + E, quantum=quantum)
+    idx = O.topk_select(z, k)
+    for t in range(T):
+        assert list(idx[t]) == brute_topk(z[t], k)
+
+
+def test_constructed_ties():
+    # all equal: experts 0..k-1, weights 1/k
+    z = np.full((3, 6), 1.25, dtype=np.float32)
+    r = O.route(z, 3)
+    assert np.array_equal(r["idx"], np.tile(np.arange(3, dtype=np.int32), (3, 1)))
+    assert np.allclose(r["w"], 1.0 / 3.0, atol=1e-15)
+    # -0.0 and +0.0 are the same logit: lower id wins
+    z = np.array([[-0.0, 0.0, -1.0, 0.0]], dtype=np.float32)
+    assert list(O.topk_select(z, 2)[0]) == [0, 1]
+    z = np.array([[0.0, -0.0, -1.0, 0.0]], dtype=np.float32)
+    assert list(O.topk_select(z, 3)[0]) == [0, 1, 3]
+    # duplicates straddling the k-th place: the lower ids among the equals get in
+    z = np.array([[1.0, 5.0, 1.0, 1.0, 7.0]], dtype=np.float32)
+    assert list(O.topk_select(z, 3)[0]) == [4, 1, 0]
+    assert list(O.topk_select(z, 4)[0]) == [4, 1, 0, 2]
+    # pairs equal: order inside the pair is by id
+    z = np.array([[2.0, 3.0, 3.0, 2.0]], dtype=np.float32)
+    assert list(O.topk_select(z, 4)[0]) == [1, 2, 0, 3]
+    # k = 1 is argmax with the first occurrence
+    z = random_logits(100, 7, seed=3, quantum=1.0)
+    assert np.array_equal(O.topk_select(z, 1)[:, 0], np.argmax(z, axis=1))
+    # E = k selects everything
+    z = random_logits(10, 4, seed=5)
+    assert np.array_equal(np.sort(O.topk_select(z, 4), axis=1), np.tile(np.arange(4), (10, 1)))
+
+
+def test_slot_order_is_descending_logit():
+    z = random_logits(200, 16, seed=9)
+    idx = O.topk_select(z, 5)
+    sel = np.take_along_axis(z, idx.astype(np.int64), axis=1)
+    assert np.all(np.diff(sel, axis=1) <= 0)
+
+
+def test_gate_weights_closed_forms():
+    z = random_logits(128, 8, seed=1)
+    for k in (1, 2, 8):
+        idx = O.topk_select(z, k)
+        w = O.gate_weights(z, idx, renorm=1)
+        assert np.allclose(w.sum(axis=1), 1.0, atol=1e-12)
+        assert np.all(w > 0)
+    # k = E with renormalisation is the full softmax (library routine), in the selected order
+    idx = O.topk_select(z, 8)
+    w = O.gate_weights(z, idx, renorm=1)
+    p = scipy_softmax(z.astype(np.float64), axis=1)
+    assert np.allclose(w, np.take_along_axis(p, idx.astype(np.int64), axis=1), rtol=1e-12, atol=1e-15)
+    # renorm = 0: softmax over all experts read at the selected ones
+    idx = O.topk_select(z, 2)
+    w0 = O.gate_weights(z, idx, renorm=0)
+    assert np.allclose(w0, np.take_along_axis(p, idx.astype(np.int64), axis=1), rtol=1e-12, atol=1e-15)
+    # renormalising the selected entries of the full softmax gives the renorm=1 weights
+    w1 = O.gate_weights(z, idx, renorm=1)
+    assert np.allclose(w0 / w0.sum(axis=1, keepdims=True), w1, rtol=1e-12)
+    # two experts: weight of the top one is the logistic of the logit gap
+    sel = np.take_along_axis(z.astype(np.float64), idx.astype(np.int64), axis=1)
+    assert np.allclose(w1[:, 0], 1.0 / (1.0 + np.exp(-(sel[:, 0] - sel[:, 1]))), rtol=1e-12)
+
+
+def test_gate_weights_shift_invariance_and_large_logits():
+    z = (random_logits(16, 8, seed=2) * 30).astype(np.float32)
+    idx = O.topk_select(z, 3)
+    w = O.gate_weights(z, idx)
+    w_shift = O.gate_weights(z.astype(np.float64) + 1000.0, idx)
+    assert np.all(np.isfinite(w)) and np.allclose(w, w_shift, rtol=1e-9)
+
+
+@pytest.mark.parametrize("T,E,k,quantum", [(23, 4, 2, None), (40, 8, 3, 1.0), (16, 6, 6, None), (31, 9, 1, 0.5)])
+def test_row_map_matches_brute_force(T, E, k, quantum):
+    z = random_logits(T, E, seed=7 * T + k, quantum=quantum)
+    r = O.route(z, k)
+    counts, offsets, perm, inv = brute_row_map(r["idx"], E)
+    assert list(r["counts"]) == counts
+    assert list(r["offsets"]) == offsets
+    assert list(r["perm"]) == perm
+    assert list(r["inv_perm"]) == inv
+
+
+def test_row_map_invariants_and_library_routines():
+    T, E, k = 3000, 64, 8
+    z = random_logits(T, E, seed=11)
+    z[:, 5] -= 100.0          # expert 5 is never chosen
+    r = O.route(z, k)
+    M = T * k
+    e_of_a = r["idx"].reshape(-1)
+    assert r["counts"].sum() == M and r["counts"][5] == 0
+    assert np.array_equal(r["counts"], np.bincount(e_of_a, minlength=E))
+    assert np.array_equal(r["offsets"], np.concatenate([[0], np.cumsum(r["counts"])]))
+    assert r["offsets"][E] == M and np.all(np.diff(r["offsets"]) >= 0)
+    assert np.array_equal(np.sort(r["perm"]), np.arange(M))
+    assert np.array_equal(r["inv_perm"][r["perm"]], np.arange(M))
+    e_sorted = e_of_a[r["perm"]]
+    assert np.all(np.diff(e_sorted) >= 0)
+    for e in range(E):
+        seg = r["perm"][r["offsets"][e]:r["offsets"][e + 1]]
+        assert np.all(np.diff(seg) > 0)
+        assert np.all(e_of_a[seg] == e)
+    # each token's k experts are distinct
+    assert all(len(set(row)) == k for row in r["idx"][:200])
+
+
+def test_all_tokens_one_expert():
+    z = np.zeros((17, 4), dtype=np.float32)
+    z[:, 2] = 5.0
+    r = O.route(z, 1)
+    assert list(r["counts"]) == [0, 0, 17, 0]
+    assert list(r["offsets"]) == [0, 0, 0, 17, 17]
+    assert np.array_equal(r["perm"], np.arange(17))
+
+
+def _num_jac_w(z64, idx, renorm, eps=1e-6):
+    T, E = z64.shape
+    k = idx.shape[1]
+    J = np.zeros((T, k, E))
+    for e in range(E):
+        zp, zm = z64.copy(), z64.copy()
+        zp[:, e] += eps
+        zm[:, e] -= eps
+        J[:, :, e] = (O.gate_weights(zp, idx, renorm) - O.gate_weights(zm, idx, renorm)) / (2 * eps)
+    return J
+
+
+@pytest.mark.parametrize("renorm", [1, 0])
+def test_route_bwd_finite_differences(renorm):
+    T, E, k = 6, 7, 3
+    z = random_logits(T, E, seed=4)
+    idx = O.topk_select(z, k)
+    w = O.gate_weights(z, idx, renorm)
+    rng = np.random.default_rng(0)
+    dw = rng.standard_normal((T, k))
+    dz = O.route_bwd(z, idx, w, dw, renorm)
+    J = _num_jac_w(z.astype(np.float64), idx, renorm)
+    dz_num = np.einsum("tk,tke->te", dw, J)
+    assert np.allclose(dz, dz_num, rtol=1e-6, atol=1e-8)
+    if renorm:
+        # softmax Jacobian has the all-ones vector in its null space; unselected entries are zero
+        assert np.allclose(dz.sum(axis=1), 0.0, atol=1e-12)
+        mask = np.ones((T, E), bool)
+        np.put_along_axis(mask, idx.astype(np.int64), False, axis=1)
+        assert np.all(dz[mask] == 0.0)
+
+
+def test_router_matmul_and_bwd():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((5, 4))
+    W = rng.standard_normal((4, 3))
+    b = rng.standard_normal(3)
+    z = O.router_logits(x, W, b)
+    for t in range(5):
+        for e in range(3):
+            assert abs(z[t, e] - (sum(x[t, i] * W[i, e] for i in range(4)) + b[e])) < 1e-12
+    dz = rng.standard_normal((5, 3))
+    dW, dx = O.router_bwd(x, W, dz)
+    # adjoint identities: <dz, x dW'> = <dW, dW'> for any dW', likewise for x
+    Wp = rng.standard_normal((4, 3))
+    xp = rng.standard_normal((5, 4))
+    assert np.isclose((dz * (x @ Wp)).sum(), (dW * Wp).sum())
+    assert np.isclose((dz * (xp @ W)).sum(), (dx * xp).sum())
