@@ -1,0 +1,174 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) MoE expert-FFN hot path.
+ *
+ * One GPU's share of a mixture-of-experts FFN layer, forward and backward, after
+ * MegaScale-MoE (arXiv 2505.11432): top-k gating, token dispatch into expert-contiguous
+ * buffers, the expert grouped GEMMs with SwiGLU, the gate-weighted combine, and the E4M3
+ * cast that stands in for the paper's communication compression.
+ *
+ * Conventions for every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller (16-byte aligned).  The
+ *     library allocates nothing, frees nothing and keeps no pointer after it returns.
+ *     Scratch comes from the caller's `workspace` (size from moe_workspace_bytes).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call only
+ *     enqueues kernels on that stream and returns; it never synchronises and never copies
+ *     device data to the host.  Expert row counts live on the device only, so grids are
+ *     sized for the worst case and kernels read `offsets` themselves.
+ *   - Return value: MOE_OK, or a negative moe_status.  Arguments are validated before any
+ *     HIP call, so argument errors are reported on a machine without a GPU as well.
+ *   - Matrices are row-major and dense.  Weights are "out, in": w1 [E, 2f, d] (gate
+ *     projection in rows 0..f-1, up projection in rows f..2f-1), w2 [E, d, f], w_r [E_r, d].
+ *   - T tokens, d model width (the paper's h), f expert width (h_ffn), E experts, k experts
+ *     per token, M = T*k dispatched rows.  Assignment id a = t*k + j (token t, slot j).
+ *   - d and f must be multiples of 16; 1 <= k <= E <= MOE_MAX_EXPERTS; k <= MOE_MAX_TOPK.
+ *   - T = 0 is valid and does nothing.  Non-finite logits give an unspecified routing.
+ *   - Calls on different streams may run concurrently as long as their buffers (workspace
+ *     included) do not overlap.
+ */
+#ifndef MOE_HIP_MOE_H
+#define MOE_HIP_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_ABI_VERSION 1
+#define MOE_MAX_EXPERTS 256
+#define MOE_MAX_TOPK 16
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID = -1,      /* NULL pointer, negative size, k < 1, k > E, E too large */
+  MOE_ERR_UNSUPPORTED = -2,  /* dtype combination or alignment the kernels do not cover */
+  MOE_ERR_WORKSPACE = -3,    /* workspace missing or smaller than moe_workspace_bytes */
+  MOE_ERR_HIP = -4           /* a HIP runtime call failed; see moe_last_hip_error */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1, MOE_F8E4M3 = 2 /* OCP e4m3fn, max 448 */ } moe_dtype;
+typedef enum { MOE_Q_ROW = 0, MOE_Q_COLGROUP128 = 1 } moe_qmode;
+
+int moe_abi_version(void);
+/* hipError_t value of the last failed HIP call made by this thread (0 if none). */
+int moe_last_hip_error(void);
+const char* moe_status_string(int status);
+
+/* Bytes of scratch that the largest consumer (moe_expert_ffn_bwd) needs for these sizes;
+ * valid for every call of this library with the same sizes.  0 on invalid sizes. */
+size_t moe_workspace_bytes(int T, int d, int E, int k, int f, moe_dtype act);
+
+/* ---- router matmul: the "routing scores" operator (Section 7, "MoE vs. dense") -------
+ * logits[t,e] = sum_i x[t,i] * w_r[e,i] (+ bias[e]); fp32 accumulate, fp32 result.
+ * x [T,d] and w_r [E,d] in `dt` (MOE_F32 or MOE_BF16); bias [E] fp32 or NULL. */
+int moe_router_fwd(const void* x, const void* w_r, const float* bias, moe_dtype dt,
+                   int T, int d, int E, float* logits /*[T,E]*/, void* stream);
+
+/* Gradients of moe_router_fwd: d_w_r[e,i] = sum_t d_logits[t,e] * x[t,i] (fp32 [E,d],
+ * overwritten) and dx[t,i] += sum_e d_logits[t,e] * w_r[e,i] (dx [T,d] in `dt`, read and
+ * written).  d_w_r or dx may be NULL to skip that half. */
+int moe_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt,
+                   int T, int d, int E, float* d_w_r, void* dx, void* stream);
+
+/* ---- gating and row map (Section 2.1: top-k gate; Section 3.2 "Efficient operators":
+ * the pre-computed mapping from input rows to output rows; Section 4.2: rows ordered by
+ * expert, then by source, i.e. by assignment id on one rank) ---------------------------
+ * Per token the k largest logits are selected (equal logits: lower expert id first; slot
+ * j holds the (j+1)-th largest).  renorm=1: topk_w = softmax over the k selected logits;
+ * renorm=0: softmax over all E logits read at the selected experts.
+ * counts[e] = number of assignments to e; offsets = exclusive prefix sum, offsets[E] = M.
+ * perm[r] = assignment id held by dispatched row r (stable: ascending a inside an
+ * expert's segment); inv_perm[a] = r.  All outputs are fully written.  Integer outputs
+ * are deterministic and unique.  Needs workspace. */
+int moe_route(const float* logits /*[T,E]*/, int T, int E, int k, int renorm,
+              int32_t* topk_idx /*[T,k]*/, float* topk_w /*[T,k]*/,
+              int32_t* counts /*[E]*/, int32_t* offsets /*[E+1]*/,
+              int32_t* perm /*[T*k]*/, int32_t* inv_perm /*[T*k]*/,
+              void* workspace, size_t ws_bytes, void* stream);
+
+/* Derivative of the gate weights w.r.t. the logits with the selection held constant.
+ * d_logits [T,E] is fully written (zeros at unselected experts when renorm=1).
+ * `logits` is only read when renorm=0 and may be NULL otherwise. */
+int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* topk_w,
+                  const float* d_topk_w, int T, int E, int k, int renorm,
+                  float* d_logits, void* stream);
+
+/* ---- dispatch / combine (Section 3.2: scatter and gather driven by the row map) -------
+ * moe_dispatch: xp[inv_perm[t*k+j], :] = x[t, :] for every slot j, i.e. xp[r,:] =
+ * x[perm[r] / k, :]  (* row_mul[t*k+j] if row_mul != NULL; with row_mul = topk_w this is
+ * the backward of the weighted combine).  Every row of xp below T*k is written.
+ * dt = MOE_F32 | MOE_BF16 | MOE_F8E4M3.  For MOE_F8E4M3 rows are 1-byte codes and the
+ * per-token scale x_scale[t] is copied to xp_scale[row]; row_mul must then be NULL. */
+int moe_dispatch(const void* x /*[T,d]*/, const float* x_scale /*[T] or NULL*/, moe_dtype dt,
+                 const int32_t* inv_perm /*[T*k]*/, const float* row_mul /*[T*k] or NULL*/,
+                 int T, int k, int d, void* xp /*[T*k,d]*/, float* xp_scale /*[T*k] or NULL*/,
+                 void* stream);
+
+/* moe_combine: y[t,:] = sum_j topk_w[t,j] * yp[inv_perm[t*k+j], :], summed in fp32 in
+ * ascending j and rounded once to y_dt.  topk_w = NULL: unweighted (the backward of
+ * dispatch).  For dt = MOE_F8E4M3 each row is dequantised with yp_scale[row] first. */
+int moe_combine(const void* yp /*[T*k,d]*/, const float* yp_scale /*[T*k] or NULL*/, moe_dtype dt,
+                const int32_t* inv_perm, const float* topk_w /*[T,k] or NULL*/,
+                int T, int k, int d, void* y /*[T,d]*/, moe_dtype y_dt, void* stream);
+
+/* d_topk_w[t,j] = <dy[t,:], yp[inv_perm[t*k+j], :]> in fp32 (derivative of the combine
+ * w.r.t. the gate weights).  dy in dy_dt (MOE_F32|MOE_BF16); yp as in moe_combine. */
+int moe_gate_grad(const void* dy /*[T,d]*/, moe_dtype dy_dt, const void* yp /*[T*k,d]*/,
+                  const float* yp_scale, moe_dtype dt, const int32_t* inv_perm,
+                  int T, int k, int d, float* d_topk_w /*[T,k]*/, void* stream);
+
+/* ---- expert FFN (Section 4.1: FC1 GroupedGEMM -> SwiGLU -> FC2 GroupedGEMM) ----------
+ * For expert e and its rows r in [offsets[e], offsets[e+1]):
+ *   [G|U] = xp[r,:] * w1[e]^T,  A = G/(1+exp(-G)) * U,  yp[r,:] = A * w2[e]^T.
+ * h_save [M,2f] receives [G|U] in the activation type (bf16 for MOE_BF16 and for the fp8
+ * path, fp32 for MOE_F32); it is what the backward needs (the paper keeps the two FC1
+ * outputs and recomputes the FC2 input).  fp32 accumulation throughout.
+ * act_dt = w_dt = out_dt = MOE_F32 or MOE_BF16: plain path, scales must be NULL.
+ * act_dt = w_dt = MOE_F8E4M3: xp holds codes with per-row scales xp_scale[M]; w1/w2 hold
+ * codes with per-output-channel scales w1_scale [E,2f], w2_scale [E,d]; A is quantised per
+ * row before FC2; out_dt = MOE_F8E4M3 writes yp as codes with per-row scales yp_scale[M],
+ * out_dt = MOE_BF16 writes it unquantised.  Rows >= offsets[E] are not touched. */
+int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt,
+                       const int32_t* offsets /*[E+1], device*/,
+                       const void* w1 /*[E,2f,d]*/, const float* w1_scale,
+                       const void* w2 /*[E,d,f]*/, const float* w2_scale, moe_dtype w_dt,
+                       int M, int d, int E, int f,
+                       void* h_save /*[M,2f]*/, void* yp /*[M,d]*/, float* yp_scale,
+                       moe_dtype out_dt, void* workspace, size_t ws_bytes, void* stream);
+
+/* Gradients of the expert FFN (Section 4.1, Fig. 8b: the FC2 backward takes the recomputed
+ * FC2 input and the gradient of the FC2 output).  dt = MOE_F32 | MOE_BF16 for xp, h_save,
+ * d_yp, w1, w2 and d_xp.  With A recomputed from h_save:
+ *   dA = d_yp * w2[e];  d_w2[e] = d_yp_e^T * A_e;  (dG,dU) = SwiGLU'(G,U,dA);
+ *   d_xp = [dG|dU] * w1[e];  d_w1[e] = [dG|dU]_e^T * xp_e.
+ * a_override (or NULL): an [M,f] matrix in `dt` to use as A in d_w2 instead of the
+ * recomputed one (the fp8 path passes the dequantised A that FC2 consumed).
+ * grad_dt = MOE_F32 | MOE_BF16 is the type of d_w1 [E,2f,d] and d_w2 [E,d,f].
+ * accumulate = 0: weight gradients are overwritten, experts without rows get exact zeros;
+ * accumulate = 1: added into the existing values (fp32 main gradients kept across
+ * micro-batches, Section 5). */
+int moe_expert_ffn_bwd(const void* xp, const void* h_save, const void* d_yp,
+                       const void* a_override, const int32_t* offsets,
+                       const void* w1, const void* w2, moe_dtype dt,
+                       int M, int d, int E, int f,
+                       void* d_xp /*[M,d]*/, void* d_w1, void* d_w2, moe_dtype grad_dt,
+                       int accumulate, void* workspace, size_t ws_bytes, void* stream);
+
+/* ---- E4M3 cast (Section 5 "Communication compression for FP8 training"; Section 7 "FP8
+ * training": per-token 1 x h scales forward, per-channel scales in 128-token groups
+ * backward) ---------------------------------------------------------------------------
+ * MOE_Q_ROW: one scale per row.  MOE_Q_COLGROUP128: one scale per column inside each group
+ * of 128 consecutive rows.  amax = max |v| of the group; amax = 0 gives scale 1 and codes 0;
+ * otherwise scale = amax/448 and code = nearest-even e4m3 of clamp(fp32(v) * (448/amax)),
+ * all in fp32.  src_dt / dst_dt = MOE_F32 | MOE_BF16. */
+int moe_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmode mode,
+                  uint8_t* codes /*[rows,cols]*/,
+                  float* scales /*[rows] or [ceil(rows/128),cols]*/, void* stream);
+int moe_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols,
+                    moe_qmode mode, void* dst, moe_dtype dst_dt, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HIP_MOE_H */

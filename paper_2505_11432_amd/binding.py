@@ -1,0 +1,179 @@
+"""ctypes binding of libmoe_hip.so: same names as the C ABI (include/moe.h), argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used for device memory
+and streams, nothing else), passes their device pointers and the current stream to the library and
+raises MoEError on a non-zero status.  There is no CPU fallback: if the library is missing the
+import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_int, c_size_t, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
+
+F32, BF16, F8E4M3 = 0, 1, 2
+Q_ROW, Q_COLGROUP128 = 0, 1
+MAX_EXPERTS, MAX_TOPK = 256, 16
+
+EXPORTS = (
+    "moe_abi_version", "moe_last_hip_error", "moe_status_string", "moe_workspace_bytes",
+    "moe_router_fwd", "moe_router_bwd", "moe_route", "moe_route_bwd", "moe_dispatch", "moe_combine",
+    "moe_gate_grad", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_quant_fp8", "moe_dequant_fp8",
+)
+
+
+class MoEError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        msg = _lib.moe_status_string(status).decode()
+        extra = f" (hipError {_lib.moe_last_hip_error()})" if status == -4 else ""
+        super().__init__(f"{fn} failed: {status} {msg}{extra}")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2505_11432_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P, I, Z = c_void_p, c_int, c_size_t
+    sig = {
+        "moe_abi_version": (I, []),
+        "moe_last_hip_error": (I, []),
+        "moe_status_string": (c_char_p, [I]),
+        "moe_workspace_bytes": (Z, [I, I, I, I, I, I]),
+        "moe_router_fwd": (I, [P, P, P, I, I, I, I, P, P]),
+        "moe_router_bwd": (I, [P, P, P, I, I, I, I, P, P, P]),
+        "moe_route": (I, [P, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
+        "moe_route_bwd": (I, [P, P, P, P, I, I, I, I, P, P]),
+        "moe_dispatch": (I, [P, P, I, P, P, I, I, I, P, P, P]),
+        "moe_combine": (I, [P, P, I, P, P, I, I, I, P, I, P]),
+        "moe_gate_grad": (I, [P, I, P, P, I, P, I, I, I, P, P]),
+        "moe_expert_ffn_fwd": (I, [P, P, I, P, P, P, P, P, I, I, I, I, I, P, P, P, I, P, Z, P]),
+        "moe_expert_ffn_bwd": (I, [P, P, P, P, P, P, P, I, I, I, I, I, P, P, P, I, I, P, Z, P]),
+        "moe_quant_fp8": (I, [P, I, I, I, I, P, P, P]),
+        "moe_dequant_fp8": (I, [P, P, I, I, I, P, I, P]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+_lib = _load()
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    if t in (torch.uint8, torch.float8_e4m3fn):
+        return F8E4M3
+    raise TypeError(f"unsupported dtype {t}")
+
+
+def _p(t):
+    """Device pointer of a tensor (None -> NULL)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "tensors must be contiguous and on the GPU"
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(fn: str, status: int):
+    if status != 0:
+        raise MoEError(fn, status)
+
+
+def moe_abi_version() -> int:
+    return _lib.moe_abi_version()
+
+
+def moe_workspace_bytes(T, d, E, k, f, act) -> int:
+    return _lib.moe_workspace_bytes(T, d, E, k, f, act)
+
+
+def moe_router_fwd(x, w_r, bias, logits):
+    T, d = x.shape
+    E = w_r.shape[0]
+    _check("moe_router_fwd", _lib.moe_router_fwd(_p(x), _p(w_r), _p(bias), dtype_code(x.dtype), T, d, E,
+                                                 _p(logits), _stream()))
+
+
+def moe_router_bwd(x, w_r, d_logits, d_w_r, dx):
+    T, d = x.shape
+    E = w_r.shape[0]
+    _check("moe_router_bwd", _lib.moe_router_bwd(_p(x), _p(w_r), _p(d_logits), dtype_code(x.dtype), T, d, E,
+                                                 _p(d_w_r), _p(dx), _stream()))
+
+
+def moe_route(logits, k, renorm, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace):
+    T, E = logits.shape
+    _check("moe_route", _lib.moe_route(_p(logits), T, E, k, renorm, _p(topk_idx), _p(topk_w), _p(counts),
+                                       _p(offsets), _p(perm), _p(inv_perm), _p(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_route_bwd(logits, topk_idx, topk_w, d_topk_w, E, renorm, d_logits):
+    T, k = topk_idx.shape
+    _check("moe_route_bwd", _lib.moe_route_bwd(_p(logits), _p(topk_idx), _p(topk_w), _p(d_topk_w), T, E, k,
+                                               renorm, _p(d_logits), _stream()))
+
+
+def moe_dispatch(x, x_scale, inv_perm, row_mul, k, xp, xp_scale):
+    T, d = x.shape
+    _check("moe_dispatch", _lib.moe_dispatch(_p(x), _p(x_scale), dtype_code(x.dtype), _p(inv_perm), _p(row_mul),
+                                             T, k, d, _p(xp), _p(xp_scale), _stream()))
+
+
+def moe_combine(yp, yp_scale, inv_perm, topk_w, k, y):
+    T, d = y.shape
+    _check("moe_combine", _lib.moe_combine(_p(yp), _p(yp_scale), dtype_code(yp.dtype), _p(inv_perm), _p(topk_w),
+                                           T, k, d, _p(y), dtype_code(y.dtype), _stream()))
+
+
+def moe_gate_grad(dy, yp, yp_scale, inv_perm, k, d_topk_w):
+    T, d = dy.shape
+    _check("moe_gate_grad", _lib.moe_gate_grad(_p(dy), dtype_code(dy.dtype), _p(yp), _p(yp_scale),
+                                               dtype_code(yp.dtype), _p(inv_perm), T, k, d, _p(d_topk_w),
+                                               _stream()))
+
+
+def moe_expert_ffn_fwd(xp, xp_scale, offsets, w1, w1_scale, w2, w2_scale, h_save, yp, yp_scale, workspace):
+    M, d = xp.shape
+    E, two_f, _ = w1.shape
+    _check("moe_expert_ffn_fwd", _lib.moe_expert_ffn_fwd(
+        _p(xp), _p(xp_scale), dtype_code(xp.dtype), _p(offsets), _p(w1), _p(w1_scale), _p(w2), _p(w2_scale),
+        dtype_code(w1.dtype), M, d, E, two_f // 2, _p(h_save), _p(yp), _p(yp_scale), dtype_code(yp.dtype),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_expert_ffn_bwd(xp, h_save, d_yp, a_override, offsets, w1, w2, d_xp, d_w1, d_w2, accumulate, workspace):
+    M, d = xp.shape
+    E, two_f, _ = w1.shape
+    _check("moe_expert_ffn_bwd", _lib.moe_expert_ffn_bwd(
+        _p(xp), _p(h_save), _p(d_yp), _p(a_override), _p(offsets), _p(w1), _p(w2), dtype_code(xp.dtype), M, d, E,
+        two_f // 2, _p(d_xp), _p(d_w1), _p(d_w2), dtype_code(d_w1.dtype), int(accumulate), _p(workspace),
+        workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_quant_fp8(src, mode, codes, scales):
+    rows, cols = src.shape
+    _check("moe_quant_fp8", _lib.moe_quant_fp8(_p(src), dtype_code(src.dtype), rows, cols, mode, _p(codes),
+                                               _p(scales), _stream()))
+
+
+def moe_dequant_fp8(codes, scales, mode, dst):
+    rows, cols = codes.shape
+    _check("moe_dequant_fp8", _lib.moe_dequant_fp8(_p(codes), _p(scales), rows, cols, mode, _p(dst),
+                                                   dtype_code(dst.dtype), _stream()))

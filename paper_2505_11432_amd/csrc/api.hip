@@ -1,0 +1,311 @@
+// extern "C" entry points: argument validation (before any HIP call), workspace carving and the
+// sequencing of kernels for each call.  Declarations and contracts are in include/moe.h.
+#include "moe_common.h"
+
+namespace moe {
+
+static thread_local int g_last_hip_error = 0;
+
+int record_hip_error(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return MOE_ERR_HIP;
+}
+
+size_t ffn_fwd_ws_bytes(int M, int d, int f, moe_dtype act, moe_dtype out) {
+  const size_t m = (size_t)M;
+  if (act == MOE_F8E4M3) {
+    // A in bf16, A codes, A scales, Y in bf16 (only when yp is written as codes)
+    size_t b = align_up(m * f * 2, 256) + align_up(m * f, 256) + align_up(m * 4, 256);
+    if (out == MOE_F8E4M3) b += align_up(m * d * 2, 256);
+    return b;
+  }
+  return align_up(m * f * dtype_size(act), 256);
+}
+
+size_t ffn_bwd_ws_bytes(int M, int d, int f, moe_dtype dt) {
+  (void)d;
+  const size_t m = (size_t)M, es = dtype_size(dt);
+  return align_up(m * f * es, 256) * 2 + align_up(m * 2 * f * es, 256);
+}
+
+static bool sizes_ok(int T, int d, int E, int k, int f) {
+  return T >= 0 && d > 0 && f > 0 && E >= 1 && E <= MOE_MAX_EXPERTS && k >= 1 && k <= E && k <= MOE_MAX_TOPK &&
+         (long)T * k <= 0x7fffffffL;
+}
+
+static int ffn_fwd_plain(const void* xp, const int32_t* offsets, const void* w1, const void* w2, moe_dtype dt, int M,
+                         int d, int E, int f, void* h_save, void* yp, void* ws, hipStream_t s) {
+  void* A = ws;
+  GemmProblem g{};
+  g.offsets = offsets; g.E = E; g.mode = 0; g.M = M; g.accumulate = 0; g.bias = nullptr;
+  // FC1: H[M,2f] = xp[M,d] * w1[e]^T
+  g.A = xp; g.a_rs = d; g.a_cs = 1;
+  g.B = w1; g.b_es = 2L * f * d; g.b_rs = 1; g.b_cs = d;
+  g.C = h_save; g.c_es = 0; g.ldc = 2L * f; g.N = 2 * f; g.K = d;
+  int rc = launch_gemm_generic(g, dt, dt, dt, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_swiglu_fwd(h_save, A, M, f, offsets + E, dt, s);
+  if (rc != MOE_OK) return rc;
+  // FC2: yp[M,d] = A[M,f] * w2[e]^T
+  g.A = A; g.a_rs = f; g.a_cs = 1;
+  g.B = w2; g.b_es = (long)d * f; g.b_rs = 1; g.b_cs = f;
+  g.C = yp; g.ldc = d; g.N = d; g.K = f;
+  return launch_gemm_generic(g, dt, dt, dt, s);
+}
+
+static int ffn_bwd_plain(const void* xp, const void* h_save, const void* d_yp, const void* a_override,
+                         const int32_t* offsets, const void* w1, const void* w2, moe_dtype dt, int M, int d, int E,
+                         int f, void* d_xp, void* d_w1, void* d_w2, moe_dtype grad_dt, int accumulate, void* ws,
+                         hipStream_t s) {
+  const size_t es = dtype_size(dt);
+  char* base = static_cast<char*>(ws);
+  void* A = base;
+  void* dA = base + align_up((size_t)M * f * es, 256);
+  void* dH = base + 2 * align_up((size_t)M * f * es, 256);
+  int rc;
+  const void* A_used = a_override;
+  if (a_override == nullptr) {
+    rc = launch_swiglu_fwd(h_save, A, M, f, offsets + E, dt, s);     // recompute the FC2 input
+    if (rc != MOE_OK) return rc;
+    A_used = A;
+  }
+  GemmProblem g{};
+  g.offsets = offsets; g.E = E; g.bias = nullptr;
+  // dA[M,f] = d_yp[M,d] * w2[e]   (contraction over d)
+  g.mode = 0; g.M = M; g.accumulate = 0;
+  g.A = d_yp; g.a_rs = d; g.a_cs = 1;
+  g.B = w2; g.b_es = (long)d * f; g.b_rs = f; g.b_cs = 1;
+  g.C = dA; g.c_es = 0; g.ldc = f; g.N = f; g.K = d;
+  rc = launch_gemm_generic(g, dt, dt, dt, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_swiglu_bwd(h_save, dA, dH, M, f, offsets + E, dt, s);
+  if (rc != MOE_OK) return rc;
+  // d_w2[e][d,f] = d_yp_e^T * A_e   (contraction over the expert's rows)
+  g.mode = 1; g.accumulate = accumulate;
+  g.A = d_yp; g.a_rs = 1; g.a_cs = d;
+  g.B = A_used; g.b_es = 0; g.b_rs = f; g.b_cs = 1;
+  g.C = d_w2; g.c_es = (long)d * f; g.ldc = f; g.M = d; g.N = f; g.K = M;
+  rc = launch_gemm_generic(g, dt, dt, grad_dt, s);
+  if (rc != MOE_OK) return rc;
+  // d_xp[M,d] = dH[M,2f] * w1[e]   (contraction over 2f)
+  g.mode = 0; g.accumulate = 0;
+  g.A = dH; g.a_rs = 2L * f; g.a_cs = 1;
+  g.B = w1; g.b_es = 2L * f * d; g.b_rs = d; g.b_cs = 1;
+  g.C = d_xp; g.c_es = 0; g.ldc = d; g.M = M; g.N = d; g.K = 2 * f;
+  rc = launch_gemm_generic(g, dt, dt, dt, s);
+  if (rc != MOE_OK) return rc;
+  // d_w1[e][2f,d] = dH_e^T * xp_e
+  g.mode = 1; g.accumulate = accumulate;
+  g.A = dH; g.a_rs = 1; g.a_cs = 2L * f;
+  g.B = xp; g.b_es = 0; g.b_rs = d; g.b_cs = 1;
+  g.C = d_w1; g.c_es = 2L * f * d; g.ldc = d; g.M = 2 * f; g.N = d; g.K = M;
+  return launch_gemm_generic(g, dt, dt, grad_dt, s);
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+int moe_abi_version(void) { return MOE_ABI_VERSION; }
+int moe_last_hip_error(void) { return g_last_hip_error; }
+
+const char* moe_status_string(int status) {
+  switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_INVALID: return "invalid argument";
+    case MOE_ERR_UNSUPPORTED: return "unsupported dtype, size or alignment";
+    case MOE_ERR_WORKSPACE: return "workspace missing or too small";
+    case MOE_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t moe_workspace_bytes(int T, int d, int E, int k, int f, moe_dtype act) {
+  if (!sizes_ok(T, d, E, k, f)) return 0;
+  if (act != MOE_F32 && act != MOE_BF16 && act != MOE_F8E4M3) return 0;
+  const int M = T * k;
+  const moe_dtype bwd_dt = act == MOE_F32 ? MOE_F32 : MOE_BF16;
+  size_t b = route_ws_bytes(T, E);
+  const size_t fw = ffn_fwd_ws_bytes(M, d, f, act, act);
+  const size_t bw = ffn_bwd_ws_bytes(M, d, f, bwd_dt);
+  if (fw > b) b = fw;
+  if (bw > b) b = bw;
+  return b + 256;
+}
+
+int moe_router_fwd(const void* x, const void* w_r, const float* bias, moe_dtype dt, int T, int d, int E,
+                   float* logits, void* stream) {
+  if (T < 0 || d <= 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_OK;
+  if (!x || !w_r || !logits) return MOE_ERR_INVALID;
+  if (dt != MOE_F32 && dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  GemmProblem g{};
+  g.mode = 2; g.E = 1; g.offsets = nullptr; g.accumulate = 0; g.bias = bias;
+  g.A = x; g.a_rs = d; g.a_cs = 1;
+  g.B = w_r; g.b_es = 0; g.b_rs = 1; g.b_cs = d;
+  g.C = logits; g.c_es = 0; g.ldc = E; g.M = T; g.N = E; g.K = d;
+  return launch_gemm_generic(g, dt, dt, MOE_F32, as_stream(stream));
+}
+
+int moe_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt, int T, int d, int E,
+                   float* d_w_r, void* dx, void* stream) {
+  if (T < 0 || d <= 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (dt != MOE_F32 && dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (!d_logits && T > 0) return MOE_ERR_INVALID;
+  if ((d_w_r && !x) || (dx && !w_r)) return MOE_ERR_INVALID;
+  hipStream_t s = as_stream(stream);
+  GemmProblem g{};
+  g.mode = 2; g.E = 1; g.offsets = nullptr; g.bias = nullptr;
+  if (d_w_r) {
+    // d_w_r[E,d] = d_logits^T * x   (contraction over tokens; T = 0 writes zeros)
+    g.accumulate = 0;
+    g.A = d_logits; g.a_rs = 1; g.a_cs = E;
+    g.B = x; g.b_es = 0; g.b_rs = d; g.b_cs = 1;
+    g.C = d_w_r; g.c_es = 0; g.ldc = d; g.M = E; g.N = d; g.K = T;
+    const int rc = launch_gemm_generic(g, MOE_F32, dt, MOE_F32, s);
+    if (rc != MOE_OK) return rc;
+  }
+  if (dx && T > 0) {
+    g.accumulate = 1;
+    g.A = d_logits; g.a_rs = E; g.a_cs = 1;
+    g.B = w_r; g.b_es = 0; g.b_rs = d; g.b_cs = 1;
+    g.C = dx; g.c_es = 0; g.ldc = d; g.M = T; g.N = d; g.K = E;
+    return launch_gemm_generic(g, MOE_F32, dt, dt, s);
+  }
+  return MOE_OK;
+}
+
+int moe_route(const float* logits, int T, int E, int k, int renorm, int32_t* topk_idx, float* topk_w,
+              int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* workspace, size_t ws_bytes,
+              void* stream) {
+  if (!sizes_ok(T, 16, E, k, 16)) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_OK;
+  if (!logits || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID;
+  if (!workspace || ws_bytes < route_ws_bytes(T, E)) return MOE_ERR_WORKSPACE;
+  return launch_route(logits, T, E, k, renorm != 0, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace,
+                      as_stream(stream));
+}
+
+int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* topk_w, const float* d_topk_w, int T,
+                  int E, int k, int renorm, float* d_logits, void* stream) {
+  if (!sizes_ok(T, 16, E, k, 16)) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_OK;
+  if (!topk_idx || !topk_w || !d_topk_w || !d_logits) return MOE_ERR_INVALID;
+  if (!renorm && !logits) return MOE_ERR_INVALID;
+  return launch_route_bwd(logits, topk_idx, topk_w, d_topk_w, T, E, k, renorm != 0, d_logits, as_stream(stream));
+}
+
+int moe_dispatch(const void* x, const float* x_scale, moe_dtype dt, const int32_t* inv_perm, const float* row_mul,
+                 int T, int k, int d, void* xp, float* xp_scale, void* stream) {
+  if (T < 0 || k < 1 || k > MOE_MAX_TOPK || d <= 0 || (long)T * k > 0x7fffffffL) return MOE_ERR_INVALID;
+  if (dt != MOE_F32 && dt != MOE_BF16 && dt != MOE_F8E4M3) return MOE_ERR_UNSUPPORTED;
+  if (d % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (T == 0) return MOE_OK;
+  if (!x || !inv_perm || !xp) return MOE_ERR_INVALID;
+  if (dt == MOE_F8E4M3) {
+    if (row_mul) return MOE_ERR_UNSUPPORTED;
+    if (!x_scale || !xp_scale) return MOE_ERR_INVALID;
+  } else if (x_scale || xp_scale) {
+    return MOE_ERR_INVALID;
+  }
+  if (!aligned16(x) || !aligned16(xp)) return MOE_ERR_UNSUPPORTED;
+  return launch_dispatch(x, x_scale, dt, inv_perm, row_mul, T, k, d, xp, xp_scale, as_stream(stream));
+}
+
+int moe_combine(const void* yp, const float* yp_scale, moe_dtype dt, const int32_t* inv_perm, const float* topk_w,
+                int T, int k, int d, void* y, moe_dtype y_dt, void* stream) {
+  if (T < 0 || k < 1 || k > MOE_MAX_TOPK || d <= 0 || (long)T * k > 0x7fffffffL) return MOE_ERR_INVALID;
+  if (d % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (dt != MOE_F32 && dt != MOE_BF16 && dt != MOE_F8E4M3) return MOE_ERR_UNSUPPORTED;
+  if (y_dt != MOE_F32 && y_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (dt == MOE_F32 && y_dt != MOE_F32) return MOE_ERR_UNSUPPORTED;
+  if (T == 0) return MOE_OK;
+  if (!yp || !inv_perm || !y) return MOE_ERR_INVALID;
+  if ((dt == MOE_F8E4M3) != (yp_scale != nullptr)) return MOE_ERR_INVALID;
+  if (!aligned16(yp) || !aligned16(y)) return MOE_ERR_UNSUPPORTED;
+  return launch_combine(yp, yp_scale, dt, inv_perm, topk_w, T, k, d, y, y_dt, as_stream(stream));
+}
+
+int moe_gate_grad(const void* dy, moe_dtype dy_dt, const void* yp, const float* yp_scale, moe_dtype dt,
+                  const int32_t* inv_perm, int T, int k, int d, float* d_topk_w, void* stream) {
+  if (T < 0 || k < 1 || k > MOE_MAX_TOPK || d <= 0 || (long)T * k > 0x7fffffffL) return MOE_ERR_INVALID;
+  if (d % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (dy_dt != MOE_F32 && dy_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (dt != MOE_F8E4M3 && dt != dy_dt) return MOE_ERR_UNSUPPORTED;
+  if (T == 0) return MOE_OK;
+  if (!dy || !yp || !inv_perm || !d_topk_w) return MOE_ERR_INVALID;
+  if ((dt == MOE_F8E4M3) != (yp_scale != nullptr)) return MOE_ERR_INVALID;
+  if (!aligned16(yp) || !aligned16(dy)) return MOE_ERR_UNSUPPORTED;
+  return launch_gate_grad(dy, dy_dt, yp, yp_scale, dt, inv_perm, T, k, d, d_topk_w, as_stream(stream));
+}
+
+int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt, const int32_t* offsets,
+                       const void* w1, const float* w1_scale, const void* w2, const float* w2_scale, moe_dtype w_dt,
+                       int M, int d, int E, int f, void* h_save, void* yp, float* yp_scale, moe_dtype out_dt,
+                       void* workspace, size_t ws_bytes, void* stream) {
+  if (M < 0 || d <= 0 || f <= 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (d % 16 != 0 || f % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (act_dt != w_dt) return MOE_ERR_UNSUPPORTED;
+  if (act_dt != MOE_F32 && act_dt != MOE_BF16 && act_dt != MOE_F8E4M3) return MOE_ERR_UNSUPPORTED;
+  if (act_dt != MOE_F8E4M3 && out_dt != act_dt) return MOE_ERR_UNSUPPORTED;
+  if (act_dt == MOE_F8E4M3 && out_dt != MOE_F8E4M3 && out_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (M == 0) return MOE_OK;
+  if (!xp || !offsets || !w1 || !w2 || !h_save || !yp) return MOE_ERR_INVALID;
+  const bool fp8 = act_dt == MOE_F8E4M3;
+  if (fp8 != (xp_scale != nullptr) || fp8 != (w1_scale != nullptr) || fp8 != (w2_scale != nullptr))
+    return MOE_ERR_INVALID;
+  if ((out_dt == MOE_F8E4M3) != (yp_scale != nullptr)) return MOE_ERR_INVALID;
+  if (!aligned16(xp) || !aligned16(w1) || !aligned16(w2) || !aligned16(h_save) || !aligned16(yp) ||
+      !aligned16(workspace))
+    return MOE_ERR_UNSUPPORTED;
+  if (!workspace || ws_bytes < ffn_fwd_ws_bytes(M, d, f, act_dt, out_dt)) return MOE_ERR_WORKSPACE;
+  if (fp8) return MOE_ERR_UNSUPPORTED;
+  return ffn_fwd_plain(xp, offsets, w1, w2, act_dt, M, d, E, f, h_save, yp, workspace, as_stream(stream));
+}
+
+int moe_expert_ffn_bwd(const void* xp, const void* h_save, const void* d_yp, const void* a_override,
+                       const int32_t* offsets, const void* w1, const void* w2, moe_dtype dt, int M, int d, int E,
+                       int f, void* d_xp, void* d_w1, void* d_w2, moe_dtype grad_dt, int accumulate, void* workspace,
+                       size_t ws_bytes, void* stream) {
+  if (M < 0 || d <= 0 || f <= 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (d % 16 != 0 || f % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (dt != MOE_F32 && dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (grad_dt != MOE_F32 && grad_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (dt == MOE_F32 && grad_dt != MOE_F32) return MOE_ERR_UNSUPPORTED;
+  if (!offsets || !d_w1 || !d_w2) return MOE_ERR_INVALID;
+  if (M > 0 && (!xp || !h_save || !d_yp || !w1 || !w2 || !d_xp)) return MOE_ERR_INVALID;
+  if (!aligned16(xp) || !aligned16(h_save) || !aligned16(d_yp) || !aligned16(w1) || !aligned16(w2) ||
+      !aligned16(d_xp) || !aligned16(d_w1) || !aligned16(d_w2) || !aligned16(a_override) || !aligned16(workspace))
+    return MOE_ERR_UNSUPPORTED;
+  if (M > 0 && (!workspace || ws_bytes < ffn_bwd_ws_bytes(M, d, f, dt))) return MOE_ERR_WORKSPACE;
+  return ffn_bwd_plain(xp, h_save, d_yp, a_override, offsets, w1, w2, dt, M, d, E, f, d_xp, d_w1, d_w2, grad_dt,
+                       accumulate != 0, workspace, as_stream(stream));
+}
+
+int moe_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmode mode, uint8_t* codes,
+                  float* scales, void* stream) {
+  if (rows < 0 || cols < 0) return MOE_ERR_INVALID;
+  if (src_dt != MOE_F32 && src_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (mode != MOE_Q_ROW && mode != MOE_Q_COLGROUP128) return MOE_ERR_INVALID;
+  if (cols % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (rows == 0 || cols == 0) return MOE_OK;
+  if (!src || !codes || !scales) return MOE_ERR_INVALID;
+  if (!aligned16(src) || !aligned16(codes)) return MOE_ERR_UNSUPPORTED;
+  return launch_quant_fp8(src, src_dt, rows, cols, mode, codes, scales, as_stream(stream));
+}
+
+int moe_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols, moe_qmode mode, void* dst,
+                    moe_dtype dst_dt, void* stream) {
+  if (rows < 0 || cols < 0) return MOE_ERR_INVALID;
+  if (dst_dt != MOE_F32 && dst_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (mode != MOE_Q_ROW && mode != MOE_Q_COLGROUP128) return MOE_ERR_INVALID;
+  if (cols % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (rows == 0 || cols == 0) return MOE_OK;
+  if (!codes || !scales || !dst) return MOE_ERR_INVALID;
+  if (!aligned16(codes) || !aligned16(dst)) return MOE_ERR_UNSUPPORTED;
+  return launch_dequant_fp8(codes, scales, rows, cols, mode, dst, dst_dt, as_stream(stream));
+}
+
+}  // extern "C"

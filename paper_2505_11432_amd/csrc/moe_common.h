@@ -1,0 +1,88 @@
+// Shared host/device helpers of the gfx950 MoE kernels (internal; the public ABI is include/moe.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/moe.h"
+
+namespace moe {
+
+typedef __bf16 bf16;
+
+// ---- host side -----------------------------------------------------------------------------
+int record_hip_error(hipError_t e);          // remembers e for moe_last_hip_error, returns MOE_ERR_HIP
+
+#define MOE_HIP_TRY(expr)                                   \
+  do {                                                      \
+    hipError_t _e = (expr);                                 \
+    if (_e != hipSuccess) return ::moe::record_hip_error(_e); \
+  } while (0)
+
+// Call after every kernel launch: launch failures surface here, not at the next sync.
+#define MOE_LAUNCH_CHECK() MOE_HIP_TRY(hipGetLastError())
+
+static inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t dtype_size(moe_dtype t) { return t == MOE_F32 ? 4 : (t == MOE_BF16 ? 2 : 1); }
+
+// Number of token chunks the routing kernels split T into (one histogram row per chunk).
+static inline int route_chunk_tokens(int T) {
+  int tb = 64;
+  while ((T + tb - 1) / tb > 1024) tb *= 2;
+  return tb;
+}
+
+// Workspace layouts, shared by moe_workspace_bytes and the calls that carve the buffer up.
+size_t route_ws_bytes(int T, int E);
+size_t ffn_fwd_ws_bytes(int M, int d, int f, moe_dtype act, moe_dtype out);
+size_t ffn_bwd_ws_bytes(int M, int d, int f, moe_dtype dt);
+
+// ---- device side ---------------------------------------------------------------------------
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return static_cast<float>(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return static_cast<bf16>(v); }
+
+__device__ __forceinline__ float sigmoid_f32(float g) { return 1.0f / (1.0f + __expf(-g)); }
+
+// Vector of 16 bytes of T for coalesced row traffic.
+template <typename T> struct Vec16 { static constexpr int N = 16 / sizeof(T); T v[16 / sizeof(T)]; };
+
+// ---- kernel launchers (one per translation unit) -------------------------------------------
+// Generic strided grouped GEMM on the vector ALU (fp32 FMA); covers fp32 data and odd shapes.
+struct GemmProblem {
+  const void* A; long a_rs, a_cs;            // A(m,k) = A[m*a_rs + k*a_cs]
+  const void* B; long b_es, b_rs, b_cs;      // B(e,k,n) = B[e*b_es + k*b_rs + n*b_cs]
+  void* C; long c_es, ldc;                   // C(e,m,n) = C[e*c_es + m*ldc + n]
+  const int32_t* offsets; int E;             // expert segments (device)
+  int mode;                                  // 0: rows of A/C are segmented; 1: the contraction index is; 2: one plain GEMM
+  int M, N, K;                               // mode 0: M = upper bound on rows; mode 1: K = upper bound
+  int accumulate;                            // C += instead of C =
+  const float* bias;                         // per-column fp32 bias added in the epilogue, or NULL
+};
+int launch_gemm_generic(const GemmProblem& p, moe_dtype a_dt, moe_dtype b_dt, moe_dtype c_dt, hipStream_t s);
+
+int launch_route(const float* logits, int T, int E, int k, int renorm, int32_t* idx, float* w, int32_t* counts,
+                 int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t s);
+int launch_route_bwd(const float* logits, const int32_t* idx, const float* w, const float* dw, int T, int E, int k,
+                     int renorm, float* d_logits, hipStream_t s);
+int launch_dispatch(const void* x, const float* x_scale, moe_dtype dt, const int32_t* inv_perm, const float* row_mul,
+                    int T, int k, int d, void* xp, float* xp_scale, hipStream_t s);
+int launch_combine(const void* yp, const float* yp_scale, moe_dtype dt, const int32_t* inv_perm, const float* topk_w,
+                   int T, int k, int d, void* y, moe_dtype y_dt, hipStream_t s);
+int launch_gate_grad(const void* dy, moe_dtype dy_dt, const void* yp, const float* yp_scale, moe_dtype dt,
+                     const int32_t* inv_perm, int T, int k, int d, float* d_topk_w, hipStream_t s);
+int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmode mode, uint8_t* codes,
+                     float* scales, hipStream_t s);
+int launch_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols, moe_qmode mode, void* dst,
+                       moe_dtype dst_dt, hipStream_t s);
+
+int launch_swiglu_fwd(const void* H, void* A, int M, int f, const int32_t* row_limit, moe_dtype dt, hipStream_t s);
+int launch_swiglu_bwd(const void* H, const void* dA, void* dH, int M, int f, const int32_t* row_limit,
+                      moe_dtype dt, hipStream_t s);
+
+}  // namespace moe

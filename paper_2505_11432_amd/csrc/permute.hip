@@ -1,0 +1,246 @@
+// Dispatch, combine and the gate-weight gradient (Section 3.2: scatter and gather operators that move
+// rows according to a row map computed once from the routing result; Section 4.1: the weighted sum).
+// All three are HBM-bound row movers: one wave walks one token's row in 16-byte vectors per lane, so
+// every global access is a full 1 KiB wave-wide burst.  Token-centric on both sides: dispatch reads a
+// token row once and writes its k copies; combine gathers k rows and writes one.
+#include "moe_common.h"
+
+namespace moe {
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+
+// Broadcast lane `src` (wave-uniform) of a per-lane value; reads the register whatever EXEC says.
+__device__ __forceinline__ int bcast(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
+__device__ __forceinline__ float bcast(float v, int src) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src));
+}
+
+template <typename T, bool kScaled>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) dispatch_kernel(const T* __restrict__ x,
+                                                                       const float* __restrict__ x_scale,
+                                                                       const int32_t* __restrict__ inv_perm,
+                                                                       const float* __restrict__ row_mul, int T_, int k,
+                                                                       int d, T* __restrict__ xp,
+                                                                       float* __restrict__ xp_scale) {
+  constexpr int V = 16 / sizeof(T);
+  const int lane = threadIdx.x % 64;
+  const int wave = blockIdx.x * kWavesPerBlock + threadIdx.x / 64;
+  const int nwaves = gridDim.x * kWavesPerBlock;
+  const int nvec = d / V;
+  for (int t = wave; t < T_; t += nwaves) {
+    int my_row = 0;
+    float my_mul = 1.f;
+    if (lane < k) {
+      my_row = inv_perm[(long)t * k + lane];
+      if constexpr (kScaled) my_mul = row_mul[(long)t * k + lane];
+      if (x_scale != nullptr) xp_scale[my_row] = x_scale[t];
+    }
+    for (int c0 = 0; c0 < nvec; c0 += 64) {
+      const int c = c0 + lane;
+      const bool active = c < nvec;
+      Vec16<T> v;
+      if (active) v = *reinterpret_cast<const Vec16<T>*>(x + (long)t * d + (long)c * V);
+      for (int j = 0; j < k; ++j) {
+        const int r = bcast(my_row, j);
+        Vec16<T> o = v;
+        if constexpr (kScaled) {
+          const float m = bcast(my_mul, j);
+#pragma unroll
+          for (int i = 0; i < V; ++i) o.v[i] = from_f32<T>(to_f32(v.v[i]) * m);
+        }
+        if (active) *reinterpret_cast<Vec16<T>*>(xp + (long)r * d + (long)c * V) = o;
+      }
+    }
+  }
+}
+
+// fp8 codes are bytes; they are decoded by the hardware converter (OCP e4m3 on gfx950).
+template <typename TIN> struct RowLoader {
+  static constexpr int V = 16 / sizeof(TIN);
+  __device__ static void load(const TIN* p, float (&out)[V]) {
+    const Vec16<TIN> v = *reinterpret_cast<const Vec16<TIN>*>(p);
+#pragma unroll
+    for (int i = 0; i < V; ++i) out[i] = to_f32(v.v[i]);
+  }
+};
+template <> struct RowLoader<uint8_t> {
+  static constexpr int V = 16;
+  __device__ static void load(const uint8_t* p, float (&out)[16]) {
+    const uint4 q = *reinterpret_cast<const uint4*>(p);
+    const unsigned w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[4 * i + 0] = __builtin_amdgcn_cvt_f32_fp8((int)w[i], 0);
+      out[4 * i + 1] = __builtin_amdgcn_cvt_f32_fp8((int)w[i], 1);
+      out[4 * i + 2] = __builtin_amdgcn_cvt_f32_fp8((int)w[i], 2);
+      out[4 * i + 3] = __builtin_amdgcn_cvt_f32_fp8((int)w[i], 3);
+    }
+  }
+};
+
+template <typename TIN, typename TOUT>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) combine_kernel(const TIN* __restrict__ yp,
+                                                                      const float* __restrict__ yp_scale,
+                                                                      const int32_t* __restrict__ inv_perm,
+                                                                      const float* __restrict__ topk_w, int T_, int k,
+                                                                      int d, TOUT* __restrict__ y) {
+  constexpr int V = RowLoader<TIN>::V;      // elements per lane per step
+  const int lane = threadIdx.x % 64;
+  const int wave = blockIdx.x * kWavesPerBlock + threadIdx.x / 64;
+  const int nwaves = gridDim.x * kWavesPerBlock;
+  const int nvec = d / V;
+  for (int t = wave; t < T_; t += nwaves) {
+    int my_row = 0;
+    float my_w = 1.f;
+    if (lane < k) {
+      my_row = inv_perm[(long)t * k + lane];
+      if (topk_w != nullptr) my_w = topk_w[(long)t * k + lane];
+      if (yp_scale != nullptr) my_w *= yp_scale[my_row];
+    }
+    for (int c0 = 0; c0 < nvec; c0 += 64) {
+      const int c = c0 + lane;
+      const bool active = c < nvec;
+      float acc[V];
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] = 0.f;
+      for (int j = 0; j < k; ++j) {
+        const int r = bcast(my_row, j);
+        const float w = bcast(my_w, j);
+        if (active) {
+          float v[V];
+          RowLoader<TIN>::load(yp + (long)r * d + (long)c * V, v);
+#pragma unroll
+          for (int i = 0; i < V; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+        }
+      }
+      if (active) {
+        TOUT* dst = y + (long)t * d + (long)c * V;
+#pragma unroll
+        for (int i = 0; i < V; ++i) dst[i] = from_f32<TOUT>(acc[i]);
+      }
+    }
+  }
+}
+
+template <typename TDY, typename TIN>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) gate_grad_kernel(const TDY* __restrict__ dy,
+                                                                        const TIN* __restrict__ yp,
+                                                                        const float* __restrict__ yp_scale,
+                                                                        const int32_t* __restrict__ inv_perm, int T_,
+                                                                        int k, int d, float* __restrict__ d_topk_w) {
+  constexpr int V = RowLoader<TIN>::V;
+  const int lane = threadIdx.x % 64;
+  const int wave = blockIdx.x * kWavesPerBlock + threadIdx.x / 64;
+  const int nwaves = gridDim.x * kWavesPerBlock;
+  const int nvec = d / V;
+  for (int t = wave; t < T_; t += nwaves) {
+    int my_row = 0;
+    float my_scale = 1.f;
+    if (lane < k) {
+      my_row = inv_perm[(long)t * k + lane];
+      if (yp_scale != nullptr) my_scale = yp_scale[my_row];
+    }
+    float acc[MOE_MAX_TOPK];
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_TOPK; ++j) acc[j] = 0.f;
+    for (int c0 = 0; c0 < nvec; c0 += 64) {
+      const int c = c0 + lane;
+      const bool active = c < nvec;
+      float g[V];
+#pragma unroll
+      for (int i = 0; i < V; ++i) g[i] = 0.f;
+      if (active) {
+        const TDY* src = dy + (long)t * d + (long)c * V;
+#pragma unroll
+        for (int i = 0; i < V; ++i) g[i] = to_f32(src[i]);
+      }
+#pragma unroll
+      for (int j = 0; j < MOE_MAX_TOPK; ++j) {
+        if (j < k) {
+          const int r = bcast(my_row, j);
+          if (active) {
+            float v[V];
+            RowLoader<TIN>::load(yp + (long)r * d + (long)c * V, v);
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < V; ++i) s = fmaf(g[i], v[i], s);
+            acc[j] += s;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_TOPK; ++j) {
+      if (j < k) {
+        float s = acc[j];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+        s *= bcast(my_scale, j);
+        if (lane == 0) d_topk_w[(long)t * k + j] = s;
+      }
+    }
+  }
+}
+
+int row_grid(int T) {
+  int blocks = cdiv(T, kWavesPerBlock);
+  const int cap = 256 * 8;
+  return blocks < 1 ? 1 : (blocks > cap ? cap : blocks);
+}
+
+}  // namespace
+
+int launch_dispatch(const void* x, const float* x_scale, moe_dtype dt, const int32_t* inv_perm, const float* row_mul,
+                    int T, int k, int d, void* xp, float* xp_scale, hipStream_t s) {
+  const dim3 grid(row_grid(T)), block(64 * kWavesPerBlock);
+  if (dt == MOE_F32) {
+    if (row_mul) dispatch_kernel<float, true><<<grid, block, 0, s>>>((const float*)x, nullptr, inv_perm, row_mul, T, k, d, (float*)xp, nullptr);
+    else dispatch_kernel<float, false><<<grid, block, 0, s>>>((const float*)x, nullptr, inv_perm, nullptr, T, k, d, (float*)xp, nullptr);
+  } else if (dt == MOE_BF16) {
+    if (row_mul) dispatch_kernel<bf16, true><<<grid, block, 0, s>>>((const bf16*)x, nullptr, inv_perm, row_mul, T, k, d, (bf16*)xp, nullptr);
+    else dispatch_kernel<bf16, false><<<grid, block, 0, s>>>((const bf16*)x, nullptr, inv_perm, nullptr, T, k, d, (bf16*)xp, nullptr);
+  } else {
+    dispatch_kernel<uint8_t, false><<<grid, block, 0, s>>>((const uint8_t*)x, x_scale, inv_perm, nullptr, T, k, d, (uint8_t*)xp, xp_scale);
+  }
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
+int launch_combine(const void* yp, const float* yp_scale, moe_dtype dt, const int32_t* inv_perm, const float* topk_w,
+                   int T, int k, int d, void* y, moe_dtype y_dt, hipStream_t s) {
+  const dim3 grid(row_grid(T)), block(64 * kWavesPerBlock);
+#define MOE_COMBINE_CASE(DI, DO, TI, TO)                                                                       \
+  if (dt == DI && y_dt == DO) {                                                                                \
+    combine_kernel<TI, TO><<<grid, block, 0, s>>>((const TI*)yp, yp_scale, inv_perm, topk_w, T, k, d, (TO*)y); \
+    MOE_LAUNCH_CHECK();                                                                                        \
+    return MOE_OK;                                                                                             \
+  }
+  MOE_COMBINE_CASE(MOE_F32, MOE_F32, float, float)
+  MOE_COMBINE_CASE(MOE_BF16, MOE_BF16, bf16, bf16)
+  MOE_COMBINE_CASE(MOE_BF16, MOE_F32, bf16, float)
+  MOE_COMBINE_CASE(MOE_F8E4M3, MOE_BF16, uint8_t, bf16)
+  MOE_COMBINE_CASE(MOE_F8E4M3, MOE_F32, uint8_t, float)
+#undef MOE_COMBINE_CASE
+  return MOE_ERR_UNSUPPORTED;
+}
+
+int launch_gate_grad(const void* dy, moe_dtype dy_dt, const void* yp, const float* yp_scale, moe_dtype dt,
+                     const int32_t* inv_perm, int T, int k, int d, float* d_topk_w, hipStream_t s) {
+  const dim3 grid(row_grid(T)), block(64 * kWavesPerBlock);
+#define MOE_GG_CASE(DD, DI, TD, TI)                                                                               \
+  if (dy_dt == DD && dt == DI) {                                                                                  \
+    gate_grad_kernel<TD, TI><<<grid, block, 0, s>>>((const TD*)dy, (const TI*)yp, yp_scale, inv_perm, T, k, d,    \
+                                                    d_topk_w);                                                    \
+    MOE_LAUNCH_CHECK();                                                                                           \
+    return MOE_OK;                                                                                                \
+  }
+  MOE_GG_CASE(MOE_F32, MOE_F32, float, float)
+  MOE_GG_CASE(MOE_BF16, MOE_BF16, bf16, bf16)
+  MOE_GG_CASE(MOE_BF16, MOE_F8E4M3, bf16, uint8_t)
+  MOE_GG_CASE(MOE_F32, MOE_F8E4M3, float, uint8_t)
+#undef MOE_GG_CASE
+  return MOE_ERR_UNSUPPORTED;
+}
+
+}  // namespace moe

@@ -1,0 +1,149 @@
+// E4M3 cast of activations and gradients (Section 5 "Communication compression for FP8 training":
+// E4M3 for all tensors, per-token quantisation forward, per-channel quantisation in groups of 128
+// tokens backward; Section 7 "FP8 training": per-token 1 x h scales).
+//
+// Scale rule (the paper gives none): amax = max|v| of the group; amax == 0 -> scale 1, codes 0;
+// else inv = 448/amax and scale = amax/448 (one fp32 division each), code = nearest-even e4m3 of
+// clamp(fp32(v)*inv, -448, 448).  The clamp comes first because the gfx950 converter turns
+// magnitudes of 465 and more into NaN instead of saturating.
+#include "moe_common.h"
+
+namespace moe {
+namespace {
+
+constexpr float kE4M3Max = 448.0f;
+
+__device__ __forceinline__ float clamp448(float p) { return fminf(fmaxf(p, -kE4M3Max), kE4M3Max); }
+
+// Four floats -> four packed codes (byte i = element i).
+__device__ __forceinline__ unsigned pack4_e4m3(float a, float b, float c, float d) {
+  int w = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a), clamp448(b), 0, false);
+  w = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(c), clamp448(d), w, true);
+  return (unsigned)w;
+}
+
+__device__ __forceinline__ float block_max_256(float v, float* red) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+  if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = v;
+  __syncthreads();
+  v = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  return v;
+}
+
+// One 256-thread block per row.
+template <typename T>
+__global__ void __launch_bounds__(256) quant_rows_kernel(const T* __restrict__ src, int rows, int cols,
+                                                         uint8_t* __restrict__ codes, float* __restrict__ scales) {
+  __shared__ float red[4];
+  constexpr int V = 16 / sizeof(T);
+  const int nvec = cols / V;
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    const T* row = src + (long)r * cols;
+    float amax = 0.f;
+    for (int c = threadIdx.x; c < nvec; c += 256) {
+      const Vec16<T> v = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
+#pragma unroll
+      for (int i = 0; i < V; ++i) amax = fmaxf(amax, fabsf(to_f32(v.v[i])));
+    }
+    amax = block_max_256(amax, red);
+    const float inv = amax > 0.f ? kE4M3Max / amax : 1.0f;
+    if (threadIdx.x == 0) scales[r] = amax > 0.f ? amax / kE4M3Max : 1.0f;
+    for (int c = threadIdx.x; c < nvec; c += 256) {
+      const Vec16<T> v = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
+      unsigned out[V / 4];
+#pragma unroll
+      for (int i = 0; i < V / 4; ++i)
+        out[i] = pack4_e4m3(to_f32(v.v[4 * i]) * inv, to_f32(v.v[4 * i + 1]) * inv, to_f32(v.v[4 * i + 2]) * inv,
+                            to_f32(v.v[4 * i + 3]) * inv);
+      unsigned* dst = reinterpret_cast<unsigned*>(codes + (long)r * cols + (long)c * V);
+#pragma unroll
+      for (int i = 0; i < V / 4; ++i) dst[i] = out[i];
+    }
+  }
+}
+
+// One block per (128-row group, slab of 256*4 columns); a thread owns 4 adjacent columns.
+template <typename T>
+__global__ void __launch_bounds__(256) quant_colgroup_kernel(const T* __restrict__ src, int rows, int cols,
+                                                             uint8_t* __restrict__ codes,
+                                                             float* __restrict__ scales, int slabs) {
+  const int g = blockIdx.x / slabs;
+  const int c = ((blockIdx.x % slabs) * 256 + threadIdx.x) * 4;
+  if (c >= cols) return;
+  const int r0 = g * 128, r1 = min(r0 + 128, rows);
+  float amax[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int r = r0; r < r1; ++r) {
+    const T* p = src + (long)r * cols + c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) amax[i] = fmaxf(amax[i], fabsf(to_f32(p[i])));
+  }
+  float inv[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    inv[i] = amax[i] > 0.f ? kE4M3Max / amax[i] : 1.0f;
+    scales[(long)g * cols + c + i] = amax[i] > 0.f ? amax[i] / kE4M3Max : 1.0f;
+  }
+  for (int r = r0; r < r1; ++r) {
+    const T* p = src + (long)r * cols + c;
+    *reinterpret_cast<unsigned*>(codes + (long)r * cols + c) =
+        pack4_e4m3(to_f32(p[0]) * inv[0], to_f32(p[1]) * inv[1], to_f32(p[2]) * inv[2], to_f32(p[3]) * inv[3]);
+  }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* __restrict__ codes,
+                                                      const float* __restrict__ scales, int rows, int cols, int mode,
+                                                      T* __restrict__ dst) {
+  const long nquad = (long)rows * cols / 4;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nquad; i += (long)gridDim.x * blockDim.x) {
+    const long el = i * 4;
+    const int r = (int)(el / cols);
+    const int c = (int)(el % cols);
+    const int w = *reinterpret_cast<const int*>(codes + el);
+    float s[4];
+    if (mode == MOE_Q_ROW) {
+      s[0] = s[1] = s[2] = s[3] = scales[r];
+    } else {
+      const float* sp = scales + (long)(r / 128) * cols + c;
+      s[0] = sp[0]; s[1] = sp[1]; s[2] = sp[2]; s[3] = sp[3];
+    }
+    dst[el + 0] = from_f32<T>(__builtin_amdgcn_cvt_f32_fp8(w, 0) * s[0]);
+    dst[el + 1] = from_f32<T>(__builtin_amdgcn_cvt_f32_fp8(w, 1) * s[1]);
+    dst[el + 2] = from_f32<T>(__builtin_amdgcn_cvt_f32_fp8(w, 2) * s[2]);
+    dst[el + 3] = from_f32<T>(__builtin_amdgcn_cvt_f32_fp8(w, 3) * s[3]);
+  }
+}
+
+}  // namespace
+
+int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmode mode, uint8_t* codes,
+                     float* scales, hipStream_t s) {
+  if (rows == 0 || cols == 0) return MOE_OK;
+  if (mode == MOE_Q_ROW) {
+    const int grid = rows < 256 * 16 ? rows : 256 * 16;
+    if (src_dt == MOE_F32) quant_rows_kernel<float><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales);
+    else quant_rows_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
+  } else {
+    const int slabs = cdiv(cols, 1024);
+    const int grid = cdiv(rows, 128) * slabs;
+    if (src_dt == MOE_F32) quant_colgroup_kernel<float><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales, slabs);
+    else quant_colgroup_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales, slabs);
+  }
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
+int launch_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols, moe_qmode mode, void* dst,
+                       moe_dtype dst_dt, hipStream_t s) {
+  if (rows == 0 || cols == 0) return MOE_OK;
+  long blocks = ((long)rows * cols / 4 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  if (dst_dt == MOE_F32) dequant_kernel<float><<<(int)blocks, 256, 0, s>>>(codes, scales, rows, cols, (int)mode, (float*)dst);
+  else dequant_kernel<bf16><<<(int)blocks, 256, 0, s>>>(codes, scales, rows, cols, (int)mode, (bf16*)dst);
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
+}  // namespace moe

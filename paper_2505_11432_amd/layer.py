@@ -1,0 +1,88 @@
+"""One MoE FFN layer on one GPU: buffers allocated once, then forward and backward as a fixed
+sequence of C-ABI calls (router -> route -> dispatch -> expert FFN -> combine, and the reverse).
+
+This is plumbing around the library: it owns device memory (torch tensors) and the call order,
+and does no arithmetic of its own.  Operator order follows Section 4.1 of the paper (Fig. 8a/8b).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class MoELayer:
+    def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype=torch.bfloat16, renorm: int = 1,
+                 fp8: bool = False, grad_dtype=torch.float32, device="cuda:0"):
+        self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
+        self.M = T * k
+        self.dtype, self.renorm, self.fp8, self.device = dtype, renorm, fp8, device
+        M = self.M
+        dev = dict(device=device)
+        i32 = dict(dtype=torch.int32, **dev)
+        f32 = dict(dtype=torch.float32, **dev)
+        act = dict(dtype=dtype, **dev)
+        self.logits = torch.empty((T, E), **f32)
+        self.topk_idx = torch.empty((T, k), **i32)
+        self.topk_w = torch.empty((T, k), **f32)
+        self.counts = torch.empty((E,), **i32)
+        self.offsets = torch.empty((E + 1,), **i32)
+        self.perm = torch.empty((M,), **i32)
+        self.inv_perm = torch.empty((M,), **i32)
+        self.h_save = torch.empty((M, 2 * f), **act)
+        self.y = torch.empty((T, d), **act)
+        self.d_yp = torch.empty((M, d), **act)
+        self.d_topk_w = torch.empty((T, k), **f32)
+        self.d_xp = torch.empty((M, d), **act)
+        self.dx = torch.empty((T, d), **act)
+        self.d_logits = torch.empty((T, E), **f32)
+        self.d_w_r = torch.empty((E, d), **f32)
+        self.d_w1 = torch.empty((E, 2 * f, d), dtype=grad_dtype, **dev)
+        self.d_w2 = torch.empty((E, d, f), dtype=grad_dtype, **dev)
+        if fp8:
+            u8 = dict(dtype=torch.uint8, **dev)
+            self.x_codes = torch.empty((T, d), **u8)
+            self.x_scale = torch.empty((T,), **f32)
+            self.xp = torch.empty((M, d), **u8)
+            self.xp_scale = torch.empty((M,), **f32)
+            self.yp = torch.empty((M, d), **u8)
+            self.yp_scale = torch.empty((M,), **f32)
+            self.xp_deq = torch.empty((M, d), **act)
+            self.a_deq = torch.empty((M, f), **act)
+            self.dy_codes = torch.empty((T, d), **u8)
+            self.dy_scale = torch.empty(((T + 127) // 128, d), **f32)
+            self.dy_deq = torch.empty((T, d), **act)
+        else:
+            self.xp = torch.empty((M, d), **act)
+            self.yp = torch.empty((M, d), **act)
+        code = B.F8E4M3 if fp8 else B.dtype_code(dtype)
+        nbytes = B.moe_workspace_bytes(T, d, E, k, f, code)
+        self.workspace = torch.empty((max(nbytes, 256),), dtype=torch.uint8, **dev)
+
+    # ---- forward: Fig. 8a ------------------------------------------------------------------
+    def forward(self, x, w_r, bias, w1, w2, logits=None):
+        """x [T,d]; w_r [E,d]; bias [E] fp32 or None; w1 [E,2f,d]; w2 [E,d,f].  `logits` overrides the
+        router matmul (used by the parity tests to feed both sides the same fp32 bits)."""
+        if logits is None:
+            B.moe_router_fwd(x, w_r, bias, self.logits)
+        else:
+            self.logits.copy_(logits)
+        B.moe_route(self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts, self.offsets,
+                    self.perm, self.inv_perm, self.workspace)
+        B.moe_dispatch(x, None, self.inv_perm, None, self.k, self.xp, None)
+        B.moe_expert_ffn_fwd(self.xp, None, self.offsets, w1, None, w2, None, self.h_save, self.yp, None,
+                             self.workspace)
+        B.moe_combine(self.yp, None, self.inv_perm, self.topk_w, self.k, self.y)
+        return self.y
+
+    # ---- backward: Fig. 8b -----------------------------------------------------------------
+    def backward(self, x, w_r, w1, w2, dy, with_router: bool = True):
+        B.moe_gate_grad(dy, self.yp, None, self.inv_perm, self.k, self.d_topk_w)
+        B.moe_dispatch(dy, None, self.inv_perm, self.topk_w.view(-1), self.k, self.d_yp, None)
+        B.moe_expert_ffn_bwd(self.xp, self.h_save, self.d_yp, None, self.offsets, w1, w2, self.d_xp, self.d_w1,
+                             self.d_w2, 0, self.workspace)
+        B.moe_combine(self.d_xp, None, self.inv_perm, None, self.k, self.dx)
+        B.moe_route_bwd(self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E, self.renorm, self.d_logits)
+        if with_router:
+            B.moe_router_bwd(x, w_r, self.d_logits, self.d_w_r, self.dx)
+        return self.dx

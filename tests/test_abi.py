@@ -1,0 +1,88 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+rejects bad arguments before touching the GPU.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2505_11432_amd", "libmoe_hip.so")
+HEADER = os.path.join(ROOT, "include", "moe.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2505_11432_amd.build import build
+        build(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = declared_symbols()
+    assert {"moe_route", "moe_dispatch", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_combine",
+            "moe_quant_fp8"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_covers_every_export(lib):
+    from paper_2505_11432_amd import binding
+    assert sorted(binding.EXPORTS) == declared_symbols()
+    assert binding.moe_abi_version() == 1
+
+
+def test_status_strings(lib):
+    lib.moe_status_string.restype = ctypes.c_char_p
+    assert lib.moe_status_string(0) == b"ok"
+    for s in (-1, -2, -3, -4):
+        assert len(lib.moe_status_string(s)) > 3
+
+
+def test_workspace_bytes(lib):
+    lib.moe_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.moe_workspace_bytes(256, 128, 8, 2, 256, 0) >= 512 * 4 * 256 * 4
+    assert lib.moe_workspace_bytes(8192, 4096, 8, 2, 14336, 1) >= 16384 * 4 * 14336 * 2
+    assert lib.moe_workspace_bytes(8, 128, 8, 9, 256, 1) == 0          # k > E
+    assert lib.moe_workspace_bytes(8, 128, 300, 2, 256, 1) == 0        # E too large
+    assert lib.moe_workspace_bytes(-1, 128, 8, 2, 256, 1) == 0
+
+
+def test_argument_errors_without_gpu(lib):
+    P = ctypes.c_void_p
+    null = P(0)
+    fake = P(4096)     # non-NULL, aligned; never dereferenced because validation fails first
+    # route: k > E, NULL logits, missing workspace
+    assert lib.moe_route(fake, 4, 8, 9, 1, fake, fake, fake, fake, fake, fake, fake, ctypes.c_size_t(1 << 20), null) == -1
+    assert lib.moe_route(null, 4, 8, 2, 1, fake, fake, fake, fake, fake, fake, fake, ctypes.c_size_t(1 << 20), null) == -1
+    assert lib.moe_route(fake, 4, 8, 2, 1, fake, fake, fake, fake, fake, fake, null, ctypes.c_size_t(0), null) == -3
+    assert lib.moe_route(fake, 4, 8, 2, 1, fake, fake, fake, fake, fake, fake, fake, ctypes.c_size_t(8), null) == -3
+    assert lib.moe_route(fake, 0, 8, 2, 1, null, null, null, null, null, null, null, ctypes.c_size_t(0), null) == 0
+    # dispatch: d not a multiple of 16, bad dtype, misaligned pointer, fp8 without scales
+    assert lib.moe_dispatch(fake, null, 1, fake, null, 4, 2, 24, fake, null, null) == -2
+    assert lib.moe_dispatch(fake, null, 7, fake, null, 4, 2, 32, fake, null, null) == -2
+    assert lib.moe_dispatch(P(4100), null, 1, fake, null, 4, 2, 32, fake, null, null) == -2
+    assert lib.moe_dispatch(fake, null, 2, fake, null, 4, 2, 32, fake, null, null) == -1
+    assert lib.moe_dispatch(null, null, 1, fake, null, 4, 2, 32, fake, null, null) == -1
+    assert lib.moe_dispatch(null, null, 1, null, null, 0, 2, 32, null, null, null) == 0
+    # combine: fp32 rows cannot be written as bf16; fp8 needs scales
+    assert lib.moe_combine(fake, null, 0, fake, null, 4, 2, 32, fake, 1, null) == -2
+    assert lib.moe_combine(fake, null, 2, fake, null, 4, 2, 32, fake, 1, null) == -1
+    # expert ffn: E out of range, f misaligned, workspace too small
+    Z = ctypes.c_size_t
+    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 0, 32, fake, fake, null, 1, fake, Z(1 << 30), null) == -1
+    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 4, 24, fake, fake, null, 1, fake, Z(1 << 30), null) == -2
+    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 4, 32, fake, fake, null, 1, fake, Z(16), null) == -3
+    assert lib.moe_expert_ffn_bwd(fake, fake, fake, null, fake, fake, fake, 1, 64, 32, 4, 32, fake, fake, fake, 0, 0, fake, Z(16), null) == -3
+    assert lib.moe_expert_ffn_bwd(fake, fake, fake, null, fake, fake, fake, 0, 64, 32, 4, 32, fake, fake, fake, 1, 0, fake, Z(1 << 30), null) == -2
+    # quant: bad mode, misaligned columns
+    assert lib.moe_quant_fp8(fake, 1, 4, 32, 5, fake, fake, null) == -1
+    assert lib.moe_quant_fp8(fake, 1, 4, 20, 0, fake, fake, null) == -2
+    assert lib.moe_quant_fp8(null, 1, 0, 32, 0, null, null, null) == 0

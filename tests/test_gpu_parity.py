@@ -1,0 +1,267 @@
+"""GPU parity: every call of the C ABI against the CPU oracle on the same seeded inputs.
+Integer results bit-exact; floats within 1e-4 (fp32), 2e-2 (bf16), 6e-2 (fp8) in the
+max-norm relative error (max|diff| / max|ref| per tensor)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from synth.moe_inputs import CONFIGS, MoEConfig, bf16_round, make_inputs, random_logits
+from tests.gpu_util import DEV, max_norm_err, to_dev, to_np, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2, "fp8": 6e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2505_11432_amd import binding
+    return binding
+
+
+def run_route(B, z, k, renorm=1):
+    T, E = z.shape
+    M = T * k
+    zt = to_dev(z)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    out = dict(idx=torch.full((T, k), -7, **i32), w=torch.full((T, k), -7.0, device=DEV),
+               counts=torch.full((E,), -7, **i32), offsets=torch.full((E + 1,), -7, **i32),
+               perm=torch.full((M,), -7, **i32), inv_perm=torch.full((M,), -7, **i32))
+    ws = torch.empty(max(B.moe_workspace_bytes(T, 16, E, k, 16, B.F32), 256), dtype=torch.uint8, device=DEV)
+    B.moe_route(zt, k, renorm, out["idx"], out["w"], out["counts"], out["offsets"], out["perm"], out["inv_perm"], ws)
+    torch.cuda.synchronize()
+    return out
+
+
+ROUTE_CASES = [
+    (256, 8, 2, None, 1), (1000, 8, 2, 0.5, 1), (777, 64, 8, None, 1), (513, 64, 8, 1.0, 1),
+    (300, 32, 4, 0.25, 1), (65, 5, 5, 1.0, 1), (129, 1, 1, None, 1), (4097, 16, 1, 2.0, 1),
+    (200, 256, 16, 0.5, 1), (333, 100, 7, None, 0), (64, 8, 2, None, 0), (1, 8, 3, None, 1),
+    (70000, 8, 2, 1.0, 1),
+]
+
+
+@pytest.mark.parametrize("T,E,k,quantum,renorm", ROUTE_CASES)
+def test_route_bit_exact(B, T, E, k, quantum, renorm):
+    z = random_logits(T, E, seed=T * 31 + E, quantum=quantum)
+    if T > 20:
+        z[3] = 0.75            # all-equal row
+        z[5, : E // 2] = -0.0  # signed zeros
+        z[5, E // 2:] = 0.0
+    ref = O.route(z, k, renorm)
+    got = run_route(B, z, k, renorm)
+    for name in ("idx", "counts", "offsets", "perm", "inv_perm"):
+        assert np.array_equal(to_np(got[name]), ref[name]), name
+    assert np.allclose(to_np(got["w"]), ref["w"], rtol=2e-6, atol=1e-7)
+
+
+def test_route_skewed_and_empty_experts(B):
+    cfg = CONFIGS["skewed"].with_tokens(4096)
+    inp = make_inputs(cfg, with_weights=False)
+    z = (O.router_logits(inp["x"], inp["W_r"], inp["bias"])).astype(np.float32)
+    z[:, 7] = -1e4
+    z[:, 20] = -1e4
+    ref = O.route(z, cfg.k)
+    assert ref["counts"][7] == 0 and ref["counts"][20] == 0
+    got = run_route(B, z, cfg.k)
+    for name in ("idx", "counts", "offsets", "perm", "inv_perm"):
+        assert np.array_equal(to_np(got[name]), ref[name]), name
+
+
+def test_route_is_deterministic(B):
+    z = random_logits(5000, 64, seed=2, quantum=0.5)
+    a = run_route(B, z, 8)
+    b = run_route(B, z, 8)
+    for name in a:
+        assert torch.equal(a[name], b[name]), name
+
+
+@pytest.mark.parametrize("renorm", [1, 0])
+def test_route_bwd(B, renorm):
+    T, E, k = 300, 16, 4
+    z = random_logits(T, E, seed=12)
+    ref = O.route(z, k, renorm)
+    rng = np.random.default_rng(0)
+    dw = rng.standard_normal((T, k)).astype(np.float32)
+    dz_ref = O.route_bwd(z, ref["idx"], ref["w"], dw, renorm)
+    dz = torch.full((T, E), 9.0, device=DEV)
+    B.moe_route_bwd(to_dev(z), to_dev(ref["idx"]), to_dev(ref["w"].astype(np.float32)), to_dev(dw), E, renorm, dz)
+    assert max_norm_err(to_np(dz), dz_ref) < 1e-5
+
+
+@pytest.mark.parametrize("dtype,T,d,E", [("f32", 100, 48, 8), ("bf16", 300, 256, 64), ("bf16", 64, 4096, 8)])
+def test_router_fwd_bwd(B, dtype, T, d, E):
+    cfg = MoEConfig("t", T=T, d=d, E=E, k=1, f=16, dtype=dtype, w_std=0.1, wr_std=0.1, bias="linear", bias_gamma=0.5)
+    inp = make_inputs(cfg, with_weights=False)
+    td = torch_dtype(dtype)
+    x = to_dev(inp["x"], td)
+    wr = to_dev(inp["W_r"].T, td)                 # library layout [E, d]
+    bias = to_dev(inp["bias"])
+    logits = torch.empty((T, E), device=DEV)
+    B.moe_router_fwd(x, wr, bias, logits)
+    ref = O.router_logits(inp["x"], inp["W_r"], inp["bias"])
+    assert max_norm_err(to_np(logits), ref) < 1e-5
+    rng = np.random.default_rng(1)
+    dz = rng.standard_normal((T, E)).astype(np.float32)
+    dx0 = bf16_round(rng.standard_normal((T, d)).astype(np.float32)) if dtype == "bf16" else rng.standard_normal((T, d)).astype(np.float32)
+    dwr = torch.empty((E, d), device=DEV)
+    dx = to_dev(dx0, td)
+    B.moe_router_bwd(x, wr, to_dev(dz), dwr, dx)
+    dW_ref, dx_ref = O.router_bwd(inp["x"], inp["W_r"], dz)
+    assert max_norm_err(to_np(dwr), dW_ref.T) < 1e-5
+    assert max_norm_err(to_np(dx), dx0 + dx_ref) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,T,d,E,k", [("f32", 37, 48, 4, 2), ("bf16", 500, 1040, 8, 3), ("bf16", 129, 4096, 64, 8),
+                                           ("bf16", 1, 16, 2, 1)])
+def test_dispatch_combine_gate_grad(B, dtype, T, d, E, k):
+    td = torch_dtype(dtype)
+    rnd = (lambda a: a) if dtype == "f32" else bf16_round
+    rng = np.random.default_rng(T)
+    x = rnd(rng.standard_normal((T, d)).astype(np.float32))
+    z = random_logits(T, E, seed=T)
+    r = O.route(z, k)
+    M = T * k
+    inv = to_dev(r["inv_perm"])
+    w32 = r["w"].astype(np.float32)
+    # dispatch (plain copy: exact)
+    xp = torch.full((M, d), 3.0, dtype=td, device=DEV)
+    B.moe_dispatch(to_dev(x, td), None, inv, None, k, xp, None)
+    assert np.array_equal(to_np(xp), O.dispatch(x, r["perm"], k))
+    # dispatch with row multiplier
+    B.moe_dispatch(to_dev(x, td), None, inv, to_dev(w32.reshape(-1)), k, xp, None)
+    assert max_norm_err(to_np(xp), O.dispatch(x, r["perm"], k, row_mul=w32)) < (1e-6 if dtype == "f32" else 4e-3)
+    # combine, weighted and unweighted
+    Y = rnd(rng.standard_normal((M, d)).astype(np.float32))
+    y = torch.empty((T, d), dtype=td, device=DEV)
+    B.moe_combine(to_dev(Y, td), None, inv, to_dev(w32), k, y)
+    assert max_norm_err(to_np(y), O.combine(Y, r["inv_perm"], w32, T, k)) < (1e-6 if dtype == "f32" else 4e-3)
+    B.moe_combine(to_dev(Y, td), None, inv, None, k, y)
+    assert max_norm_err(to_np(y), O.combine(Y, r["inv_perm"], None, T, k)) < (1e-6 if dtype == "f32" else 4e-3)
+    # permute then unpermute with weights 1/k is the identity when k is a power of two
+    if k & (k - 1) == 0:
+        B.moe_dispatch(to_dev(x, td), None, inv, None, k, xp, None)
+        B.moe_combine(xp, None, inv, torch.full((T, k), 1.0 / k, device=DEV), k, y)
+        assert np.array_equal(to_np(y), x.astype(np.float64))
+    # gate gradient
+    dy = rnd(rng.standard_normal((T, d)).astype(np.float32))
+    dw = torch.empty((T, k), device=DEV)
+    B.moe_gate_grad(to_dev(dy, td), to_dev(Y, td), None, inv, k, dw)
+    assert max_norm_err(to_np(dw), O.gate_grad(dy, Y, r["inv_perm"], T, k)) < 1e-5
+
+
+def run_layer(B, cfg, inp, z, grad_dtype=torch.float32, with_router=True):
+    from paper_2505_11432_amd.layer import MoELayer
+    td = torch_dtype(cfg.dtype)
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, renorm=cfg.renorm, grad_dtype=grad_dtype)
+    x, dy = to_dev(inp["x"], td), to_dev(inp["dy"], td)
+    wr = to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"], td), to_dev(inp["W2"], td)
+    layer.d_w1.fill_(7.0)
+    layer.d_w2.fill_(7.0)
+    layer.forward(x, wr, None, w1, w2, logits=to_dev(z))
+    layer.backward(x, wr, w1, w2, dy, with_router=with_router)
+    torch.cuda.synchronize()
+    return layer
+
+
+def check_layer(cfg, inp, z, layer, tol, with_router=True):
+    fwd = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k, cfg.renorm)
+    bwd = O.layer_bwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k, inp["dy"], fwd, cfg.renorm,
+                      W_r=inp["W_r"] if with_router else None)
+    for name, got in (("idx", layer.topk_idx), ("counts", layer.counts), ("offsets", layer.offsets),
+                      ("perm", layer.perm), ("inv_perm", layer.inv_perm)):
+        assert np.array_equal(to_np(got), fwd[name]), name
+    errs = {
+        "w": max_norm_err(to_np(layer.topk_w), fwd["w"]),
+        "xp": max_norm_err(to_np(layer.xp), fwd["xp"]),
+        "H": max_norm_err(to_np(layer.h_save), fwd["H"]),
+        "Y": max_norm_err(to_np(layer.yp), fwd["Y"]),
+        "y": max_norm_err(to_np(layer.y), fwd["y"]),
+        "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]),
+        "dxp": max_norm_err(to_np(layer.d_xp), bwd["dxp"]),
+        "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
+        "dz": max_norm_err(to_np(layer.d_logits), bwd["dz"]),
+    }
+    dW1, dW2 = to_np(layer.d_w1), to_np(layer.d_w2)
+    for e in range(cfg.E):
+        if fwd["counts"][e] == 0:
+            assert np.all(dW1[e] == 0) and np.all(dW2[e] == 0), f"empty expert {e} must get zero gradients"
+        else:
+            errs[f"dW1[{e}]"] = max_norm_err(dW1[e], bwd["dW1"][e])
+            errs[f"dW2[{e}]"] = max_norm_err(dW2[e], bwd["dW2"][e])
+    if with_router:
+        errs["dW_r"] = max_norm_err(to_np(layer.d_w_r), bwd["dW_r"].T)
+    bad = {k: v for k, v in errs.items() if not v < tol}
+    assert not bad, f"over tolerance {tol}: {bad}"
+    return errs
+
+
+def test_layer_tiny_fp32(B):
+    cfg = CONFIGS["tiny"]
+    inp = make_inputs(cfg, seed=0)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    layer = run_layer(B, cfg, inp, z)
+    check_layer(cfg, inp, z, layer, TOL["f32"])
+
+
+SMALL_BF16 = [
+    # ragged tails in every dimension, several tiles, one empty expert, one very small expert
+    MoEConfig("ragged", T=611, d=272, E=6, k=2, f=336, dtype="bf16", w_std=0.06, wr_std=0.5),
+    MoEConfig("fine", T=500, d=256, E=64, k=8, f=176, dtype="bf16", w_std=0.06, wr_std=0.1, bias="linear", bias_gamma=0.17),
+    MoEConfig("one_expert", T=300, d=128, E=1, k=1, f=256, dtype="bf16", w_std=0.08, wr_std=0.1),
+    MoEConfig("k_eq_E", T=130, d=128, E=4, k=4, f=128, dtype="bf16", w_std=0.08, wr_std=0.5),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL_BF16, ids=lambda c: c.name)
+def test_layer_small_bf16(B, cfg):
+    inp = make_inputs(cfg, seed=1)
+    z = O.router_logits(inp["x"], inp["W_r"], inp["bias"]).astype(np.float32)
+    if cfg.name == "ragged":
+        z[:, 4] = -1e4                  # expert 4 empty
+        z[:, 2] -= 4.0                  # expert 2 nearly empty
+    layer = run_layer(B, cfg, inp, z)
+    check_layer(cfg, inp, z, layer, TOL["bf16"])
+
+
+def test_layer_bf16_gradients_in_bf16_and_accumulate(B):
+    cfg = SMALL_BF16[0]
+    inp = make_inputs(cfg, seed=2)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    layer = run_layer(B, cfg, inp, z, grad_dtype=torch.bfloat16)
+    check_layer(cfg, inp, z, layer, TOL["bf16"])
+    # accumulate=1 adds into fp32 main gradients
+    layer = run_layer(B, cfg, inp, z)
+    g1 = layer.d_w1.clone()
+    g2 = layer.d_w2.clone()
+    td = torch.bfloat16
+    B.moe_expert_ffn_bwd(layer.xp, layer.h_save, layer.d_yp, None, layer.offsets, to_dev(inp["W1"], td),
+                         to_dev(inp["W2"], td), layer.d_xp, layer.d_w1, layer.d_w2, 1, layer.workspace)
+    torch.cuda.synchronize()
+    assert max_norm_err(to_np(layer.d_w1), 2 * to_np(g1)) < 1e-5
+    assert max_norm_err(to_np(layer.d_w2), 2 * to_np(g2)) < 1e-5
+
+
+@pytest.mark.parametrize("src_dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,cols", [(300, 272), (1, 16), (129, 4096), (257, 14336)])
+def test_quant_fp8_bit_exact(B, src_dtype, rows, cols):
+    rng = np.random.default_rng(rows + cols)
+    v = (rng.standard_normal((rows, cols)) * np.exp(rng.uniform(-4, 4, (rows, 1)))).astype(np.float32)
+    if rows > 2:
+        v[2] = 0.0
+    if src_dtype == "bf16":
+        v = bf16_round(v)
+    td = torch_dtype(src_dtype)
+    src = to_dev(v, td)
+    for mode, qf, dq in ((B.Q_ROW, O.quant_rows, O.dequant_rows), (B.Q_COLGROUP128, O.quant_colgroup128, O.dequant_colgroup128)):
+        c_ref, s_ref = qf(v)
+        codes = torch.full((rows, cols), 0x55, dtype=torch.uint8, device=DEV)
+        scales = torch.full(s_ref.shape, -1.0, device=DEV)
+        B.moe_quant_fp8(src, mode, codes, scales)
+        assert np.array_equal(to_np(scales).astype(np.float32), s_ref), mode
+        assert np.array_equal(to_np(codes), c_ref), mode
+        out = torch.empty((rows, cols), dtype=torch.float32, device=DEV)
+        B.moe_dequant_fp8(codes, scales, mode, out)
+        assert np.array_equal(to_np(out), dq(c_ref, s_ref).astype(np.float32).astype(np.float64)), mode
