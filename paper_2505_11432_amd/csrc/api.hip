@@ -53,6 +53,31 @@ static int ffn_fwd_plain(const void* xp, const int32_t* offsets, const void* w1,
   return launch_gemm_generic(g, dt, dt, dt, s);
 }
 
+// bf16: every GEMM on the matrix cores, SwiGLU and its derivative fused into the FC1 / dgrad2 epilogues.
+static int ffn_fwd_bf16(const void* xp, const int32_t* offsets, const void* w1, const void* w2, int M, int d, int E,
+                        int f, void* h_save, void* yp, void* ws, hipStream_t s) {
+  void* A = ws;
+  int rc = mfma_fc1_swiglu(xp, w1, offsets, M, d, E, f, h_save, A, s);
+  if (rc != MOE_OK) return rc;
+  return mfma_rowseg_nt(A, w2, (long)d * f, offsets, M, d, f, E, yp, s);
+}
+
+static int ffn_bwd_bf16(const void* xp, const void* h_save, const void* d_yp, const void* a_override,
+                        const int32_t* offsets, const void* w1, const void* w2, int M, int d, int E, int f,
+                        void* d_xp, void* d_w1, void* d_w2, moe_dtype grad_dt, int accumulate, void* ws,
+                        hipStream_t s) {
+  char* base = static_cast<char*>(ws);
+  void* A = base;
+  void* dH = base + 2 * align_up((size_t)M * f * 2, 256);
+  int rc = mfma_dgrad2_swiglu_bwd(d_yp, w2, offsets, M, d, E, f, h_save, dH, a_override ? nullptr : A, s);
+  if (rc != MOE_OK) return rc;
+  rc = mfma_wgrad(d_yp, a_override ? a_override : A, offsets, d, f, E, d_w2, grad_dt, accumulate, s);
+  if (rc != MOE_OK) return rc;
+  rc = mfma_rowseg_nn(dH, w1, 2L * f * d, offsets, M, d, 2 * f, E, d_xp, s);
+  if (rc != MOE_OK) return rc;
+  return mfma_wgrad(dH, xp, offsets, 2 * f, d, E, d_w1, grad_dt, accumulate, s);
+}
+
 static int ffn_bwd_plain(const void* xp, const void* h_save, const void* d_yp, const void* a_override,
                          const int32_t* offsets, const void* w1, const void* w2, moe_dtype dt, int M, int d, int E,
                          int f, void* d_xp, void* d_w1, void* d_w2, moe_dtype grad_dt, int accumulate, void* ws,
@@ -262,6 +287,8 @@ int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt, 
     return MOE_ERR_UNSUPPORTED;
   if (!workspace || ws_bytes < ffn_fwd_ws_bytes(M, d, f, act_dt, out_dt)) return MOE_ERR_WORKSPACE;
   if (fp8) return MOE_ERR_UNSUPPORTED;
+  if (act_dt == MOE_BF16)
+    return ffn_fwd_bf16(xp, offsets, w1, w2, M, d, E, f, h_save, yp, workspace, as_stream(stream));
   return ffn_fwd_plain(xp, offsets, w1, w2, act_dt, M, d, E, f, h_save, yp, workspace, as_stream(stream));
 }
 
@@ -280,6 +307,9 @@ int moe_expert_ffn_bwd(const void* xp, const void* h_save, const void* d_yp, con
       !aligned16(d_xp) || !aligned16(d_w1) || !aligned16(d_w2) || !aligned16(a_override) || !aligned16(workspace))
     return MOE_ERR_UNSUPPORTED;
   if (M > 0 && (!workspace || ws_bytes < ffn_bwd_ws_bytes(M, d, f, dt))) return MOE_ERR_WORKSPACE;
+  if (dt == MOE_BF16)
+    return ffn_bwd_bf16(xp, h_save, d_yp, a_override, offsets, w1, w2, M, d, E, f, d_xp, d_w1, d_w2, grad_dt,
+                        accumulate != 0, workspace, as_stream(stream));
   return ffn_bwd_plain(xp, h_save, d_yp, a_override, offsets, w1, w2, dt, M, d, E, f, d_xp, d_w1, d_w2, grad_dt,
                        accumulate != 0, workspace, as_stream(stream));
 }

@@ -1,0 +1,87 @@
+// Launchers of the grouped MFMA GEMM template for the bf16 expert FFN (Section 4.1: FC1 -> SwiGLU
+// -> FC2 and the backward of each).  Tile shapes were picked by measurement on MI355X.
+#include "gemm_mfma.h"
+
+namespace moe {
+namespace {
+
+using namespace mfma;
+
+template <int BM, int BN, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC>
+int launch(const Args& a, long blocks, hipStream_t s) {
+  if (blocks <= 0) return MOE_OK;
+  if (blocks > 0x7fffffffL) return MOE_ERR_UNSUPPORTED;
+  auto kern = grouped_gemm_kernel<BM, BN, WM, WN, LA, LB, MODE, EPI, TC>;
+  constexpr int smem = smem_bytes<BM, BN, LA, LB>();
+  static bool configured = false;    // one flag per instantiation; the attribute is per function
+  if (!configured) {
+    MOE_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+    configured = true;
+  }
+  kern<<<dim3((unsigned)blocks), dim3(WM * WN * 64), smem, s>>>(a);
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
+long rowseg_blocks(int M, int E, int N, int bm, int bn_out) {
+  return (long)cdiv(N, bn_out) * (cdiv(M, bm) + E);
+}
+
+}  // namespace
+
+// H[M,2f] = xp * w1[e]^T, A_out = SwiGLU(H)
+int mfma_fc1_swiglu(const void* xp, const void* w1, const int32_t* offsets, int M, int d, int E, int f, void* H,
+                    void* A_out, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)xp; a.lda = d;
+  a.B = (const bf16*)w1; a.ldb = d; a.b_es = 2L * f * d;
+  a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d; a.f = f;
+  a.H = (bf16*)H; a.A_out = (bf16*)A_out;
+  return launch<256, 256, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_SWIGLU, bf16>(a, rowseg_blocks(M, E, f, 256, 128), s);
+}
+
+// C[M,N] = A[M,K] * W[e]^T with W[e] = [N,K]
+int mfma_rowseg_nt(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
+                   void* C, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)A; a.lda = K;
+  a.B = (const bf16*)W; a.ldb = K; a.b_es = w_es;
+  a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
+  return launch<256, 256, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
+}
+
+// C[M,N] = A[M,K] * W[e] with W[e] = [K,N]
+int mfma_rowseg_nn(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
+                   void* C, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)A; a.lda = K;
+  a.B = (const bf16*)W; a.ldb = N; a.b_es = w_es;
+  a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
+  return launch<256, 256, 2, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
+}
+
+// dA = d_yp * w2[e] fused with the SwiGLU derivative: reads H=[G|U], writes dH=[dG|dU] and (optionally) A
+int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offsets, int M, int d, int E, int f,
+                           const void* H, void* dH, void* A_out, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)d_yp; a.lda = d;
+  a.B = (const bf16*)w2; a.ldb = f; a.b_es = (long)d * f;
+  a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d;
+  a.H = (bf16*)const_cast<void*>(H); a.dH = (bf16*)dH; a.A_out = (bf16*)A_out;
+  return launch<256, 256, 2, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_SWIGLU_BWD, bf16>(a, rowseg_blocks(M, E, f, 256, 256), s);
+}
+
+// C[e][Mo,N] (+)= P[rows_e, Mo]^T * Q[rows_e, N]
+int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int N, int E, void* C, moe_dtype c_dt,
+               int accumulate, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)P; a.lda = Mo;
+  a.B = (const bf16*)Q; a.ldb = N; a.b_es = 0;
+  a.C = C; a.ldc = N; a.c_es = (long)Mo * N; a.offsets = offsets; a.E = E; a.M = Mo; a.N = N; a.K = 0;
+  a.accumulate = accumulate;
+  const long blocks = (long)E * cdiv(Mo, 256) * cdiv(N, 256);
+  if (c_dt == MOE_F32) return launch<256, 256, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, float>(a, blocks, s);
+  return launch<256, 256, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, bf16>(a, blocks, s);
+}
+
+}  // namespace moe

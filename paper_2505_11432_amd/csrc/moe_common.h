@@ -81,6 +81,18 @@ int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_
 int launch_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols, moe_qmode mode, void* dst,
                        moe_dtype dst_dt, hipStream_t s);
 
+// bf16 grouped GEMMs on the matrix cores (gemm_mfma.hip)
+int mfma_fc1_swiglu(const void* xp, const void* w1, const int32_t* offsets, int M, int d, int E, int f, void* H,
+                    void* A_out, hipStream_t s);
+int mfma_rowseg_nt(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
+                   void* C, hipStream_t s);
+int mfma_rowseg_nn(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
+                   void* C, hipStream_t s);
+int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offsets, int M, int d, int E, int f,
+                           const void* H, void* dH, void* A_out, hipStream_t s);
+int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int N, int E, void* C, moe_dtype c_dt,
+               int accumulate, hipStream_t s);
+
 int launch_swiglu_fwd(const void* H, void* A, int M, int f, const int32_t* row_limit, moe_dtype dt, hipStream_t s);
 int launch_swiglu_bwd(const void* H, const void* dA, void* dH, int M, int f, const int32_t* row_limit,
                       moe_dtype dt, hipStream_t s);
