@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+A "step" is one forward + backward pass of the whole path (router matmul, gating, dispatch, expert
+grouped GEMMs with SwiGLU, combine, and every gradient) over one batch of seeded synthetic input
+of the Mixtral-8x7B layer shape (T=8192, d=4096, E=8, top-2, d_ff=14336, bf16).  Inputs and weights
+are resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="mixtral", help="synthetic workload name (see synth/moe_inputs.py)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = T/8)")
+    return ap.parse_args()
+
+
+def ensure_built():
+    lib = os.path.join(ROOT, "paper_2505_11432_amd", "libmoe_hip.so")
+    if not os.path.exists(lib):
+        from paper_2505_11432_amd.build import build
+        build(verbose=False)
+
+
+def to_dev_bf16(a, torch):
+    import numpy as np
+    from synth.moe_inputs import bf16_bits
+    bits = bf16_bits(a).view(np.int16)
+    return torch.from_numpy(bits).to("cuda:0").view(torch.bfloat16)
+
+
+def cpu_baseline(cfg, inp, tokens):
+    """The oracle as it stands, timed on the host cores on the first `tokens` tokens."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import moe_oracle as O
+    x = inp["x"][:tokens]
+    dy = inp["dy"][:tokens]
+    t0 = time.perf_counter()
+    z = O.router_logits(x, inp["W_r"], inp["bias"]).astype(np.float32)
+    fwd = O.layer_fwd(x, z, inp["W1"], inp["W2"], cfg.k, cfg.renorm)
+    O.layer_bwd(x, z, inp["W1"], inp["W2"], cfg.k, dy, fwd, cfg.renorm, W_r=inp["W_r"])
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {tokens} of {cfg.T} tokens, all {cfg.E} experts and full d, d_ff; "
+                      f"numpy float64 forward+backward, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported.", file=sys.stderr)
+        sys.exit(2)
+    ensure_built()
+    import numpy as np
+    import torch
+    from paper_2505_11432_amd import binding as B          # fails loudly if the HIP library is missing
+    from paper_2505_11432_amd.layer import MoELayer
+    from synth.moe_inputs import CONFIGS, make_inputs
+
+    cfg = CONFIGS[args.config]
+    assert cfg.dtype == "bf16", "the benchmark workload is a bf16 configuration"
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    inp = make_inputs(cfg, seed=0)
+    x, dy = to_dev_bf16(inp["x"], torch), to_dev_bf16(inp["dy"], torch)
+    w_r = to_dev_bf16(np.ascontiguousarray(inp["W_r"].T), torch)
+    bias = torch.from_numpy(inp["bias"]).to("cuda:0") if cfg.bias != "none" else None
+    w1, w2 = to_dev_bf16(inp["W1"], torch), to_dev_bf16(inp["W2"], torch)
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step():
+        layer.forward(x, w_r, bias, w1, w2)
+        layer.backward(x, w_r, w1, w2, dy)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    layer.timers = {}
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(args.steps):
+        step()
+    end.record()
+    torch.cuda.synchronize()
+    total_ms = start.elapsed_time(end)
+    per_call = {k: v / args.steps for k, v in layer.timer_ms().items()}
+    layer.timers = None
+    ms_per_step = total_ms / args.steps
+
+    M = cfg.M
+    gemm_flops = 18.0 * M * cfg.d * cfg.f                      # three matmuls per routed token, fwd + 2x bwd
+    gemm_ms = per_call["expert_ffn_fwd"] + per_call["expert_ffn_bwd"]   # exactly the six GEMM launches
+    gemm_tflops = gemm_flops / gemm_ms / 1e9
+    row_bytes = (cfg.T + M) * cfg.d * 2.0
+    counts = layer.counts.cpu().tolist()
+
+    out = {
+        "metric": "MoE layer fwd+bwd tokens/s; grouped-GEMM TFLOPS as % of MI355X MFMA peak",
+        "value": cfg.T / (ms_per_step / 1e3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d} E={cfg.E} top-{cfg.k} d_ff={cfg.f} "
+                               "SwiGLU, bf16 weights/activations, fp32 accumulate, fp32 weight gradients",
+                   "tokens": cfg.T, "expert_rows": counts},
+        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
+                                                "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",
+                     "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "flops_per_launch_avg": gemm_flops / 6, "launch_ms_avg": gemm_ms / 6},
+        "gemm_tflops": {"fwd": 6.0 * M * cfg.d * cfg.f / per_call["expert_ffn_fwd"] / 1e9,
+                        "bwd": 12.0 * M * cfg.d * cfg.f / per_call["expert_ffn_bwd"] / 1e9},
+        "hbm_gbps": {"dispatch": row_bytes / per_call["dispatch"] / 1e6,
+                     "combine": row_bytes / per_call["combine"] / 1e6,
+                     "peak": PEAK_HBM_GBPS},
+        "ms_per_call": per_call,
+        "setup_s": setup_s,
+    }
+    if not args.no_cpu_baseline:
+        tokens = args.cpu_tokens or max(cfg.T // 8, 1)
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

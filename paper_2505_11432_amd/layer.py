@@ -55,34 +55,56 @@ class MoELayer:
         else:
             self.xp = torch.empty((M, d), **act)
             self.yp = torch.empty((M, d), **act)
+        self.timers = None      # set to a dict to collect (start, end) event pairs per call name
         code = B.F8E4M3 if fp8 else B.dtype_code(dtype)
         nbytes = B.moe_workspace_bytes(T, d, E, k, f, code)
         self.workspace = torch.empty((max(nbytes, 256),), dtype=torch.uint8, **dev)
+
+    def _call(self, name, fn, *args):
+        """Run one C-ABI call; with timers enabled, bracket it with events on the current stream."""
+        if self.timers is None:
+            fn(*args)
+            return
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn(*args)
+        e1.record()
+        self.timers.setdefault(name, []).append((e0, e1))
+
+    def timer_ms(self) -> dict:
+        """Total milliseconds per call name over everything recorded so far (synchronises)."""
+        torch.cuda.synchronize()
+        return {k: sum(a.elapsed_time(b) for a, b in v) for k, v in (self.timers or {}).items()}
 
     # ---- forward: Fig. 8a ------------------------------------------------------------------
     def forward(self, x, w_r, bias, w1, w2, logits=None):
         """x [T,d]; w_r [E,d]; bias [E] fp32 or None; w1 [E,2f,d]; w2 [E,d,f].  `logits` overrides the
         router matmul (used by the parity tests to feed both sides the same fp32 bits)."""
+        c = self._call
         if logits is None:
-            B.moe_router_fwd(x, w_r, bias, self.logits)
+            c("router_fwd", B.moe_router_fwd, x, w_r, bias, self.logits)
         else:
             self.logits.copy_(logits)
-        B.moe_route(self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts, self.offsets,
-                    self.perm, self.inv_perm, self.workspace)
-        B.moe_dispatch(x, None, self.inv_perm, None, self.k, self.xp, None)
-        B.moe_expert_ffn_fwd(self.xp, None, self.offsets, w1, None, w2, None, self.h_save, self.yp, None,
-                             self.workspace)
-        B.moe_combine(self.yp, None, self.inv_perm, self.topk_w, self.k, self.y)
+        c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
+          self.offsets, self.perm, self.inv_perm, self.workspace)
+        c("dispatch", B.moe_dispatch, x, None, self.inv_perm, None, self.k, self.xp, None)
+        c("expert_ffn_fwd", B.moe_expert_ffn_fwd, self.xp, None, self.offsets, w1, None, w2, None, self.h_save,
+          self.yp, None, self.workspace)
+        c("combine", B.moe_combine, self.yp, None, self.inv_perm, self.topk_w, self.k, self.y)
         return self.y
 
     # ---- backward: Fig. 8b -----------------------------------------------------------------
     def backward(self, x, w_r, w1, w2, dy, with_router: bool = True):
-        B.moe_gate_grad(dy, self.yp, None, self.inv_perm, self.k, self.d_topk_w)
-        B.moe_dispatch(dy, None, self.inv_perm, self.topk_w.view(-1), self.k, self.d_yp, None)
-        B.moe_expert_ffn_bwd(self.xp, self.h_save, self.d_yp, None, self.offsets, w1, w2, self.d_xp, self.d_w1,
-                             self.d_w2, 0, self.workspace)
-        B.moe_combine(self.d_xp, None, self.inv_perm, None, self.k, self.dx)
-        B.moe_route_bwd(self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E, self.renorm, self.d_logits)
+        c = self._call
+        c("gate_grad", B.moe_gate_grad, dy, self.yp, None, self.inv_perm, self.k, self.d_topk_w)
+        c("dispatch_bwd_of_combine", B.moe_dispatch, dy, None, self.inv_perm, self.topk_w.view(-1), self.k,
+          self.d_yp, None)
+        c("expert_ffn_bwd", B.moe_expert_ffn_bwd, self.xp, self.h_save, self.d_yp, None, self.offsets, w1, w2,
+          self.d_xp, self.d_w1, self.d_w2, 0, self.workspace)
+        c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, None, self.k, self.dx)
+        c("route_bwd", B.moe_route_bwd, self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E,
+          self.renorm, self.d_logits)
         if with_router:
-            B.moe_router_bwd(x, w_r, self.d_logits, self.d_w_r, self.dx)
+            c("router_bwd", B.moe_router_bwd, x, w_r, self.d_logits, self.d_w_r, self.dx)
         return self.dx

@@ -5,7 +5,8 @@ holds none of the layer's arithmetic: no gating, no permutation, no matmul of th
 expert path.  Both the CPU oracle's tests and the HIP path's tests/bench feed on
 the arrays made here, so the two sides always see the same bytes.
 
-Recipe (one PCG64 stream per tensor, keyed by (seed, tensor_id)):
+Recipe (one PCG64 stream per tensor, keyed by (seed, tensor_id); the expert weights use one
+stream per expert, keyed by (seed, tensor_id, expert), so they can be drawn in parallel):
   tensor_id: x=0, W_r=1, W_g=2, W_u=3, W_d=4, dy=5, router-bias permutation=6
   draw float32 standard normals, multiply by the std, round once to the storage
   type (bf16 round-to-nearest-even, or keep fp32).
@@ -14,6 +15,7 @@ Weights are laid out "out, in":  W1 = [W_g ; W_u] as [E, 2f, d],  W2 = W_d as [E
 from __future__ import annotations
 
 import math
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, replace
 
 import numpy as np
@@ -84,12 +86,17 @@ def bf16_from_bits(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def _normal(seed: int, tensor_id: int, shape, std: float, storage: str) -> np.ndarray:
-    rng = np.random.Generator(np.random.PCG64([seed, tensor_id]))
+def _normal(key, shape, std: float, storage: str, out=None) -> np.ndarray:
+    rng = np.random.Generator(np.random.PCG64(list(key)))
     a = rng.standard_normal(size=shape, dtype=np.float32)
     if std != 1.0:
         a *= np.float32(std)
-    return bf16_round(a) if storage != "f32" else a
+    if storage != "f32":
+        a = bf16_round(a)
+    if out is not None:
+        out[...] = a
+        return out
+    return a
 
 
 def router_bias(cfg: MoEConfig, seed: int = 0) -> np.ndarray:
@@ -111,17 +118,22 @@ def make_inputs(cfg: MoEConfig, seed: int = 0, with_weights: bool = True) -> dic
     """All tensors of one layer as float32 numpy arrays holding storage-rounded values."""
     st = "f32" if cfg.dtype == "f32" else "bf16"
     out = {
-        "x": _normal(seed, TENSOR_IDS["x"], (cfg.T, cfg.d), 1.0, st),
-        "dy": _normal(seed, TENSOR_IDS["dy"], (cfg.T, cfg.d), 1.0, st),
-        "W_r": _normal(seed, TENSOR_IDS["W_r"], (cfg.d, cfg.E), cfg.wr_std, st),
+        "x": _normal((seed, TENSOR_IDS["x"]), (cfg.T, cfg.d), 1.0, st),
+        "dy": _normal((seed, TENSOR_IDS["dy"]), (cfg.T, cfg.d), 1.0, st),
+        "W_r": _normal((seed, TENSOR_IDS["W_r"]), (cfg.d, cfg.E), cfg.wr_std, st),
         "bias": router_bias(cfg, seed),
     }
     if with_weights:
         w1 = np.empty((cfg.E, 2 * cfg.f, cfg.d), dtype=np.float32)
-        w1[:, :cfg.f, :] = _normal(seed, TENSOR_IDS["W_g"], (cfg.E, cfg.f, cfg.d), cfg.w_std, st)
-        w1[:, cfg.f:, :] = _normal(seed, TENSOR_IDS["W_u"], (cfg.E, cfg.f, cfg.d), cfg.w_std, st)
-        out["W1"] = w1
-        out["W2"] = _normal(seed, TENSOR_IDS["W_d"], (cfg.E, cfg.d, cfg.f), cfg.w_std, st)
+        w2 = np.empty((cfg.E, cfg.d, cfg.f), dtype=np.float32)
+        jobs = []
+        for e in range(cfg.E):
+            jobs.append(((seed, TENSOR_IDS["W_g"], e), (cfg.f, cfg.d), w1[e, :cfg.f, :]))
+            jobs.append(((seed, TENSOR_IDS["W_u"], e), (cfg.f, cfg.d), w1[e, cfg.f:, :]))
+            jobs.append(((seed, TENSOR_IDS["W_d"], e), (cfg.d, cfg.f), w2[e]))
+        with ThreadPoolExecutor(max_workers=8) as pool:
+            list(pool.map(lambda j: _normal(j[0], j[1], cfg.w_std, st, out=j[2]), jobs))
+        out["W1"], out["W2"] = w1, w2
     return out
 
 
