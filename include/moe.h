@@ -66,10 +66,12 @@ int moe_router_fwd(const void* x, const void* w_r, const float* bias, moe_dtype 
                    int T, int d, int E, float* logits /*[T,E]*/, void* stream);
 
 /* Gradients of moe_router_fwd: d_w_r[e,i] = sum_t d_logits[t,e] * x[t,i] (fp32 [E,d],
- * overwritten) and dx[t,i] += sum_e d_logits[t,e] * w_r[e,i] (dx [T,d] in `dt`, read and
- * written).  d_w_r or dx may be NULL to skip that half. */
+ * overwritten; summed in a fixed order, so reproducible) and dx[t,i] += sum_e d_logits[t,e]
+ * * w_r[e,i] (dx [T,d] in `dt`, read and written).  d_w_r or dx may be NULL to skip that
+ * half.  d_w_r needs workspace. */
 int moe_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt,
-                   int T, int d, int E, float* d_w_r, void* dx, void* stream);
+                   int T, int d, int E, float* d_w_r, void* dx,
+                   void* workspace, size_t ws_bytes, void* stream);
 
 /* ---- gating and row map (Section 2.1: top-k gate; Section 3.2 "Efficient operators":
  * the pre-computed mapping from input rows to output rows; Section 4.2: rows ordered by

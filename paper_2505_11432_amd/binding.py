@@ -47,7 +47,7 @@ def _load() -> ctypes.CDLL:
         "moe_status_string": (c_char_p, [I]),
         "moe_workspace_bytes": (Z, [I, I, I, I, I, I]),
         "moe_router_fwd": (I, [P, P, P, I, I, I, I, P, P]),
-        "moe_router_bwd": (I, [P, P, P, I, I, I, I, P, P, P]),
+        "moe_router_bwd": (I, [P, P, P, I, I, I, I, P, P, P, Z, P]),
         "moe_route": (I, [P, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
         "moe_route_bwd": (I, [P, P, P, P, I, I, I, I, P, P]),
         "moe_dispatch": (I, [P, P, I, P, P, I, I, I, P, P, P]),
@@ -110,11 +110,12 @@ def moe_router_fwd(x, w_r, bias, logits):
                                                  _p(logits), _stream()))
 
 
-def moe_router_bwd(x, w_r, d_logits, d_w_r, dx):
+def moe_router_bwd(x, w_r, d_logits, d_w_r, dx, workspace):
     T, d = x.shape
     E = w_r.shape[0]
     _check("moe_router_bwd", _lib.moe_router_bwd(_p(x), _p(w_r), _p(d_logits), dtype_code(x.dtype), T, d, E,
-                                                 _p(d_w_r), _p(dx), _stream()))
+                                                 _p(d_w_r), _p(dx), _p(workspace),
+                                                 workspace.numel() * workspace.element_size(), _stream()))
 
 
 def moe_route(logits, k, renorm, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace):

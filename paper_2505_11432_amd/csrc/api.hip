@@ -153,6 +153,8 @@ size_t moe_workspace_bytes(int T, int d, int E, int k, int f, moe_dtype act) {
   const int M = T * k;
   const moe_dtype bwd_dt = act == MOE_F32 ? MOE_F32 : MOE_BF16;
   size_t b = route_ws_bytes(T, E);
+  const size_t rb = router_bwd_ws_bytes(T, d, E);
+  if (rb > b) b = rb;
   const size_t fw = ffn_fwd_ws_bytes(M, d, f, act, act);
   const size_t bw = ffn_bwd_ws_bytes(M, d, f, bwd_dt);
   if (fw > b) b = fw;
@@ -166,6 +168,8 @@ int moe_router_fwd(const void* x, const void* w_r, const float* bias, moe_dtype 
   if (T == 0) return MOE_OK;
   if (!x || !w_r || !logits) return MOE_ERR_INVALID;
   if (dt != MOE_F32 && dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (dt == MOE_BF16 && d % 8 == 0 && aligned16(x) && aligned16(w_r))
+    return mfma_router_fwd(x, w_r, bias, T, d, E, logits, as_stream(stream));
   GemmProblem g{};
   g.mode = 2; g.E = 1; g.offsets = nullptr; g.accumulate = 0; g.bias = bias;
   g.A = x; g.a_rs = d; g.a_cs = 1;
@@ -175,31 +179,16 @@ int moe_router_fwd(const void* x, const void* w_r, const float* bias, moe_dtype 
 }
 
 int moe_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt, int T, int d, int E,
-                   float* d_w_r, void* dx, void* stream) {
+                   float* d_w_r, void* dx, void* workspace, size_t ws_bytes, void* stream) {
   if (T < 0 || d <= 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
   if (dt != MOE_F32 && dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (d % 16 != 0) return MOE_ERR_UNSUPPORTED;
   if (!d_logits && T > 0) return MOE_ERR_INVALID;
-  if ((d_w_r && !x) || (dx && !w_r)) return MOE_ERR_INVALID;
-  hipStream_t s = as_stream(stream);
-  GemmProblem g{};
-  g.mode = 2; g.E = 1; g.offsets = nullptr; g.bias = nullptr;
-  if (d_w_r) {
-    // d_w_r[E,d] = d_logits^T * x   (contraction over tokens; T = 0 writes zeros)
-    g.accumulate = 0;
-    g.A = d_logits; g.a_rs = 1; g.a_cs = E;
-    g.B = x; g.b_es = 0; g.b_rs = d; g.b_cs = 1;
-    g.C = d_w_r; g.c_es = 0; g.ldc = d; g.M = E; g.N = d; g.K = T;
-    const int rc = launch_gemm_generic(g, MOE_F32, dt, MOE_F32, s);
-    if (rc != MOE_OK) return rc;
-  }
-  if (dx && T > 0) {
-    g.accumulate = 1;
-    g.A = d_logits; g.a_rs = E; g.a_cs = 1;
-    g.B = w_r; g.b_es = 0; g.b_rs = d; g.b_cs = 1;
-    g.C = dx; g.c_es = 0; g.ldc = d; g.M = T; g.N = d; g.K = E;
-    return launch_gemm_generic(g, MOE_F32, dt, dt, s);
-  }
-  return MOE_OK;
+  if ((d_w_r && !x && T > 0) || (dx && !w_r)) return MOE_ERR_INVALID;
+  if (!aligned16(x) || !aligned16(w_r) || !aligned16(dx) || !aligned16(d_w_r) || !aligned16(workspace))
+    return MOE_ERR_UNSUPPORTED;
+  if (d_w_r && (!workspace || ws_bytes < router_bwd_ws_bytes(T, d, E))) return MOE_ERR_WORKSPACE;
+  return launch_router_bwd(x, w_r, d_logits, dt, T, d, E, d_w_r, dx, workspace, as_stream(stream));
 }
 
 int moe_route(const float* logits, int T, int E, int k, int renorm, int32_t* topk_idx, float* topk_w,

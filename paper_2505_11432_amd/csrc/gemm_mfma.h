@@ -28,8 +28,8 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 enum Layout { KMAJOR = 0, MNMAJOR = 1 };
-enum Mode { ROWSEG = 0, KSEG = 1 };
-enum Epi { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SWIGLU_BWD = 2 };
+enum Mode { ROWSEG = 0, KSEG = 1, PLAIN = 2 };   // PLAIN: one dense GEMM, no expert segments
+enum Epi { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SWIGLU_BWD = 2, EPI_BIAS_F32 = 3 };
 
 constexpr int BK = 64;
 constexpr int MN_PAD = 32;   // bf16 elements of padding per k-row of an M/N-major tile (64 bytes)
@@ -47,6 +47,7 @@ struct Args {
   bf16* H;                           // EPI_SWIGLU: [rows, 2f] receives G|U;  EPI_SWIGLU_BWD: read G|U
   bf16* A_out;                       // [rows, f]: SwiGLU output (both fused epilogues)
   bf16* dH;                          // EPI_SWIGLU_BWD: [rows, 2f] receives dG|dU
+  const float* bias;                 // EPI_BIAS_F32: per-column fp32 bias or NULL; C is fp32, any N
 };
 
 template <int ROWS> struct KMajorTile {   // [ROWS][64] bf16, swizzled

@@ -1,18 +1,20 @@
-// Launchers of the grouped MFMA GEMM template for the bf16 expert FFN (Section 4.1: FC1 -> SwiGLU
-// -> FC2 and the backward of each).  Tile shapes were picked by measurement on MI355X.
-#include "gemm_mfma.h"
+// Launchers of the grouped MFMA GEMM (asynchronous global->LDS pipeline) for the bf16 expert FFN
+// (Section 4.1: FC1 -> SwiGLU -> FC2 and the backward of each) and for the router matmul.
+// Tile shapes, wave layouts and pipeline depths were picked by measurement on MI355X.
+#include "gemm_mfma_dma.h"
 
 namespace moe {
 namespace {
 
 using namespace mfma;
 
-template <int BM, int BN, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC>
 int launch(const Args& a, long blocks, hipStream_t s) {
   if (blocks <= 0) return MOE_OK;
+  blocks = (blocks + 7) / 8 * 8;          // the tile map deals whole rounds of 8 workgroups (one per XCD)
   if (blocks > 0x7fffffffL) return MOE_ERR_UNSUPPORTED;
-  auto kern = grouped_gemm_kernel<BM, BN, WM, WN, LA, LB, MODE, EPI, TC>;
-  constexpr int smem = smem_bytes<BM, BN, LA, LB>();
+  auto kern = grouped_gemm_dma_kernel<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC>;
+  constexpr int smem = dma_smem_bytes<BM, BN, BKT, NS, LA, LB>();
   static bool configured = false;    // one flag per instantiation; the attribute is per function
   if (!configured) {
     MOE_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
@@ -37,7 +39,7 @@ int mfma_fc1_swiglu(const void* xp, const void* w1, const int32_t* offsets, int 
   a.B = (const bf16*)w1; a.ldb = d; a.b_es = 2L * f * d;
   a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d; a.f = f;
   a.H = (bf16*)H; a.A_out = (bf16*)A_out;
-  return launch<256, 256, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_SWIGLU, bf16>(a, rowseg_blocks(M, E, f, 256, 128), s);
+  return launch<256, 256, 64, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_SWIGLU, bf16>(a, rowseg_blocks(M, E, f, 256, 128), s);
 }
 
 // C[M,N] = A[M,K] * W[e]^T with W[e] = [N,K]
@@ -47,7 +49,7 @@ int mfma_rowseg_nt(const void* A, const void* W, long w_es, const int32_t* offse
   a.A = (const bf16*)A; a.lda = K;
   a.B = (const bf16*)W; a.ldb = K; a.b_es = w_es;
   a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
-  return launch<256, 256, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
+  return launch<256, 256, 64, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
 }
 
 // C[M,N] = A[M,K] * W[e] with W[e] = [K,N]
@@ -57,7 +59,7 @@ int mfma_rowseg_nn(const void* A, const void* W, long w_es, const int32_t* offse
   a.A = (const bf16*)A; a.lda = K;
   a.B = (const bf16*)W; a.ldb = N; a.b_es = w_es;
   a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
-  return launch<256, 256, 2, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
+  return launch<256, 256, 32, 4, 4, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
 }
 
 // dA = d_yp * w2[e] fused with the SwiGLU derivative: reads H=[G|U], writes dH=[dG|dU] and (optionally) A
@@ -68,7 +70,7 @@ int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offs
   a.B = (const bf16*)w2; a.ldb = f; a.b_es = (long)d * f;
   a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d;
   a.H = (bf16*)const_cast<void*>(H); a.dH = (bf16*)dH; a.A_out = (bf16*)A_out;
-  return launch<256, 256, 2, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_SWIGLU_BWD, bf16>(a, rowseg_blocks(M, E, f, 256, 256), s);
+  return launch<256, 256, 32, 4, 4, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_SWIGLU_BWD, bf16>(a, rowseg_blocks(M, E, f, 256, 256), s);
 }
 
 // C[e][Mo,N] (+)= P[rows_e, Mo]^T * Q[rows_e, N]
@@ -80,8 +82,21 @@ int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int
   a.C = C; a.ldc = N; a.c_es = (long)Mo * N; a.offsets = offsets; a.E = E; a.M = Mo; a.N = N; a.K = 0;
   a.accumulate = accumulate;
   const long blocks = (long)E * cdiv(Mo, 256) * cdiv(N, 256);
-  if (c_dt == MOE_F32) return launch<256, 256, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, float>(a, blocks, s);
-  return launch<256, 256, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, bf16>(a, blocks, s);
+  if (c_dt == MOE_F32) return launch<256, 256, 32, 4, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, float>(a, blocks, s);
+  return launch<256, 256, 32, 4, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, bf16>(a, blocks, s);
+}
+
+// logits[T,E] = x[T,d] * w_r[E,d]^T (+ bias), fp32 out
+int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, int d, int E, float* logits,
+                    hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)x; a.lda = d;
+  a.B = (const bf16*)w_r; a.ldb = d; a.b_es = 0;
+  a.C = logits; a.ldc = E; a.E = 1; a.M = T; a.N = E; a.K = d; a.bias = bias;
+  const long mt = cdiv(T, 256);
+  if (E <= 32) return launch<256, 32, 64, 2, 4, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, mt, s);
+  if (E <= 64) return launch<256, 64, 64, 2, 4, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, mt, s);
+  return launch<256, 128, 64, 2, 4, 2, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, mt * cdiv(E, 128), s);
 }
 
 }  // namespace moe

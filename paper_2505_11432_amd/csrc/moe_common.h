@@ -93,6 +93,12 @@ int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offs
 int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int N, int E, void* C, moe_dtype c_dt,
                int accumulate, hipStream_t s);
 
+int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, int d, int E, float* logits,
+                    hipStream_t s);
+size_t router_bwd_ws_bytes(int T, int d, int E);
+int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt, int T, int d, int E,
+                      float* d_w_r, void* dx, void* ws, hipStream_t s);
+
 int launch_swiglu_fwd(const void* H, void* A, int M, int f, const int32_t* row_limit, moe_dtype dt, hipStream_t s);
 int launch_swiglu_bwd(const void* H, const void* dA, void* dH, int M, int f, const int32_t* row_limit,
                       moe_dtype dt, hipStream_t s);

@@ -106,5 +106,5 @@ class MoELayer:
         c("route_bwd", B.moe_route_bwd, self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E,
           self.renorm, self.d_logits)
         if with_router:
-            c("router_bwd", B.moe_router_bwd, x, w_r, self.d_logits, self.d_w_r, self.dx)
+            c("router_bwd", B.moe_router_bwd, x, w_r, self.d_logits, self.d_w_r, self.dx, self.workspace)
         return self.dx

@@ -107,7 +107,8 @@ def test_router_fwd_bwd(B, dtype, T, d, E):
     dx0 = bf16_round(rng.standard_normal((T, d)).astype(np.float32)) if dtype == "bf16" else rng.standard_normal((T, d)).astype(np.float32)
     dwr = torch.empty((E, d), device=DEV)
     dx = to_dev(dx0, td)
-    B.moe_router_bwd(x, wr, to_dev(dz), dwr, dx)
+    ws = torch.empty(max(B.moe_workspace_bytes(T, d, E, 1, 16, B.dtype_code(td)), 256), dtype=torch.uint8, device=DEV)
+    B.moe_router_bwd(x, wr, to_dev(dz), dwr, dx, ws)
     dW_ref, dx_ref = O.router_bwd(inp["x"], inp["W_r"], dz)
     assert max_norm_err(to_np(dwr), dW_ref.T) < 1e-5
     assert max_norm_err(to_np(dx), dx0 + dx_ref) < TOL[dtype]
