@@ -48,6 +48,7 @@ struct Args {
   bf16* A_out;                       // [rows, f]: SwiGLU output (both fused epilogues)
   bf16* dH;                          // EPI_SWIGLU_BWD: [rows, 2f] receives dG|dU
   const float* bias;                 // EPI_BIAS_F32: per-column fp32 bias or NULL; C is fp32, any N
+  unsigned long long* clk_out;       // tuning aid (NULL in the library): per-block {core clocks, 100 MHz ticks}
 };
 
 template <int ROWS> struct KMajorTile {   // [ROWS][64] bf16, swizzled

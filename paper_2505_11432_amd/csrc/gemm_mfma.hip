@@ -8,11 +8,27 @@ namespace {
 
 using namespace mfma;
 
+// One persistent workgroup per CU, in whole rounds of 8 (one per XCD).
+int persistent_grid(int* grid) {
+  static int cached[64] = {0};
+  int dev = 0;
+  MOE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return MOE_ERR_UNSUPPORTED;
+  if (cached[dev] == 0) {
+    int cus = 0;
+    MOE_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    cached[dev] = cus >= 8 ? cus / 8 * 8 : 8;
+  }
+  *grid = cached[dev];
+  return MOE_OK;
+}
+
 template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC>
-int launch(const Args& a, long blocks, hipStream_t s) {
-  if (blocks <= 0) return MOE_OK;
-  blocks = (blocks + 7) / 8 * 8;          // the tile map deals whole rounds of 8 workgroups (one per XCD)
-  if (blocks > 0x7fffffffL) return MOE_ERR_UNSUPPORTED;
+int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
+  if (tiles_upper_bound <= 0) return MOE_OK;
+  int blocks = 0;
+  const int rc = persistent_grid(&blocks);
+  if (rc != MOE_OK) return rc;
   auto kern = grouped_gemm_dma_kernel<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC>;
   constexpr int smem = dma_smem_bytes<BM, BN, BKT, NS, LA, LB>();
   static bool configured = false;    // one flag per instantiation; the attribute is per function

@@ -7,6 +7,11 @@
 // One s_barrier per k-step: after it every wave's loads for the step have landed and every wave has
 // left the previous step, whose buffer the new loads may overwrite.
 //
+// The kernel is persistent: one workgroup per CU walks a static list of tiles.  When the last k-step of
+// a tile is done the ring is free, so the first stages of the NEXT tile are put in flight before the
+// current tile's epilogue runs; workgroup launch, tile lookup, pointer set-up and the cold first loads
+// all disappear behind the epilogue's stores.
+//
 // A direct-to-LDS load deposits the wave's 64 x 16 bytes contiguously, so the LDS swizzles are applied
 // on the global side: the lane that owns physical chunk pc of a row fetches logical chunk pc ^ swz(row).
 //   K-major tile [rows][BKT]:  swz = (row / rows_per_256B) mod chunks_per_row  -> ds_read_b128 conflict-free
@@ -14,6 +19,8 @@
 // Loads that fall outside the contraction range fetch from a 16-byte zero block instead, which gives
 // the exact zero fill that ragged expert segments (wgrad) and K tails need.
 #pragma once
+#include <type_traits>
+
 #include "gemm_mfma.h"
 
 namespace moe {
@@ -23,7 +30,9 @@ static __device__ __attribute__((aligned(16))) const unsigned int g_zero_block[4
 
 // One wave-wide direct-to-LDS load: lane i's 16 bytes land at lds_addr + 16*i.  lds_addr is wave-uniform.
 __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory", "m0");
+  // No "memory" clobber: the LDS write is asynchronous anyway and is ordered by wait_vmcnt + s_barrier, and
+  // without it the compiler stays free to hoist LDS fragment reads of the current stage across the load.
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "m0");
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
@@ -70,136 +79,159 @@ __device__ __forceinline__ bf16x8 read_frag_dma(const char* tile, int base, int 
 }
 
 template <int BM, int BN, int BKT, int NSTAGE, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC,
-          int PROBE = 0>   // PROBE (tuning only): 1 = no global loads, 2 = no LDS reads / MFMAs
+          int PROBE = 0>   // PROBE (tuning only): 1 = no global loads, 2 = no LDS reads / MFMAs, 3 = all tiles load tile 0
 __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) {
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int A_BYTES = DmaTileBytes<LA, BM, BKT>::value, B_BYTES = DmaTileBytes<LB, BN, BKT>::value;
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
   constexpr int A_DMA = A_BYTES / 1024 / NW, B_DMA = B_BYTES / 1024 / NW;     // loads per wave per stage
   constexpr int LOADS = A_DMA + B_DMA;
+  constexpr int KK = BKT / 16;
+  constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr int GN = 4, XCDS = 8;
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile does not split over the waves");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * LOADS < 64, "pipeline depth exceeds the vmcnt range");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up MFMA tiles inside a wave");
+  static_assert(NW * 64 >= MOE_MAX_EXPERTS, "the tile table is built one expert per thread");
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  int* cum_tiles = reinterpret_cast<int*>(smem + RING_BYTES);          // [E+1] running count of m-tiles (ROWSEG)
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
+  const char* zero = reinterpret_cast<const char*>(g_zero_block);
 
-  // ---- which tile is mine -----------------------------------------------------------------
+  // ---- the tile list ------------------------------------------------------------------------------
   // Workgroup b runs on XCD b % 8 and each XCD has its own L2, so XCD x is handed the x-th eighth of a
   // logical tile order in which 32 consecutive tiles (one per CU of the XCD) form a compact block of one
-  // expert: all of GN adjacent n-tiles for a run of m-tiles.  Those tiles stream the same A and B panels
-  // at the same k, which turns most of their loads into L2 hits.
-  constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
-  constexpr int GN = 4, XCDS = 8;
+  // expert: GN adjacent n-tiles for a run of m-tiles.  Those tiles stream the same A and B panels at the
+  // same k, which turns most of their loads into L2 hits.  Workgroup b takes slots b/8, b/8 + G/8, ...
   const int tiles_n = (p.N + BN_OUT - 1) / BN_OUT;
-  const int tiles_m_fixed = (p.M + BM - 1) / BM;              // KSEG only
+  const int tiles_m_fixed = (p.M + BM - 1) / BM;              // KSEG / PLAIN
   int total_tiles;
   if constexpr (MODE == ROWSEG) {
-    int mts = 0;
-    for (int i = 0; i < p.E; ++i) mts += (p.offsets[i + 1] - p.offsets[i] + BM - 1) / BM;
-    total_tiles = mts * tiles_n;
+    if (tid == 0) {
+      int run = 0;
+      cum_tiles[0] = 0;
+      for (int i = 0; i < p.E; ++i) {
+        run += (p.offsets[i + 1] - p.offsets[i] + BM - 1) / BM;
+        cum_tiles[i + 1] = run;
+      }
+    }
+    __syncthreads();
+    total_tiles = cum_tiles[p.E] * tiles_n;
   } else if constexpr (MODE == KSEG) {
     total_tiles = p.E * tiles_m_fixed * tiles_n;
   } else {
     total_tiles = tiles_m_fixed * tiles_n;
   }
   const int per_xcd = (total_tiles + XCDS - 1) / XCDS;
-  const int slot = blockIdx.x / XCDS;
-  if (slot >= per_xcd) return;
-  int l = (blockIdx.x % XCDS) * per_xcd + slot;                // logical tile index
-  if (l >= total_tiles) return;
-  int e, mt_e, m_lo, m_hi;
-  if constexpr (MODE == ROWSEG) {
-    for (e = 0; e < p.E; ++e) {
-      m_lo = p.offsets[e]; m_hi = p.offsets[e + 1];
-      mt_e = (m_hi - m_lo + BM - 1) / BM;
-      if (l < mt_e * tiles_n) break;
-      l -= mt_e * tiles_n;
-    }
-  } else {
-    mt_e = tiles_m_fixed;
-    e = l / (mt_e * tiles_n);          // always 0 in PLAIN mode
-    l -= e * mt_e * tiles_n;
-    m_lo = 0; m_hi = p.M;
-  }
-  const int ng = l / (mt_e * GN);
-  const int r = l - ng * mt_e * GN;
-  const int gw = min(GN, tiles_n - ng * GN);
-  const int mt = r / gw;
-  const int nt = ng * GN + (r - mt * gw);
-  const int m0 = m_lo + mt * BM, m_end = m_hi;
-  int k_begin, k_end;
-  if constexpr (MODE == KSEG) { k_begin = p.offsets[e]; k_end = p.offsets[e + 1]; }
-  else { k_begin = 0; k_end = p.K; }
-  const int n0 = nt * BN_OUT;
-  const bf16* __restrict__ Ag = p.A;
-  const bf16* __restrict__ Bg = p.B + (long)e * p.b_es;
-  const char* zero = reinterpret_cast<const char*>(g_zero_block);
+  const int xcd = blockIdx.x % XCDS;
+  const int slot_step = gridDim.x / XCDS;
+  int slot = blockIdx.x / XCDS;
 
-  // ---- per-lane source pointers of this wave's loads (k-step 0), and what advances them ----------
-  // load j of the wave covers DMA slot q = wave + j*NW of the tile (1 KiB of LDS each).
+  // tile state
+  int e = 0, m0 = 0, m_end = 0, n0 = 0, klen = 0, nk = 0;
   const char* a_src[A_DMA];
   const char* b_src[B_DMA];
   int a_k[A_DMA], b_k[B_DMA];       // k coordinate (relative to the k-step start) this lane's chunk begins at
-  long a_step, b_step;              // bytes to advance per k-step
-#pragma unroll
-  for (int j = 0; j < A_DMA; ++j) {
-    const int q = wave + j * NW;
-    if constexpr (LA == KMAJOR) {
-      using TL = KTile<BM, BKT>;
-      const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
-      const int lc = (lane % TL::CPR) ^ TL::swz(row);
-      const int gr = min(m0 + row, p.M - 1);
-      a_src[j] = reinterpret_cast<const char*>(Ag + (long)gr * p.lda + k_begin + lc * 8);
-      a_k[j] = lc * 8;
-    } else {
-      using TL = MNTile<BM, BKT>;
-      const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
-      const int lc = (lane % TL::CPR) ^ TL::swz(krow);
-      const int col = min(m0 + lc * 8, p.M - 8);
-      a_src[j] = reinterpret_cast<const char*>(Ag + (long)(k_begin + krow) * p.lda + col);
-      a_k[j] = krow;
-    }
-  }
-  a_step = (LA == KMAJOR) ? (long)BKT * 2 : (long)BKT * p.lda * 2;
-#pragma unroll
-  for (int j = 0; j < B_DMA; ++j) {
-    const int q = wave + j * NW;
-    if constexpr (LB == KMAJOR) {
-      using TL = KTile<BN, BKT>;
-      const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
-      const int lc = (lane % TL::CPR) ^ TL::swz(row);
-      int gr;
-      if constexpr (EPI == EPI_SWIGLU) {
-        const int qq = row >> 5;
-        const int n = min(n0 + (qq >> 1) * 32 + (row & 31), p.f - 1);
-        gr = (qq & 1) ? p.f + n : n;
-      } else {
-        gr = min(n0 + row, p.N - 1);
+  const long a_step = (LA == KMAJOR) ? (long)BKT * 2 : (long)BKT * p.lda * 2;   // bytes per k-step
+  const long b_step = (LB == KMAJOR) ? (long)BKT * 2 : (long)BKT * p.ldb * 2;
+
+  // Decode slot -> tile and set up this lane's source pointers.  Returns false when the list is exhausted.
+  auto open_tile = [&](int sl) -> bool {
+    if (sl >= per_xcd) return false;
+    int l = xcd * per_xcd + sl;
+    if (l >= total_tiles) return false;
+    int mt_e, m_lo, m_hi;
+    if constexpr (MODE == ROWSEG) {
+      // binary search: largest ex with cum_tiles[ex] * tiles_n <= l
+      int lo = 0, hi = p.E;
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cum_tiles[mid] * tiles_n <= l) lo = mid; else hi = mid;
       }
-      b_src[j] = reinterpret_cast<const char*>(Bg + (long)gr * p.ldb + k_begin + lc * 8);
-      b_k[j] = lc * 8;
+      e = lo;
+      mt_e = cum_tiles[e + 1] - cum_tiles[e];
+      l -= cum_tiles[e] * tiles_n;
+      m_lo = p.offsets[e]; m_hi = p.offsets[e + 1];
     } else {
-      using TL = MNTile<BN, BKT>;
-      const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
-      const int lc = (lane % TL::CPR) ^ TL::swz(krow);
-      const int col = min(n0 + lc * 8, p.N - 8);
-      b_src[j] = reinterpret_cast<const char*>(Bg + (long)(k_begin + krow) * p.ldb + col);
-      b_k[j] = krow;
+      mt_e = tiles_m_fixed;
+      e = l / (mt_e * tiles_n);          // always 0 in PLAIN mode
+      l -= e * mt_e * tiles_n;
+      m_lo = 0; m_hi = p.M;
     }
-  }
-  b_step = (LB == KMAJOR) ? (long)BKT * 2 : (long)BKT * p.ldb * 2;
+    const int ng = l / (mt_e * GN);
+    const int r = l - ng * mt_e * GN;
+    const int gw = min(GN, tiles_n - ng * GN);
+    const int mt = r / gw;
+    const int nt = ng * GN + (r - mt * gw);
+    m0 = m_lo + mt * BM; m_end = m_hi; n0 = nt * BN_OUT;
+    int k_begin, k_end;
+    if constexpr (MODE == KSEG) { k_begin = p.offsets[e]; k_end = p.offsets[e + 1]; }
+    else { k_begin = 0; k_end = p.K; }
+    klen = k_end - k_begin;
+    nk = (klen + BKT - 1) / BKT;
+    const bf16* __restrict__ Ag = p.A;
+    const bf16* __restrict__ Bg = p.B + (long)e * p.b_es;
+    const int real_m0 = m0, real_n0 = n0;
+    if constexpr (PROBE == 3) { m0 = 0; n0 = 0; Bg = p.B; }      // every tile loads the same panels (all L2 hits)
+    // load j of the wave covers DMA slot q = wave + j*NW of the tile (1 KiB of LDS each)
+#pragma unroll
+    for (int j = 0; j < A_DMA; ++j) {
+      const int q = wave + j * NW;
+      if constexpr (LA == KMAJOR) {
+        using TL = KTile<BM, BKT>;
+        const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
+        const int lc = (lane % TL::CPR) ^ TL::swz(row);
+        const int gr = min(m0 + row, p.M - 1);
+        a_src[j] = reinterpret_cast<const char*>(Ag + (long)gr * p.lda + k_begin + lc * 8);
+        a_k[j] = lc * 8;
+      } else {
+        using TL = MNTile<BM, BKT>;
+        const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
+        const int lc = (lane % TL::CPR) ^ TL::swz(krow);
+        const int col = min(m0 + lc * 8, p.M - 8);
+        a_src[j] = reinterpret_cast<const char*>(Ag + (long)(k_begin + krow) * p.lda + col);
+        a_k[j] = krow;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < B_DMA; ++j) {
+      const int q = wave + j * NW;
+      if constexpr (LB == KMAJOR) {
+        using TL = KTile<BN, BKT>;
+        const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
+        const int lc = (lane % TL::CPR) ^ TL::swz(row);
+        int gr;
+        if constexpr (EPI == EPI_SWIGLU) {
+          const int qq = row >> 5;
+          const int n = min(n0 + (qq >> 1) * 32 + (row & 31), p.f - 1);
+          gr = (qq & 1) ? p.f + n : n;
+        } else {
+          gr = min(n0 + row, p.N - 1);
+        }
+        b_src[j] = reinterpret_cast<const char*>(Bg + (long)gr * p.ldb + k_begin + lc * 8);
+        b_k[j] = lc * 8;
+      } else {
+        using TL = MNTile<BN, BKT>;
+        const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
+        const int lc = (lane % TL::CPR) ^ TL::swz(krow);
+        const int col = min(n0 + lc * 8, p.N - 8);
+        b_src[j] = reinterpret_cast<const char*>(Bg + (long)(k_begin + krow) * p.ldb + col);
+        b_k[j] = krow;
+      }
+    }
+    m0 = real_m0; n0 = real_n0;
+    return true;
+  };
 
-  const int klen = k_end - k_begin;
-  const int nk = (klen + BKT - 1) / BKT;
-
-  // Issue the loads of k-step `ks` into ring slot ks % NSTAGE.  Only the last step can be ragged.
+  // Issue the loads of k-step `ks` of the open tile into ring slot ks % NSTAGE.  Only the last step can be ragged.
   auto issue = [&](int ks) {
     if constexpr (PROBE == 1) return;
     const unsigned stage = smem_lds + (unsigned)(ks % NSTAGE) * STAGE_BYTES;
@@ -218,147 +250,171 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       dma16(src, stage + A_BYTES + (unsigned)(wave + j * NW) * 1024u);
     }
   };
+  auto issue_prologue = [&]() {
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nk) issue(s);
+  };
 
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  if (!open_tile(slot)) return;
+  issue_prologue();
 
-  // ---- pipeline ---------------------------------------------------------------------------------
+  for (;;) {
+    unsigned long long clk0 = 0, rt0 = 0;
+    if (p.clk_out) { clk0 = __builtin_readcyclecounter(); rt0 = __builtin_amdgcn_s_memrealtime(); }
+    f32x16 acc[TM][TN];
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
-    if (s < nk) issue(s);
-
-  for (int kt = 0; kt < nk; ++kt) {
-    // my loads for step kt have landed once at most the younger steps' loads are outstanding
-    if (kt + NSTAGE - 2 < nk) wait_vmcnt<(NSTAGE - 2) * LOADS>();
-    else wait_vmcnt<0>();
-    __syncthreads();
-    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
-
-    const char* at = smem + (kt % NSTAGE) * STAGE_BYTES;
-    const char* bt = at + A_BYTES;
-    if constexpr (PROBE == 2) continue;
-#pragma unroll
-    for (int kk = 0; kk < BKT / 16; ++kk) {
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = read_frag_dma<LA, BM, BKT>(at, wm * WTM + i * 32, kk, lane);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = read_frag_dma<LB, BN, BKT>(bt, wn * WTN + j * 32, kk, lane);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-    }
-  }
-
-  // ---- epilogue (same register layout as gemm_mfma.h) ------------------------------------------
-  const int lrow = lane & 31, lcol = (lane >> 5) << 2;
-  if constexpr (EPI == EPI_STORE) {
-    TC* __restrict__ Cg = static_cast<TC*>(p.C) + (long)e * p.c_es;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + wm * WTM + i * 32 + lrow;
-      if (m >= m_end) continue;
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn * WTN + j * 32 + q * 8 + lcol;
-          if (n >= p.N) continue;
-          TC* dst = Cg + (long)m * p.ldc + n;
-          float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-          Vec16<TC> o;
-          if (p.accumulate) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) v[t] += to_f32(dst[t]);
-          }
-#pragma unroll
-          for (int t = 0; t < 4; ++t) o.v[t] = from_f32<TC>(v[t]);
-          if constexpr (sizeof(TC) == 4) *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<uint4*>(&o);
-          else *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<uint2*>(&o);
-        }
-      }
-    }
-  } else if constexpr (EPI == EPI_BIAS_F32) {
-    float* __restrict__ Cg = static_cast<float*>(p.C);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + wm * WTM + i * 32 + lrow;
-      if (m >= m_end) continue;
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int n = n0 + wn * WTN + j * 32 + (r >> 2) * 8 + lcol + (r & 3);
-          if (n < p.N) Cg[(long)m * p.ldc + n] = acc[i][j][r] + (p.bias ? p.bias[n] : 0.f);
-        }
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // ---- k loop ------------------------------------------------------------------------------------
+    for (int kt = 0; kt < nk; ++kt) {
+      // my loads for step kt have landed once at most the younger steps' loads are outstanding; the first
+      // step of a tile also drains the previous tile's epilogue stores, which share the counter
+      if (kt > 0 && kt + NSTAGE - 2 < nk) wait_vmcnt<(NSTAGE - 2) * LOADS>();
+      else wait_vmcnt<0>();
+      __syncthreads();
+      if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+      const char* at = smem + (kt % NSTAGE) * STAGE_BYTES;
+      const char* bt = at + A_BYTES;
+      if constexpr (PROBE == 2) continue;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        bf16x8 af[TM], bfr[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[i] = read_frag_dma<LA, BM, BKT>(at, wm * WTM + i * 32, kk, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[j] = read_frag_dma<LB, BN, BKT>(bt, wn * WTN + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+      }
     }
-  } else if constexpr (EPI == EPI_SWIGLU) {
+    if (p.clk_out && tid == 0 && blockIdx.x < 2048) {
+      p.clk_out[2 * blockIdx.x] += __builtin_readcyclecounter() - clk0;
+      p.clk_out[2 * blockIdx.x + 1] += __builtin_amdgcn_s_memrealtime() - rt0;
+    }
+
+    // ---- hand the ring to the next tile, then write this one out -------------------------------------
+    const int ep_e = e, ep_m0 = m0, ep_m_end = m_end, ep_n0 = n0;
+    slot += slot_step;
+    __syncthreads();                      // every wave has read its last fragments: the ring is free
+    const bool has_next = open_tile(slot);
+    if (has_next) issue_prologue();
+    {
+      const int e = ep_e, m0 = ep_m0, m_end = ep_m_end, n0 = ep_n0;
+      (void)e;
+      // lane holds output row m = base + lane%32 and columns 8q + 4(lane/32) + 0..3 of each MFMA tile
+      const int lrow = lane & 31, lcol = (lane >> 5) << 2;
+      if constexpr (EPI == EPI_STORE) {
+        TC* __restrict__ Cg = static_cast<TC*>(p.C) + (long)e * p.c_es;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + wm * WTM + i * 32 + lrow;
-      if (m >= m_end) continue;
+        for (int i = 0; i < TM; ++i) {
+          const int m = m0 + wm * WTM + i * 32 + lrow;
+          if (m >= m_end) continue;
 #pragma unroll
-      for (int j = 0; j < TN; j += 2) {
+          for (int j = 0; j < TN; ++j) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + ((wn * WTN + j * 32) >> 1) + q * 8 + lcol;
-          if (n >= p.f) continue;
-          bf16x4 g, u, a;
+            for (int q = 0; q < 4; ++q) {
+              const int n = n0 + wn * WTN + j * 32 + q * 8 + lcol;
+              if (n >= p.N) continue;
+              TC* dst = Cg + (long)m * p.ldc + n;
+              float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+              Vec16<TC> o;
+              if (p.accumulate) {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            g[t] = static_cast<bf16>(acc[i][j][4 * q + t]);
-            u[t] = static_cast<bf16>(acc[i][j + 1][4 * q + t]);
-            const float gf = static_cast<float>(g[t]);
-            a[t] = static_cast<bf16>(gf * sigmoid_f32(gf) * static_cast<float>(u[t]));
+                for (int t = 0; t < 4; ++t) v[t] += to_f32(dst[t]);
+              }
+#pragma unroll
+              for (int t = 0; t < 4; ++t) o.v[t] = from_f32<TC>(v[t]);
+              if constexpr (sizeof(TC) == 4) *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<uint4*>(&o);
+              else *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<uint2*>(&o);
+            }
           }
-          *reinterpret_cast<bf16x4*>(p.H + (long)m * 2 * p.f + n) = g;
-          *reinterpret_cast<bf16x4*>(p.H + (long)m * 2 * p.f + p.f + n) = u;
-          *reinterpret_cast<bf16x4*>(p.A_out + (long)m * p.f + n) = a;
+        }
+      } else if constexpr (EPI == EPI_BIAS_F32) {
+        float* __restrict__ Cg = static_cast<float*>(p.C);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int m = m0 + wm * WTM + i * 32 + lrow;
+          if (m >= m_end) continue;
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int n = n0 + wn * WTN + j * 32 + (r >> 2) * 8 + lcol + (r & 3);
+              if (n < p.N) Cg[(long)m * p.ldc + n] = acc[i][j][r] + (p.bias ? p.bias[n] : 0.f);
+            }
+        }
+      } else if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int m = m0 + wm * WTM + i * 32 + lrow;
+          if (m >= m_end) continue;
+#pragma unroll
+          for (int j = 0; j < TN; j += 2) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int n = n0 + ((wn * WTN + j * 32) >> 1) + q * 8 + lcol;
+              if (n >= p.f) continue;
+              bf16x4 g, u, a;
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                g[t] = static_cast<bf16>(acc[i][j][4 * q + t]);
+                u[t] = static_cast<bf16>(acc[i][j + 1][4 * q + t]);
+                const float gf = static_cast<float>(g[t]);
+                a[t] = static_cast<bf16>(gf * sigmoid_f32(gf) * static_cast<float>(u[t]));
+              }
+              *reinterpret_cast<bf16x4*>(p.H + (long)m * 2 * p.f + n) = g;
+              *reinterpret_cast<bf16x4*>(p.H + (long)m * 2 * p.f + p.f + n) = u;
+              *reinterpret_cast<bf16x4*>(p.A_out + (long)m * p.f + n) = a;
+            }
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int m = m0 + wm * WTM + i * 32 + lrow;
+          if (m >= m_end) continue;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int n = n0 + wn * WTN + j * 32 + q * 8 + lcol;
+              if (n >= p.N) continue;
+              const bf16x4 g = *reinterpret_cast<const bf16x4*>(p.H + (long)m * 2 * p.N + n);
+              const bf16x4 u = *reinterpret_cast<const bf16x4*>(p.H + (long)m * 2 * p.N + p.N + n);
+              bf16x4 dg, du, a;
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                const float gf = static_cast<float>(g[t]), uf = static_cast<float>(u[t]);
+                const float d = static_cast<float>(static_cast<bf16>(acc[i][j][4 * q + t]));
+                const float s = sigmoid_f32(gf);
+                dg[t] = static_cast<bf16>(d * uf * s * (1.0f + gf * (1.0f - s)));
+                du[t] = static_cast<bf16>(d * gf * s);
+                a[t] = static_cast<bf16>(gf * s * uf);
+              }
+              *reinterpret_cast<bf16x4*>(p.dH + (long)m * 2 * p.N + n) = dg;
+              *reinterpret_cast<bf16x4*>(p.dH + (long)m * 2 * p.N + p.N + n) = du;
+              if (p.A_out) *reinterpret_cast<bf16x4*>(p.A_out + (long)m * p.N + n) = a;
+            }
+          }
         }
       }
     }
-  } else {
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int m = m0 + wm * WTM + i * 32 + lrow;
-      if (m >= m_end) continue;
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn * WTN + j * 32 + q * 8 + lcol;
-          if (n >= p.N) continue;
-          const bf16x4 g = *reinterpret_cast<const bf16x4*>(p.H + (long)m * 2 * p.N + n);
-          const bf16x4 u = *reinterpret_cast<const bf16x4*>(p.H + (long)m * 2 * p.N + p.N + n);
-          bf16x4 dg, du, a;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const float gf = static_cast<float>(g[t]), uf = static_cast<float>(u[t]);
-            const float d = static_cast<float>(static_cast<bf16>(acc[i][j][4 * q + t]));
-            const float s = sigmoid_f32(gf);
-            dg[t] = static_cast<bf16>(d * uf * s * (1.0f + gf * (1.0f - s)));
-            du[t] = static_cast<bf16>(d * gf * s);
-            a[t] = static_cast<bf16>(gf * s * uf);
-          }
-          *reinterpret_cast<bf16x4*>(p.dH + (long)m * 2 * p.N + n) = dg;
-          *reinterpret_cast<bf16x4*>(p.dH + (long)m * 2 * p.N + p.N + n) = du;
-          if (p.A_out) *reinterpret_cast<bf16x4*>(p.A_out + (long)m * p.N + n) = a;
-        }
-      }
-    }
+    if (!has_next) break;
   }
 }
 
 template <int BM, int BN, int BKT, int NSTAGE, Layout LA, Layout LB>
 constexpr int dma_smem_bytes() {
-  return NSTAGE * (DmaTileBytes<LA, BM, BKT>::value + DmaTileBytes<LB, BN, BKT>::value);
+  // the ring plus the per-expert tile table
+  return NSTAGE * (DmaTileBytes<LA, BM, BKT>::value + DmaTileBytes<LB, BN, BKT>::value) + (MOE_MAX_EXPERTS + 8) * 4;
 }
 
 }  // namespace mfma
