@@ -78,6 +78,69 @@ __device__ __forceinline__ bf16x8 read_frag_dma(const char* tile, int base, int 
   }
 }
 
+
+// ---- epilogue staging --------------------------------------------------------------------------------
+// After the MFMA (weight fragment first) a lane holds one output row (lane % 32) and columns
+// 8q + 4*(lane/32) + 0..3 (q = 0..3) of a 32x32 tile: a direct store would touch 32 rows with 16 bytes
+// each.  Each wave therefore owns a small LDS patch of 32 rows x 64 bytes; tiles pass through it so that
+// global memory sees 16-byte lanes forming 64-byte row segments (4 lanes per row, 16 rows per instruction).
+constexpr int STG_STRIDE = 80;                  // bytes per staged row (64 payload + 16 pad)
+constexpr int STG_BYTES = 32 * STG_STRIDE;      // per wave
+
+// 32 rows x 32 bf16 columns from registers to global memory (row-major, leading dimension ld elements).
+__device__ __forceinline__ void stage_store_bf16(char* stg, const bf16x4 (&v)[4], bf16* g, long ld, int rows_valid,
+                                                 int cols_valid, int lane) {
+  const int row = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) *reinterpret_cast<bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2) = v[q];
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    const uint4 val = *reinterpret_cast<const uint4*>(stg + r * STG_STRIDE + c * 2);
+    if (r < rows_valid && c < cols_valid) *reinterpret_cast<uint4*>(g + (long)r * ld + c) = val;
+  }
+}
+
+// 32 rows x 32 bf16 columns from global memory into registers (same lane layout as the accumulators).
+__device__ __forceinline__ void stage_load_bf16(char* stg, bf16x4 (&v)[4], const bf16* g, long ld, int rows_valid,
+                                                int cols_valid, int lane) {
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (r < rows_valid && c < cols_valid) val = *reinterpret_cast<const uint4*>(g + (long)r * ld + c);
+    *reinterpret_cast<uint4*>(stg + r * STG_STRIDE + c * 2) = val;
+  }
+  const int row = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2);
+}
+
+// 32 rows x 32 fp32 columns, as two halves of 16 columns; optional read-modify-write accumulation.
+__device__ __forceinline__ void stage_store_f32(char* stg, const f32x16& acc, float* g, long ld, int rows_valid,
+                                                int cols_valid, bool accumulate, int lane) {
+  const int row = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int qq = 0; qq < 2; ++qq) {
+      const int q = half * 2 + qq;
+      const f32x4 t = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      *reinterpret_cast<f32x4*>(stg + row * STG_STRIDE + (8 * qq + 4 * h) * 4) = t;
+    }
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int r = pass * 16 + (lane >> 2), c = half * 16 + (lane & 3) * 4;
+      f32x4 val = *reinterpret_cast<const f32x4*>(stg + r * STG_STRIDE + (lane & 3) * 16);
+      if (r < rows_valid && c < cols_valid) {
+        float* dst = g + (long)r * ld + c;
+        if (accumulate) val += *reinterpret_cast<const f32x4*>(dst);
+        *reinterpret_cast<f32x4*>(dst) = val;
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int BKT, int NSTAGE, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC,
           int PROBE = 0>   // PROBE (tuning only): 1 = no global loads, 2 = no LDS reads / MFMAs, 3 = all tiles load tile 0
 __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) {
@@ -95,16 +158,18 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile does not split over the waves");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * LOADS < 64, "pipeline depth exceeds the vmcnt range");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up MFMA tiles inside a wave");
-  static_assert(NW * 64 >= MOE_MAX_EXPERTS, "the tile table is built one expert per thread");
+  static_assert(NW <= 8, "LDS is budgeted for at most 8 epilogue patches");
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
   int* cum_tiles = reinterpret_cast<int*>(smem + RING_BYTES);          // [E+1] running count of m-tiles (ROWSEG)
+  constexpr int TABLE_BYTES = (MOE_MAX_EXPERTS + 8) * 4;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
   const char* zero = reinterpret_cast<const char*>(g_zero_block);
+  char* stg = smem + RING_BYTES + TABLE_BYTES + wave * STG_BYTES;      // this wave's epilogue patch
 
   // ---- the tile list ------------------------------------------------------------------------------
   // Workgroup b runs on XCD b % 8 and each XCD has its own L2, so XCD x is handed the x-th eighth of a
@@ -309,35 +374,44 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     {
       const int e = ep_e, m0 = ep_m0, m_end = ep_m_end, n0 = ep_n0;
       (void)e;
-      // lane holds output row m = base + lane%32 and columns 8q + 4(lane/32) + 0..3 of each MFMA tile
-      const int lrow = lane & 31, lcol = (lane >> 5) << 2;
+      // every 32x32 MFMA tile goes through the wave's LDS patch (see stage_store_* above)
       if constexpr (EPI == EPI_STORE) {
-        TC* __restrict__ Cg = static_cast<TC*>(p.C) + (long)e * p.c_es;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-          const int m = m0 + wm * WTM + i * 32 + lrow;
-          if (m >= m_end) continue;
+          const int mb = m0 + wm * WTM + i * 32;
+          const int rows_valid = m_end - mb;
+          if (rows_valid <= 0) continue;
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int n = n0 + wn * WTN + j * 32 + q * 8 + lcol;
-              if (n >= p.N) continue;
-              TC* dst = Cg + (long)m * p.ldc + n;
-              float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-              Vec16<TC> o;
+            const int nb = n0 + wn * WTN + j * 32;
+            const int cols_valid = p.N - nb;
+            if (cols_valid <= 0) continue;
+            if constexpr (sizeof(TC) == 4) {
+              float* g = static_cast<float*>(p.C) + (long)e * p.c_es + (long)mb * p.ldc + nb;
+              stage_store_f32(stg, acc[i][j], g, p.ldc, rows_valid, cols_valid, p.accumulate != 0, lane);
+            } else {
+              bf16* g = static_cast<bf16*>(p.C) + (long)e * p.c_es + (long)mb * p.ldc + nb;
+              bf16x4 v[4];
               if (p.accumulate) {
+                bf16x4 old[4];
+                stage_load_bf16(stg, old, g, p.ldc, rows_valid, cols_valid, lane);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) v[t] += to_f32(dst[t]);
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                  for (int t = 0; t < 4; ++t)
+                    v[q][t] = static_cast<bf16>(acc[i][j][4 * q + t] + static_cast<float>(old[q][t]));
+              } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                  for (int t = 0; t < 4; ++t) v[q][t] = static_cast<bf16>(acc[i][j][4 * q + t]);
               }
-#pragma unroll
-              for (int t = 0; t < 4; ++t) o.v[t] = from_f32<TC>(v[t]);
-              if constexpr (sizeof(TC) == 4) *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<uint4*>(&o);
-              else *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<uint2*>(&o);
+              stage_store_bf16(stg, v, g, p.ldc, rows_valid, cols_valid, lane);
             }
           }
         }
       } else if constexpr (EPI == EPI_BIAS_F32) {
+        const int lrow = lane & 31, lcol = (lane >> 5) << 2;
         float* __restrict__ Cg = static_cast<float*>(p.C);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -352,57 +426,64 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             }
         }
       } else if constexpr (EPI == EPI_SWIGLU) {
+        // MFMA tile 2j holds G and tile 2j+1 holds U for the same 32 output columns
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-          const int m = m0 + wm * WTM + i * 32 + lrow;
-          if (m >= m_end) continue;
+          const int mb = m0 + wm * WTM + i * 32;
+          const int rows_valid = m_end - mb;
+          if (rows_valid <= 0) continue;
 #pragma unroll
           for (int j = 0; j < TN; j += 2) {
+            const int nb = n0 + ((wn * WTN + j * 32) >> 1);
+            const int cols_valid = p.f - nb;
+            if (cols_valid <= 0) continue;
+            bf16x4 g[4], u[4], a[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int n = n0 + ((wn * WTN + j * 32) >> 1) + q * 8 + lcol;
-              if (n >= p.f) continue;
-              bf16x4 g, u, a;
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
               for (int t = 0; t < 4; ++t) {
-                g[t] = static_cast<bf16>(acc[i][j][4 * q + t]);
-                u[t] = static_cast<bf16>(acc[i][j + 1][4 * q + t]);
-                const float gf = static_cast<float>(g[t]);
-                a[t] = static_cast<bf16>(gf * sigmoid_f32(gf) * static_cast<float>(u[t]));
+                g[q][t] = static_cast<bf16>(acc[i][j][4 * q + t]);
+                u[q][t] = static_cast<bf16>(acc[i][j + 1][4 * q + t]);
+                const float gf = static_cast<float>(g[q][t]);
+                a[q][t] = static_cast<bf16>(gf * sigmoid_f32(gf) * static_cast<float>(u[q][t]));
               }
-              *reinterpret_cast<bf16x4*>(p.H + (long)m * 2 * p.f + n) = g;
-              *reinterpret_cast<bf16x4*>(p.H + (long)m * 2 * p.f + p.f + n) = u;
-              *reinterpret_cast<bf16x4*>(p.A_out + (long)m * p.f + n) = a;
-            }
+            bf16* hrow = p.H + (long)mb * 2 * p.f + nb;
+            stage_store_bf16(stg, g, hrow, 2L * p.f, rows_valid, cols_valid, lane);
+            stage_store_bf16(stg, u, hrow + p.f, 2L * p.f, rows_valid, cols_valid, lane);
+            stage_store_bf16(stg, a, p.A_out + (long)mb * p.f + nb, p.f, rows_valid, cols_valid, lane);
           }
         }
       } else {
+        // acc = dA; read G|U, write dG|dU and the recomputed SwiGLU output
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-          const int m = m0 + wm * WTM + i * 32 + lrow;
-          if (m >= m_end) continue;
+          const int mb = m0 + wm * WTM + i * 32;
+          const int rows_valid = m_end - mb;
+          if (rows_valid <= 0) continue;
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
+            const int nb = n0 + wn * WTN + j * 32;
+            const int cols_valid = p.N - nb;
+            if (cols_valid <= 0) continue;
+            bf16x4 g[4], u[4], dg[4], du[4], a[4];
+            const bf16* hrow = p.H + (long)mb * 2 * p.N + nb;
+            stage_load_bf16(stg, g, hrow, 2L * p.N, rows_valid, cols_valid, lane);
+            stage_load_bf16(stg, u, hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const int n = n0 + wn * WTN + j * 32 + q * 8 + lcol;
-              if (n >= p.N) continue;
-              const bf16x4 g = *reinterpret_cast<const bf16x4*>(p.H + (long)m * 2 * p.N + n);
-              const bf16x4 u = *reinterpret_cast<const bf16x4*>(p.H + (long)m * 2 * p.N + p.N + n);
-              bf16x4 dg, du, a;
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
               for (int t = 0; t < 4; ++t) {
-                const float gf = static_cast<float>(g[t]), uf = static_cast<float>(u[t]);
+                const float gf = static_cast<float>(g[q][t]), uf = static_cast<float>(u[q][t]);
                 const float d = static_cast<float>(static_cast<bf16>(acc[i][j][4 * q + t]));
-                const float s = sigmoid_f32(gf);
-                dg[t] = static_cast<bf16>(d * uf * s * (1.0f + gf * (1.0f - s)));
-                du[t] = static_cast<bf16>(d * gf * s);
-                a[t] = static_cast<bf16>(gf * s * uf);
+                const float sg = sigmoid_f32(gf);
+                dg[q][t] = static_cast<bf16>(d * uf * sg * (1.0f + gf * (1.0f - sg)));
+                du[q][t] = static_cast<bf16>(d * gf * sg);
+                a[q][t] = static_cast<bf16>(gf * sg * uf);
               }
-              *reinterpret_cast<bf16x4*>(p.dH + (long)m * 2 * p.N + n) = dg;
-              *reinterpret_cast<bf16x4*>(p.dH + (long)m * 2 * p.N + p.N + n) = du;
-              if (p.A_out) *reinterpret_cast<bf16x4*>(p.A_out + (long)m * p.N + n) = a;
-            }
+            bf16* drow = p.dH + (long)mb * 2 * p.N + nb;
+            stage_store_bf16(stg, dg, drow, 2L * p.N, rows_valid, cols_valid, lane);
+            stage_store_bf16(stg, du, drow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
+            if (p.A_out) stage_store_bf16(stg, a, p.A_out + (long)mb * p.N + nb, p.N, rows_valid, cols_valid, lane);
           }
         }
       }
@@ -413,8 +494,9 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
 template <int BM, int BN, int BKT, int NSTAGE, Layout LA, Layout LB>
 constexpr int dma_smem_bytes() {
-  // the ring plus the per-expert tile table
-  return NSTAGE * (DmaTileBytes<LA, BM, BKT>::value + DmaTileBytes<LB, BN, BKT>::value) + (MOE_MAX_EXPERTS + 8) * 4;
+  // the ring, the per-expert tile table and one epilogue patch per wave (at most 8 waves)
+  return NSTAGE * (DmaTileBytes<LA, BM, BKT>::value + DmaTileBytes<LB, BN, BKT>::value) + (MOE_MAX_EXPERTS + 8) * 4 +
+         8 * STG_BYTES;
 }
 
 }  // namespace mfma
