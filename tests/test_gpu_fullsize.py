@@ -1,0 +1,134 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+Routing, offsets and the permutation are compared in full, bit for bit.  Floating-point tensors
+are compared on samples the oracle can compute one by one: every output row of 192 random tokens
+(forward and backward are row-local given the routing), and for a few experts a 64-column slice of
+the expert width, for which the oracle computes the exact weight-gradient slices from all of the
+expert's rows (SwiGLU is elementwise in the expert width, so slicing it is exact).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from synth.moe_inputs import CONFIGS, bf16_bits, make_inputs
+from tests.gpu_util import DEV, max_norm_err, to_np
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def dev_bf16(a):
+    return torch.from_numpy(bf16_bits(a).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def run_full(cfg, inp):
+    from paper_2505_11432_amd.layer import MoELayer
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm)
+    x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
+    w_r = dev_bf16(np.ascontiguousarray(inp["W_r"].T))
+    bias = torch.from_numpy(inp["bias"]).to(DEV)
+    w1, w2 = dev_bf16(inp["W1"]), dev_bf16(inp["W2"])
+    layer.forward(x, w_r, bias, w1, w2)
+    layer.backward(x, w_r, w1, w2, dy)
+    torch.cuda.synchronize()
+    return layer
+
+
+@pytest.mark.parametrize("name", ["mixtral", "finegrained", "skewed"])
+def test_full_size_sampled_parity(name):
+    cfg = CONFIGS[name]
+    inp = make_inputs(cfg, seed=0)
+    layer = run_full(cfg, inp)
+    T, k, d, f, E = cfg.T, cfg.k, cfg.d, cfg.f, cfg.E
+
+    # ---- router matmul by tolerance, then routing bit-exact on the GPU's own fp32 logits -------
+    z = layer.logits.cpu().numpy()
+    assert max_norm_err(z, O.router_logits(inp["x"], inp["W_r"], inp["bias"])) < 1e-4
+    r = O.route(z, k, cfg.renorm)
+    for nm, got in (("idx", layer.topk_idx), ("counts", layer.counts), ("offsets", layer.offsets),
+                    ("perm", layer.perm), ("inv_perm", layer.inv_perm)):
+        assert np.array_equal(to_np(got), r[nm]), nm
+    assert np.allclose(to_np(layer.topk_w), r["w"], rtol=2e-6, atol=1e-7)
+    assert int(r["counts"].sum()) == T * k
+    print(f"{name}: rows per expert min {r['counts'].min()} max {r['counts'].max()}")
+
+    # ---- sampled tokens: every row-local tensor ------------------------------------------------
+    rng = np.random.default_rng(7)
+    toks = np.sort(rng.choice(T, size=192, replace=False))
+    a_ids = (toks[:, None] * k + np.arange(k)[None, :]).reshape(-1)          # assignments of the sample
+    rows = r["inv_perm"][a_ids].astype(np.int64)                             # their dispatched rows
+    e_of = r["idx"].reshape(-1)[a_ids]
+    order = np.argsort(e_of, kind="stable")
+    rows_s, e_s, a_s = rows[order], e_of[order], a_ids[order]
+    offs = np.concatenate([[0], np.cumsum(np.bincount(e_s, minlength=E))]).astype(np.int32)
+    xp_s = inp["x"][a_s // k].astype(np.float64)
+    H, A, Y = O.expert_ffn_fwd(xp_s, offs, inp["W1"], inp["W2"])
+    w_s = r["w"].reshape(-1)[a_s]
+    dY_s = inp["dy"][a_s // k].astype(np.float64) * w_s[:, None]
+    dxp_s, _, _, dH_s = O.expert_ffn_bwd(xp_s, H, dY_s, offs, inp["W1"], inp["W2"])
+    rows_t = torch.from_numpy(rows_s).to(DEV)
+    errs = {
+        "xp": max_norm_err(to_np(layer.xp[rows_t]), xp_s),
+        "H": max_norm_err(to_np(layer.h_save[rows_t]), H),
+        "Y": max_norm_err(to_np(layer.yp[rows_t]), Y),
+        "dYp": max_norm_err(to_np(layer.d_yp[rows_t]), dY_s),
+        "dxp": max_norm_err(to_np(layer.d_xp[rows_t]), dxp_s),
+    }
+    # token-level results need the sample's rows back in (token, slot) order
+    back = np.empty_like(order)
+    back[order] = np.arange(order.size)
+    Y_ts = Y[back].reshape(len(toks), k, d)
+    dxp_ts = dxp_s[back].reshape(len(toks), k, d)
+    w_ts = r["w"][toks]
+    y_ref = (Y_ts * w_ts[:, :, None]).sum(axis=1)
+    dw_ref = np.einsum("td,tkd->tk", inp["dy"][toks].astype(np.float64), Y_ts)
+    dz_ref = O.route_bwd(z[toks], r["idx"][toks], w_ts, dw_ref, cfg.renorm)
+    dx_ref = dxp_ts.sum(axis=1) + dz_ref @ inp["W_r"].astype(np.float64).T
+    tt = torch.from_numpy(toks).to(DEV)
+    errs["y"] = max_norm_err(to_np(layer.y[tt]), y_ref)
+    errs["dw"] = max_norm_err(to_np(layer.d_topk_w[tt]), dw_ref)
+    errs["dz"] = max_norm_err(to_np(layer.d_logits[tt]), dz_ref)
+    errs["dx"] = max_norm_err(to_np(layer.dx[tt]), dx_ref)
+
+    # ---- weight-gradient slices for a few experts ------------------------------------------------
+    nonempty = np.flatnonzero(r["counts"] > 0)
+    pick = {int(nonempty[np.argmax(r["counts"][nonempty])]), int(nonempty[np.argmin(r["counts"][nonempty])]),
+            int(rng.choice(nonempty))}
+    for e in sorted(pick):
+        lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
+        j0 = int(rng.integers(0, f // 64)) * 64
+        sl = np.r_[j0:j0 + 64, f + j0:f + j0 + 64]
+        W1s = inp["W1"][e:e + 1, sl, :]
+        W2s = inp["W2"][e:e + 1, :, j0:j0 + 64]
+        a_e = r["perm"][lo:hi].astype(np.int64)
+        xp_e = inp["x"][a_e // k].astype(np.float64)
+        dY_e = inp["dy"][a_e // k].astype(np.float64) * r["w"].reshape(-1)[a_e][:, None]
+        off_e = np.array([0, hi - lo], dtype=np.int32)
+        H_e, _, _ = O.expert_ffn_fwd(xp_e, off_e, W1s, W2s)
+        _, dW1s, dW2s, _ = O.expert_ffn_bwd(xp_e, H_e, dY_e, off_e, W1s, W2s)
+        got1 = to_np(layer.d_w1[e][torch.from_numpy(sl).to(DEV)])
+        got2 = to_np(layer.d_w2[e][:, j0:j0 + 64])
+        errs[f"dW1[{e}] ({hi - lo} rows)"] = max_norm_err(got1, dW1s[0])
+        errs[f"dW2[{e}] ({hi - lo} rows)"] = max_norm_err(got2, dW2s[0])
+    for e in range(E):
+        if r["counts"][e] == 0:
+            assert torch.count_nonzero(layer.d_w1[e]) == 0 and torch.count_nonzero(layer.d_w2[e]) == 0
+
+    # router weight gradient in full (cheap)
+    dz_full = to_np(layer.d_logits)
+    errs["dW_r"] = max_norm_err(to_np(layer.d_w_r), (inp["x"].astype(np.float64).T @ dz_full).T)
+    print(name, {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < TOL}
+    assert not bad, bad
+
+
+def test_full_size_is_deterministic():
+    cfg = CONFIGS["finegrained"]
+    inp = make_inputs(cfg, seed=0)
+    a = run_full(cfg, inp)
+    ya, dxa, g1a, g2a = a.y.clone(), a.dx.clone(), a.d_w1.clone(), a.d_w2.clone()
+    del a
+    b = run_full(cfg, inp)
+    assert torch.equal(ya, b.y) and torch.equal(dxa, b.dx)
+    assert torch.equal(g1a, b.d_w1) and torch.equal(g2a, b.d_w2)
