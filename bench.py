@@ -29,6 +29,8 @@ def parse():
     ap.add_argument("--config", default="mixtral", help="synthetic workload name (see synth/moe_inputs.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = T/8)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy, the known-size reference for HBM byte counters")
     return ap.parse_args()
 
 
@@ -97,6 +99,12 @@ def main():
         layer.forward(x, w_r, bias, w1, w2)
         layer.backward(x, w_r, w1, w2, dy)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

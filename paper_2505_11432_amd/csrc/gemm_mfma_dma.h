@@ -172,10 +172,12 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   char* stg = smem + RING_BYTES + TABLE_BYTES + wave * STG_BYTES;      // this wave's epilogue patch
 
   // ---- the tile list ------------------------------------------------------------------------------
-  // Workgroup b runs on XCD b % 8 and each XCD has its own L2, so XCD x is handed the x-th eighth of a
-  // logical tile order in which 32 consecutive tiles (one per CU of the XCD) form a compact block of one
-  // expert: GN adjacent n-tiles for a run of m-tiles.  Those tiles stream the same A and B panels at the
-  // same k, which turns most of their loads into L2 hits.  Workgroup b takes slots b/8, b/8 + G/8, ...
+  // Workgroup b runs on XCD b % 8 and each XCD has its own L2.  The logical tile order is cut into windows
+  // of W = G/8 consecutive tiles (one per CU of an XCD); a window is a compact block of one expert -- GN
+  // adjacent n-tiles for a run of m-tiles -- whose tiles stream the same A and B panels at the same k, so
+  // most of their loads hit in L2.  Windows are dealt round-robin to the XCDs: at any moment the eight
+  // XCDs work on eight neighbouring windows, i.e. the same A panels (shared through the Infinity Cache)
+  // and disjoint B panels, so every weight byte leaves HBM about once.
   const int tiles_n = (p.N + BN_OUT - 1) / BN_OUT;
   const int tiles_m_fixed = (p.M + BM - 1) / BM;              // KSEG / PLAIN
   int total_tiles;
@@ -195,10 +197,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   } else {
     total_tiles = tiles_m_fixed * tiles_n;
   }
-  const int per_xcd = (total_tiles + XCDS - 1) / XCDS;
   const int xcd = blockIdx.x % XCDS;
-  const int slot_step = gridDim.x / XCDS;
-  int slot = blockIdx.x / XCDS;
+  const int window = gridDim.x / XCDS;           // tiles per window = CUs per XCD
+  const int in_window = blockIdx.x / XCDS;
+  int slot = 0;                                  // this XCD's window counter
 
   // tile state
   int e = 0, m0 = 0, m_end = 0, n0 = 0, klen = 0, nk = 0;
@@ -210,8 +212,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
   // Decode slot -> tile and set up this lane's source pointers.  Returns false when the list is exhausted.
   auto open_tile = [&](int sl) -> bool {
-    if (sl >= per_xcd) return false;
-    int l = xcd * per_xcd + sl;
+    int l = (sl * XCDS + xcd) * window + in_window;
     if (l >= total_tiles) return false;
     int mt_e, m_lo, m_hi;
     if constexpr (MODE == ROWSEG) {
@@ -367,7 +368,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
     // ---- hand the ring to the next tile, then write this one out -------------------------------------
     const int ep_e = e, ep_m0 = m0, ep_m_end = m_end, ep_n0 = n0;
-    slot += slot_step;
+    slot += 1;
     __syncthreads();                      // every wave has read its last fragments: the ring is free
     const bool has_next = open_tile(slot);
     if (has_next) issue_prologue();
