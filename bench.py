@@ -19,6 +19,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBPS = 8000.0
+# L2-fill + write-back bytes per grouped-GEMM launch (average of the six launches of one step) on the default
+# workload, from rocprofv3 --pmc FETCH_SIZE (x2.000, the factor a 1 GiB copy gives) and WRITE_SIZE (x1.000);
+# the counter runs are summarised in profiles/grouped_gemm_mixtral_hbm_counters.txt.
+MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"mixtral": 7.83e9}
 
 
 def parse():
@@ -141,7 +145,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",
                      "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": gemm_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                      "flops_per_launch_avg": gemm_flops / 6, "launch_ms_avg": gemm_ms / 6},
         "gemm_tflops": {"fwd": 6.0 * M * cfg.d * cfg.f / per_call["expert_ffn_fwd"] / 1e9,
                         "bwd": 12.0 * M * cfg.d * cfg.f / per_call["expert_ffn_bwd"] / 1e9},
