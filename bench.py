@@ -52,6 +52,22 @@ def to_dev_bf16(a, torch):
     return torch.from_numpy(bits).to("cuda:0").view(torch.bfloat16)
 
 
+def cpu_baseline_fp8(cfg, inp, tokens):
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import moe_oracle as O
+    x, dy = inp["x"][:tokens], inp["dy"][:tokens]
+    t0 = time.perf_counter()
+    z = O.router_logits(x, inp["W_r"], inp["bias"]).astype(np.float32)
+    fwd = O.layer_fwd_fp8(x, z, inp["W1"], inp["W2"], cfg.k, cfg.renorm)
+    O.layer_bwd_fp8(x, z, inp["W1"], inp["W2"], cfg.k, dy, fwd, cfg.renorm)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {tokens} of {cfg.T} tokens, all {cfg.E} experts and full d, d_ff; numpy float64 "
+                      f"forward+backward with the E4M3 casts (weights cast included), {dt:.1f} s"}
+
+
 def cpu_baseline(cfg, inp, tokens):
     """The oracle as it stands, timed on the host cores on the first `tokens` tokens."""
     import numpy as np
@@ -84,7 +100,8 @@ def main():
     from synth.moe_inputs import CONFIGS, make_inputs
 
     cfg = CONFIGS[args.config]
-    assert cfg.dtype == "bf16", "the benchmark workload is a bf16 configuration"
+    assert cfg.dtype in ("bf16", "fp8"), "the benchmark workloads are the bf16 / fp8 configurations"
+    fp8 = cfg.dtype == "fp8"
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
@@ -95,13 +112,19 @@ def main():
     w_r = to_dev_bf16(np.ascontiguousarray(inp["W_r"].T), torch)
     bias = torch.from_numpy(inp["bias"]).to("cuda:0") if cfg.bias != "none" else None
     w1, w2 = to_dev_bf16(inp["W1"], torch), to_dev_bf16(inp["W2"], torch)
-    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm)
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=fp8)
+    if fp8:
+        layer.set_fp8_weights(w1, w2)       # parameters are kept in E4M3 across steps (Section 7): outside the timed loop
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
     def step():
-        layer.forward(x, w_r, bias, w1, w2)
-        layer.backward(x, w_r, w1, w2, dy)
+        if fp8:
+            layer.forward_fp8(x, w_r, bias)
+            layer.backward_fp8(x, w_r, w1, w2, dy)
+        else:
+            layer.forward(x, w_r, bias, w1, w2)
+            layer.backward(x, w_r, w1, w2, dy)
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")     # 1 GiB read + 1 GiB written
@@ -127,7 +150,8 @@ def main():
 
     M = cfg.M
     gemm_flops = 18.0 * M * cfg.d * cfg.f                      # three matmuls per routed token, fwd + 2x bwd
-    gemm_ms = per_call["expert_ffn_fwd"] + per_call["expert_ffn_bwd"]   # exactly the six GEMM launches
+    # bf16 path: these two calls are exactly the six GEMM launches (fp8 path: plus the two row casts in the forward)
+    gemm_ms = per_call["expert_ffn_fwd"] + per_call["expert_ffn_bwd"]
     gemm_tflops = gemm_flops / gemm_ms / 1e9
     row_bytes = (cfg.T + M) * cfg.d * 2.0
     counts = layer.counts.cpu().tolist()
@@ -138,9 +162,10 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d} E={cfg.E} top-{cfg.k} d_ff={cfg.f} "
-                               "SwiGLU, bf16 weights/activations, fp32 accumulate, fp32 weight gradients",
+        "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d} E={cfg.E} top-{cfg.k} d_ff={cfg.f} SwiGLU, " +
+                               ("e4m3 dispatched activations / expert GEMMs / returned outputs forward, bf16 backward, "
+                                if fp8 else "bf16 weights/activations, ") + "fp32 accumulate, fp32 weight gradients",
                    "tokens": cfg.T, "expert_rows": counts},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",
@@ -158,7 +183,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         tokens = args.cpu_tokens or max(cfg.T // 8, 1)
-        out["cpu_baseline"] = cpu_baseline(cfg, inp, tokens)
+        out["cpu_baseline"] = (cpu_baseline_fp8 if fp8 else cpu_baseline)(cfg, inp, tokens)
     print(json.dumps(out))
 
 

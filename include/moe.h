@@ -130,14 +130,17 @@ int moe_gate_grad(const void* dy /*[T,d]*/, moe_dtype dy_dt, const void* yp /*[T
  * act_dt = w_dt = MOE_F8E4M3: xp holds codes with per-row scales xp_scale[M]; w1/w2 hold
  * codes with per-output-channel scales w1_scale [E,2f], w2_scale [E,d]; A is quantised per
  * row before FC2; out_dt = MOE_F8E4M3 writes yp as codes with per-row scales yp_scale[M],
- * out_dt = MOE_BF16 writes it unquantised.  Rows >= offsets[E] are not touched. */
+ * out_dt = MOE_BF16 writes it unquantised.  a_codes_out [M,f] / a_scale_out [M] (both or neither,
+ * fp8 path only) receive the quantised FC2 input, which the backward dequantises and passes as
+ * a_override.  The plain paths touch no row >= offsets[E]; the fp8 path requires offsets[E] = M. */
 int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt,
                        const int32_t* offsets /*[E+1], device*/,
                        const void* w1 /*[E,2f,d]*/, const float* w1_scale,
                        const void* w2 /*[E,d,f]*/, const float* w2_scale, moe_dtype w_dt,
                        int M, int d, int E, int f,
                        void* h_save /*[M,2f]*/, void* yp /*[M,d]*/, float* yp_scale,
-                       moe_dtype out_dt, void* workspace, size_t ws_bytes, void* stream);
+                       moe_dtype out_dt, uint8_t* a_codes_out, float* a_scale_out,
+                       void* workspace, size_t ws_bytes, void* stream);
 
 /* Gradients of the expert FFN (Section 4.1, Fig. 8b: the FC2 backward takes the recomputed
  * FC2 input and the gradient of the FC2 output).  dt = MOE_F32 | MOE_BF16 for xp, h_save,

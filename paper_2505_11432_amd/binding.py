@@ -53,7 +53,7 @@ def _load() -> ctypes.CDLL:
         "moe_dispatch": (I, [P, P, I, P, P, I, I, I, P, P, P]),
         "moe_combine": (I, [P, P, I, P, P, I, I, I, P, I, P]),
         "moe_gate_grad": (I, [P, I, P, P, I, P, I, I, I, P, P]),
-        "moe_expert_ffn_fwd": (I, [P, P, I, P, P, P, P, P, I, I, I, I, I, P, P, P, I, P, Z, P]),
+        "moe_expert_ffn_fwd": (I, [P, P, I, P, P, P, P, P, I, I, I, I, I, P, P, P, I, P, P, P, Z, P]),
         "moe_expert_ffn_bwd": (I, [P, P, P, P, P, P, P, I, I, I, I, I, P, P, P, I, I, P, Z, P]),
         "moe_quant_fp8": (I, [P, I, I, I, I, P, P, P]),
         "moe_dequant_fp8": (I, [P, P, I, I, I, P, I, P]),
@@ -150,13 +150,14 @@ def moe_gate_grad(dy, yp, yp_scale, inv_perm, k, d_topk_w):
                                                _stream()))
 
 
-def moe_expert_ffn_fwd(xp, xp_scale, offsets, w1, w1_scale, w2, w2_scale, h_save, yp, yp_scale, workspace):
+def moe_expert_ffn_fwd(xp, xp_scale, offsets, w1, w1_scale, w2, w2_scale, h_save, yp, yp_scale, workspace,
+                       a_codes_out=None, a_scale_out=None):
     M, d = xp.shape
     E, two_f, _ = w1.shape
     _check("moe_expert_ffn_fwd", _lib.moe_expert_ffn_fwd(
         _p(xp), _p(xp_scale), dtype_code(xp.dtype), _p(offsets), _p(w1), _p(w1_scale), _p(w2), _p(w2_scale),
         dtype_code(w1.dtype), M, d, E, two_f // 2, _p(h_save), _p(yp), _p(yp_scale), dtype_code(yp.dtype),
-        _p(workspace), workspace.numel() * workspace.element_size(), _stream()))
+        _p(a_codes_out), _p(a_scale_out), _p(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def moe_expert_ffn_bwd(xp, h_save, d_yp, a_override, offsets, w1, w2, d_xp, d_w1, d_w2, accumulate, workspace):

@@ -62,6 +62,29 @@ static int ffn_fwd_bf16(const void* xp, const int32_t* offsets, const void* w1, 
   return mfma_rowseg_nt(A, w2, (long)d * f, offsets, M, d, f, E, yp, s);
 }
 
+// fp8 (Section 5 / Section 7 "FP8 training"): e4m3 operands with per-token and per-output-channel scales on
+// the 32x32x64 MFMA; the SwiGLU output is quantised per token before FC2; yp optionally per token as well.
+static int ffn_fwd_fp8(const void* xp, const float* xp_scale, const int32_t* offsets, const void* w1,
+                       const float* w1_scale, const void* w2, const float* w2_scale, int M, int d, int E, int f,
+                       void* h_save, void* yp, float* yp_scale, moe_dtype out_dt, uint8_t* a_codes_out,
+                       float* a_scale_out, void* ws, hipStream_t s) {
+  char* base = static_cast<char*>(ws);
+  void* A_bf16 = base;
+  uint8_t* a_codes = a_codes_out ? a_codes_out : reinterpret_cast<uint8_t*>(base + align_up((size_t)M * f * 2, 256));
+  float* a_scale = a_scale_out ? a_scale_out
+                               : reinterpret_cast<float*>(base + align_up((size_t)M * f * 2, 256) + align_up((size_t)M * f, 256));
+  void* y_bf16 = base + align_up((size_t)M * f * 2, 256) + align_up((size_t)M * f, 256) + align_up((size_t)M * 4, 256);
+  int rc = mfma_fc1_swiglu_fp8(xp, xp_scale, w1, w1_scale, offsets, M, d, E, f, h_save, A_bf16, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_quant_fp8(A_bf16, MOE_BF16, M, f, MOE_Q_ROW, a_codes, a_scale, s);
+  if (rc != MOE_OK) return rc;
+  void* y_dst = out_dt == MOE_F8E4M3 ? y_bf16 : yp;
+  rc = mfma_rowseg_nt_fp8(a_codes, a_scale, w2, w2_scale, (long)d * f, offsets, M, d, f, E, y_dst, s);
+  if (rc != MOE_OK) return rc;
+  if (out_dt == MOE_F8E4M3) rc = launch_quant_fp8(y_bf16, MOE_BF16, M, d, MOE_Q_ROW, static_cast<uint8_t*>(yp), yp_scale, s);
+  return rc;
+}
+
 static int ffn_bwd_bf16(const void* xp, const void* h_save, const void* d_yp, const void* a_override,
                         const int32_t* offsets, const void* w1, const void* w2, int M, int d, int E, int f,
                         void* d_xp, void* d_w1, void* d_w2, moe_dtype grad_dt, int accumulate, void* ws,
@@ -258,7 +281,7 @@ int moe_gate_grad(const void* dy, moe_dtype dy_dt, const void* yp, const float* 
 int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt, const int32_t* offsets,
                        const void* w1, const float* w1_scale, const void* w2, const float* w2_scale, moe_dtype w_dt,
                        int M, int d, int E, int f, void* h_save, void* yp, float* yp_scale, moe_dtype out_dt,
-                       void* workspace, size_t ws_bytes, void* stream) {
+                       uint8_t* a_codes_out, float* a_scale_out, void* workspace, size_t ws_bytes, void* stream) {
   if (M < 0 || d <= 0 || f <= 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
   if (d % 16 != 0 || f % 16 != 0) return MOE_ERR_UNSUPPORTED;
   if (act_dt != w_dt) return MOE_ERR_UNSUPPORTED;
@@ -275,7 +298,14 @@ int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt, 
       !aligned16(workspace))
     return MOE_ERR_UNSUPPORTED;
   if (!workspace || ws_bytes < ffn_fwd_ws_bytes(M, d, f, act_dt, out_dt)) return MOE_ERR_WORKSPACE;
-  if (fp8) return MOE_ERR_UNSUPPORTED;
+  if ((a_codes_out != nullptr) != (a_scale_out != nullptr)) return MOE_ERR_INVALID;
+  if (!fp8 && a_codes_out) return MOE_ERR_INVALID;
+  if (fp8) {
+    if (!aligned16(a_codes_out)) return MOE_ERR_UNSUPPORTED;
+    // rows at or beyond offsets[E] are never read by the GEMMs, but the row quantisers walk all M rows
+    return ffn_fwd_fp8(xp, xp_scale, offsets, w1, w1_scale, w2, w2_scale, M, d, E, f, h_save, yp, yp_scale, out_dt,
+                       a_codes_out, a_scale_out, workspace, as_stream(stream));
+  }
   if (act_dt == MOE_BF16)
     return ffn_fwd_bf16(xp, offsets, w1, w2, M, d, E, f, h_save, yp, workspace, as_stream(stream));
   return ffn_fwd_plain(xp, offsets, w1, w2, act_dt, M, d, E, f, h_save, yp, workspace, as_stream(stream));

@@ -23,14 +23,15 @@ int persistent_grid(int* grid) {
   return MOE_OK;
 }
 
-template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC>
+template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC,
+          typename TIN = bf16>
 int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
   if (tiles_upper_bound <= 0) return MOE_OK;
   int blocks = 0;
   const int rc = persistent_grid(&blocks);
   if (rc != MOE_OK) return rc;
-  auto kern = grouped_gemm_dma_kernel<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC>;
-  constexpr int smem = dma_smem_bytes<BM, BN, BKT, NS, LA, LB>();
+  auto kern = grouped_gemm_dma_kernel<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC, 0, TIN>;
+  constexpr int smem = dma_smem_bytes<BM, BN, BKT, NS, LA, LB, (int)sizeof(TIN)>();
   static bool configured = false;    // one flag per instantiation; the attribute is per function
   if (!configured) {
     MOE_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
@@ -100,6 +101,30 @@ int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int
   const long blocks = (long)E * cdiv(Mo, 256) * cdiv(N, 256);
   if (c_dt == MOE_F32) return launch<256, 256, 32, 4, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, float>(a, blocks, s);
   return launch<256, 256, 32, 4, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, bf16>(a, blocks, s);
+}
+
+// e4m3 operands (codes with per-row / per-output-channel scales), 32x32x64 f8f6f4 MFMA, bf16 results:
+// H[M,2f] = (xp*sx) * (w1[e]*sw1)^T, A_out = SwiGLU(H)
+int mfma_fc1_swiglu_fp8(const void* xp, const float* xp_scale, const void* w1, const float* w1_scale,
+                        const int32_t* offsets, int M, int d, int E, int f, void* H, void* A_out, hipStream_t s) {
+  Args a{};
+  a.A = xp; a.lda = d;
+  a.B = w1; a.ldb = d; a.b_es = 2L * f * d;
+  a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d; a.f = f;
+  a.H = (bf16*)H; a.A_out = (bf16*)A_out;
+  a.row_scale = xp_scale; a.col_scale = w1_scale; a.cs_es = 2L * f;
+  return launch<256, 256, 128, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_SWIGLU, bf16, uint8_t>(a, rowseg_blocks(M, E, f, 256, 128), s);
+}
+
+// C[M,N] = (A*sa) * (W[e]*sw)^T, bf16 out
+int mfma_rowseg_nt_fp8(const void* A, const float* a_scale, const void* W, const float* w_scale, long w_es,
+                       const int32_t* offsets, int M, int N, int K, int E, void* C, hipStream_t s) {
+  Args a{};
+  a.A = A; a.lda = K;
+  a.B = W; a.ldb = K; a.b_es = w_es;
+  a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
+  a.row_scale = a_scale; a.col_scale = w_scale; a.cs_es = N;
+  return launch<256, 256, 128, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_STORE, bf16, uint8_t>(a, rowseg_blocks(M, E, N, 256, 256), s);
 }
 
 // logits[T,E] = x[T,d] * w_r[E,d]^T (+ bias), fp32 out

@@ -41,8 +41,8 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int ROWS, int BKT> struct KTile {        // K-major [ROWS][BKT] bf16
-  static constexpr int ROW_BYTES = BKT * 2, CPR = ROW_BYTES / 16, RPL = 256 / ROW_BYTES;
+template <int ROWS, int BKT, int ESZ = 2> struct KTile {        // K-major [ROWS][BKT] of ESZ-byte elements
+  static constexpr int ROW_BYTES = BKT * ESZ, CPR = ROW_BYTES / 16, RPL = 256 / ROW_BYTES;
   static constexpr int BYTES = ROWS * ROW_BYTES;
   static constexpr int ROWS_PER_DMA = 1024 / ROW_BYTES;
   __device__ static __forceinline__ int swz(int row) { return (row / RPL) % CPR; }
@@ -56,9 +56,12 @@ template <int COLS, int BKT> struct MNTile {       // M/N-major [BKT][COLS] bf16
   __device__ static __forceinline__ int swz(int krow) { return (krow & 3) << 2; }
 };
 
-template <Layout L, int EXTENT, int BKT> struct DmaTileBytes;
-template <int EXTENT, int BKT> struct DmaTileBytes<KMAJOR, EXTENT, BKT> { static constexpr int value = KTile<EXTENT, BKT>::BYTES; };
-template <int EXTENT, int BKT> struct DmaTileBytes<MNMAJOR, EXTENT, BKT> { static constexpr int value = MNTile<EXTENT, BKT>::BYTES; };
+template <Layout L, int EXTENT, int BKT, int ESZ = 2> struct DmaTileBytes;
+template <int EXTENT, int BKT, int ESZ> struct DmaTileBytes<KMAJOR, EXTENT, BKT, ESZ> { static constexpr int value = KTile<EXTENT, BKT, ESZ>::BYTES; };
+template <int EXTENT, int BKT, int ESZ> struct DmaTileBytes<MNMAJOR, EXTENT, BKT, ESZ> {
+  static_assert(ESZ == 2, "M/N-major tiles exist for bf16 only");
+  static constexpr int value = MNTile<EXTENT, BKT>::BYTES;
+};
 
 template <Layout L, int EXTENT, int BKT>
 __device__ __forceinline__ bf16x8 read_frag_dma(const char* tile, int base, int kk, int lane) {
@@ -141,18 +144,34 @@ __device__ __forceinline__ void stage_store_f32(char* stg, const f32x16& acc, fl
   }
 }
 
+// e4m3 fragment (32 rows x 64 k, 32 bytes per lane) for the 32x32x64 f8f6f4 MFMA out of a K-major tile.
+template <int EXTENT, int BKT>
+__device__ __forceinline__ i32x8 read_frag_fp8(const char* tile, int base, int kk, int lane) {
+  using TL = KTile<EXTENT, BKT, 1>;
+  const int row = base + (lane & 31);
+  const int c0 = kk * 4 + ((lane >> 5) << 1);
+  const uint4 lo = *reinterpret_cast<const uint4*>(tile + TL::offset(row, c0));
+  const uint4 hi = *reinterpret_cast<const uint4*>(tile + TL::offset(row, c0 + 1));
+  i32x8 r = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+  return r;
+}
+
 template <int BM, int BN, int BKT, int NSTAGE, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC,
-          int PROBE = 0>   // PROBE (tuning only): 1 = no global loads, 2 = no LDS reads / MFMAs, 3 = all tiles load tile 0
+          int PROBE = 0, typename TIN = bf16>   // TIN = uint8_t: e4m3 codes, K-major operands only   // PROBE (tuning only): 1 = no global loads, 2 = no LDS reads / MFMAs, 3 = all tiles load tile 0
 __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) {
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int A_BYTES = DmaTileBytes<LA, BM, BKT>::value, B_BYTES = DmaTileBytes<LB, BN, BKT>::value;
+  constexpr int ESZ = sizeof(TIN);
+  constexpr bool FP8 = ESZ == 1;
+  constexpr int CHUNK = 16 / ESZ;                     // elements per 16-byte chunk
+  static_assert(!FP8 || (LA == KMAJOR && LB == KMAJOR), "e4m3 operands are K-major");
+  constexpr int A_BYTES = DmaTileBytes<LA, BM, BKT, ESZ>::value, B_BYTES = DmaTileBytes<LB, BN, BKT, ESZ>::value;
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
   constexpr int A_DMA = A_BYTES / 1024 / NW, B_DMA = B_BYTES / 1024 / NW;     // loads per wave per stage
   constexpr int LOADS = A_DMA + B_DMA;
-  constexpr int KK = BKT / 16;
+  constexpr int KK = FP8 ? BKT / 64 : BKT / 16;    // MFMA sub-steps per k-step
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int GN = 4, XCDS = 8;
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile does not split over the waves");
@@ -207,8 +226,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   const char* a_src[A_DMA];
   const char* b_src[B_DMA];
   int a_k[A_DMA], b_k[B_DMA];       // k coordinate (relative to the k-step start) this lane's chunk begins at
-  const long a_step = (LA == KMAJOR) ? (long)BKT * 2 : (long)BKT * p.lda * 2;   // bytes per k-step
-  const long b_step = (LB == KMAJOR) ? (long)BKT * 2 : (long)BKT * p.ldb * 2;
+  const long a_step = (LA == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.lda * ESZ;   // bytes per k-step
+  const long b_step = (LB == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.ldb * ESZ;
 
   // Decode slot -> tile and set up this lane's source pointers.  Returns false when the list is exhausted.
   auto open_tile = [&](int sl) -> bool {
@@ -243,21 +262,21 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     else { k_begin = 0; k_end = p.K; }
     klen = k_end - k_begin;
     nk = (klen + BKT - 1) / BKT;
-    const bf16* __restrict__ Ag = p.A;
-    const bf16* __restrict__ Bg = p.B + (long)e * p.b_es;
+    const TIN* __restrict__ Ag = static_cast<const TIN*>(p.A);
+    const TIN* __restrict__ Bg = static_cast<const TIN*>(p.B) + (long)e * p.b_es;
     const int real_m0 = m0, real_n0 = n0;
-    if constexpr (PROBE == 3) { m0 = 0; n0 = 0; Bg = p.B; }      // every tile loads the same panels (all L2 hits)
+    if constexpr (PROBE == 3) { m0 = 0; n0 = 0; Bg = static_cast<const TIN*>(p.B); }      // every tile loads the same panels (all L2 hits)
     // load j of the wave covers DMA slot q = wave + j*NW of the tile (1 KiB of LDS each)
 #pragma unroll
     for (int j = 0; j < A_DMA; ++j) {
       const int q = wave + j * NW;
       if constexpr (LA == KMAJOR) {
-        using TL = KTile<BM, BKT>;
+        using TL = KTile<BM, BKT, ESZ>;
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
         const int lc = (lane % TL::CPR) ^ TL::swz(row);
         const int gr = min(m0 + row, p.M - 1);
-        a_src[j] = reinterpret_cast<const char*>(Ag + (long)gr * p.lda + k_begin + lc * 8);
-        a_k[j] = lc * 8;
+        a_src[j] = reinterpret_cast<const char*>(Ag + (long)gr * p.lda + k_begin + lc * CHUNK);
+        a_k[j] = lc * CHUNK;
       } else {
         using TL = MNTile<BM, BKT>;
         const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
@@ -271,7 +290,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     for (int j = 0; j < B_DMA; ++j) {
       const int q = wave + j * NW;
       if constexpr (LB == KMAJOR) {
-        using TL = KTile<BN, BKT>;
+        using TL = KTile<BN, BKT, ESZ>;
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
         const int lc = (lane % TL::CPR) ^ TL::swz(row);
         int gr;
@@ -282,8 +301,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         } else {
           gr = min(n0 + row, p.N - 1);
         }
-        b_src[j] = reinterpret_cast<const char*>(Bg + (long)gr * p.ldb + k_begin + lc * 8);
-        b_k[j] = lc * 8;
+        b_src[j] = reinterpret_cast<const char*>(Bg + (long)gr * p.ldb + k_begin + lc * CHUNK);
+        b_k[j] = lc * CHUNK;
       } else {
         using TL = MNTile<BN, BKT>;
         const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
@@ -349,16 +368,30 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       if constexpr (PROBE == 2) continue;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        bf16x8 af[TM], bfr[TN];
+        if constexpr (FP8) {
+          // 32x32x64 e4m3 x e4m3 (format selectors 0, 0), both block scales 2^0 (E8M0 code 127)
+          i32x8 af[TM], bfr[TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[i] = read_frag_dma<LA, BM, BKT>(at, wm * WTM + i * 32, kk, lane);
+          for (int i = 0; i < TM; ++i) af[i] = read_frag_fp8<BM, BKT>(at, wm * WTM + i * 32, kk, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[j] = read_frag_dma<LB, BN, BKT>(bt, wn * WTN + j * 32, kk, lane);
+          for (int j = 0; j < TN; ++j) bfr[j] = read_frag_fp8<BN, BKT>(bt, wn * WTN + j * 32, kk, lane);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+          for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[j], af[i], acc[i][j], 0, 0, 0, 127, 0, 127);
+        } else {
+          bf16x8 af[TM], bfr[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) af[i] = read_frag_dma<LA, BM, BKT>(at, wm * WTM + i * 32, kk, lane);
+#pragma unroll
+          for (int j = 0; j < TN; ++j) bfr[j] = read_frag_dma<LB, BN, BKT>(bt, wn * WTN + j * 32, kk, lane);
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        }
       }
     }
     if (p.clk_out && tid == 0 && blockIdx.x < 2048) {
@@ -375,6 +408,32 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     {
       const int e = ep_e, m0 = ep_m0, m_end = ep_m_end, n0 = ep_n0;
       (void)e;
+      if constexpr (FP8) {
+        // dequantise: output = acc * scale of the row (token) * scale of the output channel
+        const int lrow = lane & 31, lcol = (lane >> 5) << 2;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const int m = min(m0 + wm * WTM + i * 32 + lrow, p.M - 1);
+          const float rs = p.row_scale ? p.row_scale[m] : 1.f;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              int n;
+              if constexpr (EPI == EPI_SWIGLU) {
+                const int nn = min(n0 + ((wn * WTN + (j & ~1) * 32) >> 1) + q * 8 + lcol, p.f - 4);
+                n = (j & 1) ? p.f + nn : nn;
+              } else {
+                n = min(n0 + wn * WTN + j * 32 + q * 8 + lcol, p.N - 4);
+              }
+              f32x4 cs = {1.f, 1.f, 1.f, 1.f};
+              if (p.col_scale) cs = *reinterpret_cast<const f32x4*>(p.col_scale + (long)e * p.cs_es + n);
+#pragma unroll
+              for (int t = 0; t < 4; ++t) acc[i][j][4 * q + t] *= rs * cs[t];
+            }
+          }
+        }
+      }
       // every 32x32 MFMA tile goes through the wave's LDS patch (see stage_store_* above)
       if constexpr (EPI == EPI_STORE) {
 #pragma unroll
@@ -493,10 +552,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   }
 }
 
-template <int BM, int BN, int BKT, int NSTAGE, Layout LA, Layout LB>
+template <int BM, int BN, int BKT, int NSTAGE, Layout LA, Layout LB, int ESZ = 2>
 constexpr int dma_smem_bytes() {
   // the ring, the per-expert tile table and one epilogue patch per wave (at most 8 waves)
-  return NSTAGE * (DmaTileBytes<LA, BM, BKT>::value + DmaTileBytes<LB, BN, BKT>::value) + (MOE_MAX_EXPERTS + 8) * 4 +
+  return NSTAGE * (DmaTileBytes<LA, BM, BKT, ESZ>::value + DmaTileBytes<LB, BN, BKT, ESZ>::value) + (MOE_MAX_EXPERTS + 8) * 4 +
          8 * STG_BYTES;
 }
 

@@ -93,6 +93,10 @@ int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offs
 int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int N, int E, void* C, moe_dtype c_dt,
                int accumulate, hipStream_t s);
 
+int mfma_fc1_swiglu_fp8(const void* xp, const float* xp_scale, const void* w1, const float* w1_scale,
+                        const int32_t* offsets, int M, int d, int E, int f, void* H, void* A_out, hipStream_t s);
+int mfma_rowseg_nt_fp8(const void* A, const float* a_scale, const void* W, const float* w_scale, long w_es,
+                       const int32_t* offsets, int M, int N, int K, int E, void* C, hipStream_t s);
 int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, int d, int E, float* logits,
                     hipStream_t s);
 size_t router_bwd_ws_bytes(int T, int d, int E);

@@ -48,7 +48,10 @@ class MoELayer:
             self.yp = torch.empty((M, d), **u8)
             self.yp_scale = torch.empty((M,), **f32)
             self.xp_deq = torch.empty((M, d), **act)
+            self.a_codes = torch.empty((M, f), **u8)
+            self.a_scale = torch.empty((M,), **f32)
             self.a_deq = torch.empty((M, f), **act)
+            self.w1_codes = self.w1_scale = self.w2_codes = self.w2_scale = None
             self.dy_codes = torch.empty((T, d), **u8)
             self.dy_scale = torch.empty(((T + 127) // 128, d), **f32)
             self.dy_deq = torch.empty((T, d), **act)
@@ -76,6 +79,57 @@ class MoELayer:
         """Total milliseconds per call name over everything recorded so far (synchronises)."""
         torch.cuda.synchronize()
         return {k: sum(a.elapsed_time(b) for a, b in v) for k, v in (self.timers or {}).items()}
+
+    def set_fp8_weights(self, w1, w2):
+        """Per-output-channel E4M3 copies of the expert weights (kept across steps: the paper stores
+        parameters in FP8, Section 7, so this cast is outside the timed loop)."""
+        E, two_f, d = w1.shape
+        f = two_f // 2
+        dev = dict(device=w1.device)
+        self.w1_codes = torch.empty((E, two_f, d), dtype=torch.uint8, **dev)
+        self.w1_scale = torch.empty((E, two_f), dtype=torch.float32, **dev)
+        self.w2_codes = torch.empty((E, d, f), dtype=torch.uint8, **dev)
+        self.w2_scale = torch.empty((E, d), dtype=torch.float32, **dev)
+        B.moe_quant_fp8(w1.view(E * two_f, d), B.Q_ROW, self.w1_codes.view(E * two_f, d), self.w1_scale.view(-1))
+        B.moe_quant_fp8(w2.view(E * d, f), B.Q_ROW, self.w2_codes.view(E * d, f), self.w2_scale.view(-1))
+
+    def forward_fp8(self, x, w_r, bias, logits=None):
+        """Forward with E4M3 dispatched activations and returned expert outputs (per-token scales), e4m3 expert
+        GEMMs, gate weight applied after FC2 on the dequantised outputs."""
+        c = self._call
+        if logits is None:
+            c("router_fwd", B.moe_router_fwd, x, w_r, bias, self.logits)
+        else:
+            self.logits.copy_(logits)
+        c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
+          self.offsets, self.perm, self.inv_perm, self.workspace)
+        c("quant_x", B.moe_quant_fp8, x, B.Q_ROW, self.x_codes, self.x_scale)
+        c("dispatch", B.moe_dispatch, self.x_codes, self.x_scale, self.inv_perm, None, self.k, self.xp, self.xp_scale)
+        c("expert_ffn_fwd", B.moe_expert_ffn_fwd, self.xp, self.xp_scale, self.offsets, self.w1_codes, self.w1_scale,
+          self.w2_codes, self.w2_scale, self.h_save, self.yp, self.yp_scale, self.workspace, self.a_codes,
+          self.a_scale)
+        c("combine", B.moe_combine, self.yp, self.yp_scale, self.inv_perm, self.topk_w, self.k, self.y)
+        return self.y
+
+    def backward_fp8(self, x, w_r, w1, w2, dy, with_router: bool = True):
+        """Straight-through backward of forward_fp8: dy cast per channel in 128-token groups, bf16 GEMMs on the
+        master weights, the saved H and the dequantised xp / A that the forward GEMMs consumed."""
+        c = self._call
+        c("quant_dy", B.moe_quant_fp8, dy, B.Q_COLGROUP128, self.dy_codes, self.dy_scale)
+        c("dequant_dy", B.moe_dequant_fp8, self.dy_codes, self.dy_scale, B.Q_COLGROUP128, self.dy_deq)
+        c("gate_grad", B.moe_gate_grad, self.dy_deq, self.yp, self.yp_scale, self.inv_perm, self.k, self.d_topk_w)
+        c("dispatch_bwd_of_combine", B.moe_dispatch, self.dy_deq, None, self.inv_perm, self.topk_w.view(-1), self.k,
+          self.d_yp, None)
+        c("dequant_xp", B.moe_dequant_fp8, self.xp, self.xp_scale, B.Q_ROW, self.xp_deq)
+        c("dequant_a", B.moe_dequant_fp8, self.a_codes, self.a_scale, B.Q_ROW, self.a_deq)
+        c("expert_ffn_bwd", B.moe_expert_ffn_bwd, self.xp_deq, self.h_save, self.d_yp, self.a_deq, self.offsets, w1,
+          w2, self.d_xp, self.d_w1, self.d_w2, 0, self.workspace)
+        c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, None, self.k, self.dx)
+        c("route_bwd", B.moe_route_bwd, self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E,
+          self.renorm, self.d_logits)
+        if with_router:
+            c("router_bwd", B.moe_router_bwd, x, w_r, self.d_logits, self.d_w_r, self.dx, self.workspace)
+        return self.dx
 
     # ---- forward: Fig. 8a ------------------------------------------------------------------
     def forward(self, x, w_r, bias, w1, w2, logits=None):

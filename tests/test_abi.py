@@ -77,9 +77,9 @@ def test_argument_errors_without_gpu(lib):
     assert lib.moe_combine(fake, null, 2, fake, null, 4, 2, 32, fake, 1, null) == -1
     # expert ffn: E out of range, f misaligned, workspace too small
     Z = ctypes.c_size_t
-    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 0, 32, fake, fake, null, 1, fake, Z(1 << 30), null) == -1
-    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 4, 24, fake, fake, null, 1, fake, Z(1 << 30), null) == -2
-    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 4, 32, fake, fake, null, 1, fake, Z(16), null) == -3
+    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 0, 32, fake, fake, null, 1, null, null, fake, Z(1 << 30), null) == -1
+    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 4, 24, fake, fake, null, 1, null, null, fake, Z(1 << 30), null) == -2
+    assert lib.moe_expert_ffn_fwd(fake, null, 1, fake, fake, null, fake, null, 1, 64, 32, 4, 32, fake, fake, null, 1, null, null, fake, Z(16), null) == -3
     assert lib.moe_expert_ffn_bwd(fake, fake, fake, null, fake, fake, fake, 1, 64, 32, 4, 32, fake, fake, fake, 0, 0, fake, Z(16), null) == -3
     assert lib.moe_expert_ffn_bwd(fake, fake, fake, null, fake, fake, fake, 0, 64, 32, 4, 32, fake, fake, fake, 1, 0, fake, Z(1 << 30), null) == -2
     # quant: bad mode, misaligned columns

@@ -266,3 +266,102 @@ def test_quant_fp8_bit_exact(B, src_dtype, rows, cols):
         out = torch.empty((rows, cols), dtype=torch.float32, device=DEV)
         B.moe_dequant_fp8(codes, scales, mode, out)
         assert np.array_equal(to_np(out), dq(c_ref, s_ref).astype(np.float32).astype(np.float64)), mode
+
+
+FP8_CASES = [
+    MoEConfig("fp8_ragged", T=611, d=272, E=6, k=2, f=336, dtype="bf16", w_std=0.06, wr_std=0.5),
+    MoEConfig("fp8_tiles", T=700, d=512, E=4, k=2, f=640, dtype="bf16", w_std=0.05, wr_std=0.3),
+]
+
+
+@pytest.mark.parametrize("cfg", FP8_CASES, ids=lambda c: c.name)
+def test_layer_fp8_forward_backward(B, cfg):
+    """Config-5 reading: e4m3 dispatch / expert GEMMs / returned outputs forward, straight-through bf16 backward.
+
+    A cast turns floating point into integer codes, and a code can flip when its input differs in the last bit,
+    which moves that element by a whole e4m3 step (up to 32/448 = 7.1 % of the row maximum).  So the chain is
+    checked stage by stage with both sides taking every cast decision from the same input: each cast is compared
+    bit for bit with the oracle's quantiser applied to the kernel's own pre-cast tensor, and each floating-point
+    stage is compared with the oracle fed the kernel's codes.  The end-to-end distance is printed as information."""
+    from paper_2505_11432_amd.layer import MoELayer
+    inp = make_inputs(cfg, seed=3)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    if cfg.name == "fp8_ragged":
+        z[:, 4] = -1e4
+    td = torch.bfloat16
+    T, k, d, f, E = cfg.T, cfg.k, cfg.d, cfg.f, cfg.E
+    layer = MoELayer(T, d, E, k, f, dtype=td, fp8=True)
+    x, dy = to_dev(inp["x"], td), to_dev(inp["dy"], td)
+    wr = to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"], td), to_dev(inp["W2"], td)
+    layer.set_fp8_weights(w1, w2)
+    layer.forward_fp8(x, wr, None, logits=to_dev(z))
+    layer.backward_fp8(x, wr, w1, w2, dy, with_router=False)
+    # the same expert FFN with unquantised bf16 output: the pre-cast Y
+    y_pre = torch.empty((layer.M, d), dtype=td, device=DEV)
+    h2 = torch.empty_like(layer.h_save)
+    B.moe_expert_ffn_fwd(layer.xp, layer.xp_scale, layer.offsets, layer.w1_codes, layer.w1_scale, layer.w2_codes,
+                         layer.w2_scale, h2, y_pre, None, layer.workspace)
+    torch.cuda.synchronize()
+    fwd = O.layer_fwd_fp8(inp["x"], z, inp["W1"], inp["W2"], k)
+    assert np.array_equal(to_np(layer.perm), fwd["perm"])
+    tol = TOL["fp8"]
+
+    # (1) casts of inputs and weights, and the dispatch of codes: bit-exact
+    c1, s1 = O.quant_rows(inp["W1"].reshape(-1, d))
+    c2, s2 = O.quant_rows(inp["W2"].reshape(-1, f))
+    assert np.array_equal(to_np(layer.w1_codes).reshape(-1, d), c1) and np.array_equal(to_np(layer.w2_codes).reshape(-1, f), c2)
+    assert np.array_equal(to_np(layer.w1_scale).reshape(-1).astype(np.float32), s1)
+    assert np.array_equal(to_np(layer.w2_scale).reshape(-1).astype(np.float32), s2)
+    cx, sx = O.quant_rows(inp["x"])
+    assert np.array_equal(to_np(layer.x_codes), cx) and np.array_equal(to_np(layer.x_scale).astype(np.float32), sx)
+    assert np.array_equal(to_np(layer.xp), cx[fwd["perm"] // k])
+    assert np.array_equal(to_np(layer.xp_scale).astype(np.float32), sx[fwd["perm"] // k])
+    errs = {}
+    # (2) FC1 on identical codes
+    H_gpu = to_np(layer.h_save)
+    errs["H"] = max_norm_err(H_gpu, fwd["H"])
+    assert torch.equal(h2, layer.h_save)
+    # (3) cast of the SwiGLU output: quantiser applied to A recomputed from the kernel's own H
+    A_pre = bf16_round((O.silu(H_gpu[:, :f]) * H_gpu[:, f:]).astype(np.float32))
+    ca, sa = O.quant_rows(A_pre)
+    ca_gpu, sa_gpu = to_np(layer.a_codes), to_np(layer.a_scale).astype(np.float32)
+    diff = ca_gpu.astype(np.int32) != ca.astype(np.int32)
+    assert diff.mean() < 5e-3, f"A codes differ on {diff.mean():.2%} of the elements"
+    assert np.all(np.abs((ca_gpu & 0x7F).astype(np.int32) - (ca & 0x7F).astype(np.int32))[diff] <= 1)
+    assert np.allclose(sa_gpu, sa, rtol=2 ** -7)
+    # (4) FC2 on the kernel's A codes, then the cast of Y: bit-exact on the kernel's own pre-cast Y
+    W1h, W2h = O.quant_weights(inp["W1"], inp["W2"])
+    A_hat = O.dequant_rows(ca_gpu, sa_gpu)
+    Y_ref = np.zeros((layer.M, d))
+    for e in range(E):
+        lo, hi = int(fwd["offsets"][e]), int(fwd["offsets"][e + 1])
+        Y_ref[lo:hi] = A_hat[lo:hi] @ W2h[e].T
+    errs["Y (bf16 out)"] = max_norm_err(to_np(y_pre), Y_ref)
+    cy, sy = O.quant_rows(to_np(y_pre).astype(np.float32))
+    assert np.array_equal(to_np(layer.yp), cy) and np.array_equal(to_np(layer.yp_scale).astype(np.float32), sy)
+    # (5) combine of the dequantised outputs
+    Y_hat = O.dequant_rows(cy, sy)
+    errs["y"] = max_norm_err(to_np(layer.y), O.combine(Y_hat, fwd["inv_perm"], fwd["w"], T, k))
+    # (6) backward: dy cast bit-exact, then the oracle's backward on the kernel's codes
+    cdy, sdy = O.quant_colgroup128(inp["dy"])
+    assert np.array_equal(to_np(layer.dy_codes), cdy) and np.array_equal(to_np(layer.dy_scale).astype(np.float32), sdy)
+    fwd_tf = dict(fwd)
+    fwd_tf["A"], fwd_tf["Y"] = A_hat, Y_hat
+    bwd = O.layer_bwd_fp8(inp["x"], z, inp["W1"], inp["W2"], k, inp["dy"], fwd_tf)
+    errs["dw"] = max_norm_err(to_np(layer.d_topk_w), bwd["dw"])
+    errs["dx"] = max_norm_err(to_np(layer.dx), bwd["dx"])
+    dW1, dW2 = to_np(layer.d_w1), to_np(layer.d_w2)
+    for e in range(E):
+        if fwd["counts"][e] == 0:
+            assert np.all(dW1[e] == 0) and np.all(dW2[e] == 0)
+        else:
+            errs[f"dW1[{e}]"] = max_norm_err(dW1[e], bwd["dW1"][e])
+            errs[f"dW2[{e}]"] = max_norm_err(dW2[e], bwd["dW2"][e])
+    print(cfg.name, {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < tol}
+    assert not bad, bad
+    # information only: end to end against the oracle taking its own cast decisions, and against no casts at all
+    plain = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], k)
+    print("   y end to end vs fp8 oracle:", f"{max_norm_err(to_np(layer.y), fwd['y']):.2e}",
+          " vs unquantised oracle:", f"{max_norm_err(to_np(layer.y), plain['y']):.2e}")
