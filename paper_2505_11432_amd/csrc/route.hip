@@ -3,26 +3,29 @@
 // expert, then by source).  The paper lists the "multitude of small operators" of the gate as a
 // launch-latency straggler (Section 7); here the whole step is three launches and no host read-back:
 //   1. route_topk_kernel   per token: k-fold arg-max under the total order (logit desc, id asc) with
-//                          wave shuffles, softmax over the selected logits, per-chunk expert histogram
-//   2. route_scan_kernel   exclusive scan of the histograms over chunks (per expert) and over experts
-//   3. route_rank_kernel   stable rank of every assignment inside its expert via wave ballots
+//                          shuffles inside groups of <= 16 lanes (4+ tokens per wave at a time), softmax
+//                          over the selected logits, per-chunk expert histogram
+//   2. route_scan_kernel   one wave per expert: exclusive scan of its per-chunk counts
+//   3. route_rank_kernel   offsets = scan of the counts; stable rank of every assignment inside its
+//                          expert: equal-expert lanes found with one ballot per bit of the expert id
 // No atomics decide an order, so perm / inv_perm are unique and reproducible bit for bit.
 #include "moe_common.h"
 
 namespace moe {
 namespace {
 
-constexpr int kMaxValsPerLane = MOE_MAX_EXPERTS / 64;
-
 __device__ __forceinline__ bool better(float az, int ae, float bz, int be) {
   return az > bz || (az == bz && ae < be);
 }
 
-// G lanes cooperate on one token; lane `sub` holds experts sub, sub+G, sub+2G, ...
-template <int G>
+// G lanes (G <= 16) cooperate on one token, 64/G tokens per wave at a time; lane `sub` of a group holds the
+// VPL experts sub, sub+G, sub+2G, ...  The per-chunk histogram is written transposed, [E][nchunks], so the
+// scan kernel reads rows.
+template <int G, int VPL>
 __global__ void __launch_bounds__(256) route_topk_kernel(const float* __restrict__ logits, int T, int E, int k,
-                                                         int renorm, int chunk_tokens, int32_t* __restrict__ topk_idx,
-                                                         float* __restrict__ topk_w, int32_t* __restrict__ chunk_hist) {
+                                                         int renorm, int chunk_tokens, int nchunks,
+                                                         int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                         int32_t* __restrict__ chunk_hist) {
   __shared__ int hist[MOE_MAX_EXPERTS];
   for (int e = threadIdx.x; e < MOE_MAX_EXPERTS; e += blockDim.x) hist[e] = 0;
   __syncthreads();
@@ -32,29 +35,33 @@ __global__ void __launch_bounds__(256) route_topk_kernel(const float* __restrict
   const int ngroups = blockDim.x / G;
   const int t_begin = blockIdx.x * chunk_tokens;
   const int t_end = min(t_begin + chunk_tokens, T);
-  const int vpl = (E + G - 1) / G;
 
-  for (int t = t_begin + grp; t < t_end; t += ngroups) {
-    float v[kMaxValsPerLane];
+  // all groups of a wave run the same number of rounds (shuffles need the whole group active; a group past
+  // the end of the chunk works on the last token again and skips the stores)
+  const int rounds = (t_end - t_begin + ngroups - 1) / ngroups;
+  for (int it = 0; it < rounds; ++it) {
+    const int t_raw = t_begin + it * ngroups + grp;
+    const bool live = t_raw < t_end;
+    const int t = live ? t_raw : t_end - 1;
+    float v[VPL];
     unsigned taken = 0;
 #pragma unroll
-    for (int i = 0; i < kMaxValsPerLane; ++i) {
+    for (int i = 0; i < VPL; ++i) {
       const int e = sub + i * G;
-      if (i < vpl && e < E) {
+      if (e < E) {
         v[i] = logits[(long)t * E + e];
       } else {
         v[i] = -INFINITY;
         taken |= 1u << i;
       }
     }
-    float my_z = -INFINITY;
+    float my_z = -INFINITY, top_z = 0.f;
     int my_e = 0;
-    float top_z = 0.f;
     for (int j = 0; j < k; ++j) {
       float bz = -INFINITY;
       int be = 0x7fffffff;
 #pragma unroll
-      for (int i = 0; i < kMaxValsPerLane; ++i) {
+      for (int i = 0; i < VPL; ++i) {
         const int e = sub + i * G;
         if (!((taken >> i) & 1u) && better(v[i], e, bz, be)) { bz = v[i]; be = e; }
       }
@@ -65,9 +72,10 @@ __global__ void __launch_bounds__(256) route_topk_kernel(const float* __restrict
         if (better(oz, oe, bz, be)) { bz = oz; be = oe; }
       }
       if (be % G == sub) taken |= 1u << (be / G);   // the owner retires the winner
-      if (sub == j) { my_z = bz; my_e = be; }
+      if (sub == j) { my_z = bz; my_e = be; }        // lane j keeps slot j (k <= min(E, 16) <= G)
       if (j == 0) top_z = bz;
     }
+    // weights: softmax over the selected logits (renorm) or over all logits read at the selected ones
     const bool holds_slot = sub < k;
     const float ex = holds_slot ? expf(my_z - top_z) : 0.f;
     float den;
@@ -76,79 +84,104 @@ __global__ void __launch_bounds__(256) route_topk_kernel(const float* __restrict
     } else {
       den = 0.f;
 #pragma unroll
-      for (int i = 0; i < kMaxValsPerLane; ++i)
-        if (i < vpl && sub + i * G < E) den += expf(v[i] - top_z);
+      for (int i = 0; i < VPL; ++i)
+        if (sub + i * G < E) den += expf(v[i] - top_z);
     }
 #pragma unroll
     for (int off = G / 2; off >= 1; off >>= 1) den += __shfl_xor(den, off, G);
-    if (holds_slot) {
+    if (live && holds_slot) {
       topk_idx[(long)t * k + sub] = my_e;
       topk_w[(long)t * k + sub] = ex / den;
       atomicAdd(&hist[my_e], 1);     // integer count: the sum does not depend on the order
     }
   }
   __syncthreads();
-  for (int e = threadIdx.x; e < E; e += blockDim.x) chunk_hist[(long)blockIdx.x * E + e] = hist[e];
+  for (int e = threadIdx.x; e < E; e += blockDim.x) chunk_hist[(long)e * nchunks + blockIdx.x] = hist[e];
 }
 
-// chunk_hist [nchunks, E] -> exclusive prefix over chunks, in place; counts, offsets.
-__global__ void __launch_bounds__(MOE_MAX_EXPERTS) route_scan_kernel(int32_t* __restrict__ chunk_hist, int nchunks,
-                                                                     int E, int32_t* __restrict__ counts,
-                                                                     int32_t* __restrict__ offsets) {
-  __shared__ int total[MOE_MAX_EXPERTS];
-  const int e = threadIdx.x;
-  if (e < E) {
-    int run = 0;
-    for (int c = 0; c < nchunks; ++c) {
-      const int h = chunk_hist[(long)c * E + e];
-      chunk_hist[(long)c * E + e] = run;
-      run += h;
-    }
-    total[e] = run;
-    counts[e] = run;
+// One wave per expert: exclusive prefix of that expert's per-chunk counts, in place; counts[e] = total.
+__global__ void __launch_bounds__(64) route_scan_kernel(int32_t* __restrict__ chunk_hist, int nchunks,
+                                                        int32_t* __restrict__ counts) {
+  const int e = blockIdx.x, lane = threadIdx.x;
+  int32_t* row = chunk_hist + (long)e * nchunks;
+  const int per_lane = (nchunks + 63) / 64;          // nchunks <= 1024 -> at most 16
+  const int c0 = lane * per_lane;
+  int vals[16];
+  int sum = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    vals[i] = (i < per_lane && c0 + i < nchunks) ? row[c0 + i] : 0;
+    sum += vals[i];
   }
-  __syncthreads();
-  if (e == 0) {
-    int run = 0;
-    for (int i = 0; i < E; ++i) { offsets[i] = run; run += total[i]; }
-    offsets[E] = run;
+  int incl = sum;                                    // inclusive scan of the lane sums across the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
   }
+  int run = incl - sum;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (i < per_lane && c0 + i < nchunks) row[c0 + i] = run;
+    run += vals[i];
+  }
+  if (lane == 63) counts[e] = incl;
 }
 
-// One wave per chunk walks its assignments in order, 64 at a time.
+// One wave per chunk walks its assignments in order, 64 at a time.  Lanes with the same expert are found with
+// one ballot per bit of the expert id; the rank inside the group is a popcount of the lower lanes.
 __global__ void __launch_bounds__(64) route_rank_kernel(const int32_t* __restrict__ topk_idx, int T, int E, int k,
-                                                        int chunk_tokens, const int32_t* __restrict__ chunk_base,
-                                                        const int32_t* __restrict__ offsets,
+                                                        int chunk_tokens, int nchunks,
+                                                        const int32_t* __restrict__ chunk_base,
+                                                        const int32_t* __restrict__ counts,
+                                                        int32_t* __restrict__ offsets,
                                                         int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
   __shared__ int next_row[MOE_MAX_EXPERTS];
+  __shared__ int expert_off[MOE_MAX_EXPERTS + 1];
   const int lane = threadIdx.x;
-  for (int e = lane; e < E; e += 64) next_row[e] = offsets[e] + chunk_base[(long)blockIdx.x * E + e];
+  // offsets = exclusive scan of counts (every block recomputes it; block 0 publishes it)
+  int run = 0;
+  for (int e0 = 0; e0 < E; e0 += 64) {
+    const int e = e0 + lane;
+    const int c = e < E ? counts[e] : 0;
+    int incl = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    if (e < E) expert_off[e] = run + incl - c;
+    run += __shfl(incl, 63);
+  }
+  if (lane == 0) expert_off[E] = run;
   __syncthreads();
+  if (blockIdx.x == 0)
+    for (int e = lane; e <= E; e += 64) offsets[e] = expert_off[e];
+  for (int e = lane; e < E; e += 64) next_row[e] = expert_off[e] + chunk_base[(long)e * nchunks + blockIdx.x];
+  __syncthreads();
+
+  int ebits = 0;
+  while ((1 << ebits) < E) ++ebits;
   const long a_begin = (long)blockIdx.x * chunk_tokens * k;
   const long a_end = min((long)(blockIdx.x + 1) * chunk_tokens, (long)T) * k;
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
   for (long base = a_begin; base < a_end; base += 64) {
     const long a = base + lane;
     const bool valid = a < a_end;
-    const int e = valid ? topk_idx[a] : -1;
-    bool pending = valid;
-    unsigned long long todo = __ballot(pending);
-    while (todo) {
-      const int leader = __ffsll((long long)todo) - 1;
-      const int e0 = __shfl(e, leader);
-      const unsigned long long same = __ballot(pending && e == e0);
-      const int start = next_row[e0];
-      if (pending && e == e0) {
-        const int r = start + __popcll(same & lt_mask);
-        inv_perm[a] = r;
-        perm[r] = (int)a;
-        pending = false;
-      }
-      __syncthreads();                       // every lane has read next_row[e0]
-      if (lane == leader) next_row[e0] = start + __popcll(same);
-      __syncthreads();
-      todo &= ~same;
+    const int e = valid ? topk_idx[a] : 0;
+    unsigned long long same = __ballot(valid);
+    for (int b = 0; b < ebits; ++b) {
+      const unsigned long long mb = __ballot((e >> b) & 1);
+      same &= ((e >> b) & 1) ? mb : ~mb;
     }
+    if (valid) {
+      const int start = next_row[e];
+      const int r = start + __popcll(same & lt_mask);
+      inv_perm[a] = r;
+      perm[r] = (int)a;
+      if ((same >> lane) >> 1 == 0) next_row[e] = start + __popcll(same);   // the group's highest lane advances the row
+    }
+    __syncthreads();
   }
 }
 
@@ -186,10 +219,10 @@ __global__ void __launch_bounds__(256) route_bwd_kernel(const float* __restrict_
   }
 }
 
-template <int G>
+template <int G, int VPL>
 int launch_topk(const float* logits, int T, int E, int k, int renorm, int chunk_tokens, int nchunks, int32_t* idx,
                 float* w, int32_t* hist, hipStream_t s) {
-  route_topk_kernel<G><<<nchunks, 256, 0, s>>>(logits, T, E, k, renorm, chunk_tokens, idx, w, hist);
+  route_topk_kernel<G, VPL><<<nchunks, 256, 0, s>>>(logits, T, E, k, renorm, chunk_tokens, nchunks, idx, w, hist);
   MOE_LAUNCH_CHECK();
   return MOE_OK;
 }
@@ -207,17 +240,20 @@ int launch_route(const float* logits, int T, int E, int k, int renorm, int32_t* 
   const int nchunks = cdiv(T, tb);
   int32_t* hist = static_cast<int32_t*>(ws);
   int rc;
-  if (E <= 1) rc = launch_topk<1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 2) rc = launch_topk<2>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 4) rc = launch_topk<4>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 8) rc = launch_topk<8>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 16) rc = launch_topk<16>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 32) rc = launch_topk<32>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else rc = launch_topk<64>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  // lanes per token G = min(16, pow2 >= E) (so G >= k: one slot per lane); experts beyond 16 go VPL per lane
+  if (E <= 1) rc = launch_topk<1, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else if (E <= 2) rc = launch_topk<2, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else if (E <= 4) rc = launch_topk<4, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else if (E <= 8) rc = launch_topk<8, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else if (E <= 16) rc = launch_topk<16, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else if (E <= 32) rc = launch_topk<16, 2>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else if (E <= 64) rc = launch_topk<16, 4>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else if (E <= 128) rc = launch_topk<16, 8>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  else rc = launch_topk<16, 16>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
   if (rc != MOE_OK) return rc;
-  route_scan_kernel<<<1, MOE_MAX_EXPERTS, 0, s>>>(hist, nchunks, E, counts, offsets);
+  route_scan_kernel<<<E, 64, 0, s>>>(hist, nchunks, counts);
   MOE_LAUNCH_CHECK();
-  route_rank_kernel<<<nchunks, 64, 0, s>>>(idx, T, E, k, tb, hist, offsets, perm, inv_perm);
+  route_rank_kernel<<<nchunks, 64, 0, s>>>(idx, T, E, k, tb, nchunks, hist, counts, offsets, perm, inv_perm);
   MOE_LAUNCH_CHECK();
   return MOE_OK;
 }

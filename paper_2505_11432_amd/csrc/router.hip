@@ -22,12 +22,17 @@ template <> struct Pair<bf16> {
   }
 };
 
-// partial[chunk][e][col] = sum over the chunk's tokens of d_logits[t][e] * x[t][col]
+// partial[chunk][e][col] = sum over the chunk's tokens of d_logits[t][e] * x[t][col].
+// The chunk's gate gradients (up to 128 tokens x 64 experts) are staged in LDS once and read back as
+// broadcasts, so the inner loop is one LDS read per four FMAs and the kernel is FMA-bound.
+constexpr int kChunkTokens = 128;
+
 template <typename T>
 __global__ void __launch_bounds__(256) router_dwr_partial_kernel(const T* __restrict__ x,
                                                                  const float* __restrict__ d_logits, int Tn, int d,
                                                                  int E, int tokens_per_chunk,
                                                                  float* __restrict__ partial) {
+  __shared__ __attribute__((aligned(16))) float g_lds[kChunkTokens][kETile];
   const int slabs = (d + kSlabCols - 1) / kSlabCols;
   const int slab = blockIdx.x % slabs, chunk = blockIdx.x / slabs;
   const int col = slab * kSlabCols + threadIdx.x * 2;
@@ -37,15 +42,24 @@ __global__ void __launch_bounds__(256) router_dwr_partial_kernel(const T* __rest
     float2 acc[kETile];
 #pragma unroll
     for (int i = 0; i < kETile; ++i) acc[i] = make_float2(0.f, 0.f);
-    for (int t = t0; t < t1; ++t) {
-      const float2 xv = active ? Pair<T>::load(x + (long)t * d + col) : make_float2(0.f, 0.f);
-      const float* g = d_logits + (long)t * E + e0;      // wave-uniform address: scalar loads
+    for (int ts = t0; ts < t1; ts += kChunkTokens) {          // 128 tokens at a time through LDS
+      const int te = min(ts + kChunkTokens, t1);
+      __syncthreads();
+      for (int i = threadIdx.x; i < (te - ts) * kETile; i += 256) {
+        const int tt = i / kETile, ee = i % kETile;
+        g_lds[tt][ee] = (e0 + ee < E) ? d_logits[(long)(ts + tt) * E + e0 + ee] : 0.f;
+      }
+      __syncthreads();
+      for (int t = ts; t < te; ++t) {
+        const float2 xv = active ? Pair<T>::load(x + (long)t * d + col) : make_float2(0.f, 0.f);
+        const float4* g = reinterpret_cast<const float4*>(g_lds[t - ts]);
 #pragma unroll
-      for (int i = 0; i < kETile; ++i) {
-        if (e0 + i < E) {
-          const float gv = g[i];
-          acc[i].x = fmaf(gv, xv.x, acc[i].x);
-          acc[i].y = fmaf(gv, xv.y, acc[i].y);
+        for (int i = 0; i < kETile / 4; ++i) {
+          const float4 gv = g[i];
+          acc[4 * i + 0].x = fmaf(gv.x, xv.x, acc[4 * i + 0].x); acc[4 * i + 0].y = fmaf(gv.x, xv.y, acc[4 * i + 0].y);
+          acc[4 * i + 1].x = fmaf(gv.y, xv.x, acc[4 * i + 1].x); acc[4 * i + 1].y = fmaf(gv.y, xv.y, acc[4 * i + 1].y);
+          acc[4 * i + 2].x = fmaf(gv.z, xv.x, acc[4 * i + 2].x); acc[4 * i + 2].y = fmaf(gv.z, xv.y, acc[4 * i + 2].y);
+          acc[4 * i + 3].x = fmaf(gv.w, xv.x, acc[4 * i + 3].x); acc[4 * i + 3].y = fmaf(gv.w, xv.y, acc[4 * i + 3].y);
         }
       }
     }
@@ -66,36 +80,62 @@ __global__ void __launch_bounds__(256) router_dwr_reduce_kernel(const float* __r
   }
 }
 
-// dx[t, cols] += sum_e d_logits[t][e] * w_r[e][cols]; a wave owns one token's 512-column slab at a time.
+// dx[t, cols] += sum_e d_logits[t][e] * w_r[e][cols].  A block owns a slab of 512 columns (64 lanes x 8) and
+// keeps that slab of w_r (up to 64 experts x 1 KiB) in LDS; its four waves walk the tokens.  More than 64
+// experts are done in passes of 64 that each read-modify-write dx.
+constexpr int kDxCols = 512;
+
 template <typename T>
 __global__ void __launch_bounds__(256) router_dx_kernel(const T* __restrict__ w_r, const float* __restrict__ d_logits,
-                                                        int Tn, int d, int E, T* __restrict__ dx) {
-  constexpr int V = 16 / sizeof(T);
-  const int nvec = d / V;
-  const long total = (long)Tn * nvec;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
-    const long t = i / nvec;
-    const int c = (int)(i % nvec) * V;
-    Vec16<T> cur = *reinterpret_cast<const Vec16<T>*>(dx + t * d + c);
-    float acc[V];
-#pragma unroll
-    for (int j = 0; j < V; ++j) acc[j] = to_f32(cur.v[j]);
-    const float* g = d_logits + t * E;
-    for (int e = 0; e < E; ++e) {
-      const float gv = g[e];
-      const Vec16<T> w = *reinterpret_cast<const Vec16<T>*>(w_r + (long)e * d + c);
-#pragma unroll
-      for (int j = 0; j < V; ++j) acc[j] = fmaf(gv, to_f32(w.v[j]), acc[j]);
+                                                        int Tn, int d, int E, int token_groups, T* __restrict__ dx) {
+  constexpr int V = 8;                                  // columns per lane
+  __shared__ __attribute__((aligned(16))) T w_lds[kETile][kDxCols];
+  const int slabs = (d + kDxCols - 1) / kDxCols;
+  const int slab = blockIdx.x % slabs, tg = blockIdx.x / slabs;
+  const int lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+  const int col = slab * kDxCols + lane * V;
+  const bool active = col < d;
+  for (int e0 = 0; e0 < E; e0 += kETile) {
+    const int ne = min(kETile, E - e0);
+    __syncthreads();
+    for (int i = threadIdx.x; i < ne * (kDxCols / V); i += 256) {
+      const int ee = i / (kDxCols / V), cc = (i % (kDxCols / V)) * V;
+      Vec16<T> v;      // V elements of T fill 16 bytes for bf16; fp32 uses two 16-byte halves below
+      if constexpr (sizeof(T) == 2) {
+        if (slab * kDxCols + cc < d) v = *reinterpret_cast<const Vec16<T>*>(w_r + (long)(e0 + ee) * d + slab * kDxCols + cc);
+        else for (int j = 0; j < V; ++j) v.v[j] = from_f32<T>(0.f);
+        *reinterpret_cast<Vec16<T>*>(&w_lds[ee][cc]) = v;
+      } else {
+        for (int j = 0; j < V; ++j)
+          w_lds[ee][cc + j] = (slab * kDxCols + cc + j < d) ? w_r[(long)(e0 + ee) * d + slab * kDxCols + cc + j] : from_f32<T>(0.f);
+      }
     }
+    __syncthreads();
+    for (int t = tg * 4 + wave; t < Tn; t += token_groups * 4) {
+      if (!active) continue;
+      float acc[V];
+      T* dst = dx + (long)t * d + col;
 #pragma unroll
-    for (int j = 0; j < V; ++j) cur.v[j] = from_f32<T>(acc[j]);
-    *reinterpret_cast<Vec16<T>*>(dx + t * d + c) = cur;
+      for (int j = 0; j < V; ++j) acc[j] = to_f32(dst[j]);
+      const float* g = d_logits + (long)t * E + e0;      // wave-uniform: scalar loads
+      for (int e = 0; e < ne; ++e) {
+        const float gv = g[e];
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = fmaf(gv, to_f32(w_lds[e][lane * V + j]), acc[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < V; ++j) dst[j] = from_f32<T>(acc[j]);
+    }
   }
 }
 
+int dwr_tokens_per_chunk(int T) {                // a multiple of the LDS staging size; at most 256 chunks
+  int tpc = kChunkTokens;
+  while (cdiv(T, tpc) > 256) tpc *= 2;
+  return tpc;
+}
 int dwr_chunks(int T) {
-  int chunks = cdiv(T, 128);
-  if (chunks > 128) chunks = 128;
+  const int chunks = cdiv(T, dwr_tokens_per_chunk(T));
   return chunks < 1 ? 1 : chunks;
 }
 
@@ -107,7 +147,7 @@ int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe
                       float* d_w_r, void* dx, void* ws, hipStream_t s) {
   if (d_w_r) {
     const int chunks = dwr_chunks(T);
-    const int tpc = cdiv(T, chunks);
+    const int tpc = dwr_tokens_per_chunk(T);
     const int slabs = cdiv(d, kSlabCols);
     float* partial = static_cast<float*>(ws);
     if (dt == MOE_F32)
@@ -122,11 +162,12 @@ int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe
     MOE_LAUNCH_CHECK();
   }
   if (dx && T > 0) {
-    const long total = (long)T * d / (dt == MOE_F32 ? 4 : 8);
-    long blocks = (total + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    if (dt == MOE_F32) router_dx_kernel<float><<<(int)blocks, 256, 0, s>>>((const float*)w_r, d_logits, T, d, E, (float*)dx);
-    else router_dx_kernel<bf16><<<(int)blocks, 256, 0, s>>>((const bf16*)w_r, d_logits, T, d, E, (bf16*)dx);
+    const int slabs = cdiv(d, kDxCols);
+    int token_groups = cdiv(512, slabs);                 // about two blocks per CU
+    if (token_groups > cdiv(T, 4)) token_groups = cdiv(T, 4);
+    const int blocks = slabs * token_groups;
+    if (dt == MOE_F32) router_dx_kernel<float><<<blocks, 256, 0, s>>>((const float*)w_r, d_logits, T, d, E, token_groups, (float*)dx);
+    else router_dx_kernel<bf16><<<blocks, 256, 0, s>>>((const bf16*)w_r, d_logits, T, d, E, token_groups, (bf16*)dx);
     MOE_LAUNCH_CHECK();
   }
   return MOE_OK;
