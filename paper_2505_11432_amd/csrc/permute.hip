@@ -9,6 +9,7 @@ namespace moe {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes for the nontemporal builtins
 
 // Broadcast lane `src` (wave-uniform) of a per-lane value; reads the register whatever EXEC says.
 __device__ __forceinline__ int bcast(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
@@ -49,7 +50,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) dispatch_kernel(const T* 
 #pragma unroll
           for (int i = 0; i < V; ++i) o.v[i] = from_f32<T>(to_f32(v.v[i]) * m);
         }
-        if (active) *reinterpret_cast<Vec16<T>*>(xp + (long)r * d + (long)c * V) = o;
+        if (active)
+          __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o), reinterpret_cast<u32x4*>(xp + (long)r * d + (long)c * V));
       }
     }
   }
@@ -59,7 +61,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) dispatch_kernel(const T* 
 template <typename TIN> struct RowLoader {
   static constexpr int V = 16 / sizeof(TIN);
   __device__ static void load(const TIN* p, float (&out)[V]) {
-    const Vec16<TIN> v = *reinterpret_cast<const Vec16<TIN>*>(p);
+    const u32x4 raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));     // rows are streamed once
+    const Vec16<TIN> v = __builtin_bit_cast(Vec16<TIN>, raw);
 #pragma unroll
     for (int i = 0; i < V; ++i) out[i] = to_f32(v.v[i]);
   }
@@ -67,8 +70,8 @@ template <typename TIN> struct RowLoader {
 template <> struct RowLoader<uint8_t> {
   static constexpr int V = 16;
   __device__ static void load(const uint8_t* p, float (&out)[16]) {
-    const uint4 q = *reinterpret_cast<const uint4*>(p);
-    const unsigned w[4] = {q.x, q.y, q.z, q.w};
+    const u32x4 q = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    const unsigned w[4] = {q[0], q[1], q[2], q[3]};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       out[4 * i + 0] = __builtin_amdgcn_cvt_f32_fp8((int)w[i], 0);
@@ -185,7 +188,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) gate_grad_kernel(const TD
 
 int row_grid(int T) {
   int blocks = cdiv(T, kWavesPerBlock);
-  const int cap = 256 * 8;
+  const int cap = 256 * 16;
   return blocks < 1 ? 1 : (blocks > cap ? cap : blocks);
 }
 

@@ -32,26 +32,42 @@ __device__ __forceinline__ float block_max_256(float v, float* red) {
   return v;
 }
 
-// One 256-thread block per row.
+// One 256-thread block per row.  Rows of up to 256 x 8 vectors (16384 bf16 / 8192 fp32 columns) stay in
+// registers between the amax pass and the convert pass, so HBM sees each element once; longer rows are
+// read a second time (from L2).
 template <typename T>
 __global__ void __launch_bounds__(256) quant_rows_kernel(const T* __restrict__ src, int rows, int cols,
                                                          uint8_t* __restrict__ codes, float* __restrict__ scales) {
   __shared__ float red[4];
   constexpr int V = 16 / sizeof(T);
+  constexpr int kHold = 8;                       // vectors held per thread
   const int nvec = cols / V;
+  const bool in_regs = nvec <= 256 * kHold;
   for (int r = blockIdx.x; r < rows; r += gridDim.x) {
     const T* row = src + (long)r * cols;
+    Vec16<T> hold[kHold];
     float amax = 0.f;
-    for (int c = threadIdx.x; c < nvec; c += 256) {
-      const Vec16<T> v = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
+    if (in_regs) {
 #pragma unroll
-      for (int i = 0; i < V; ++i) amax = fmaxf(amax, fabsf(to_f32(v.v[i])));
+      for (int h = 0; h < kHold; ++h) {
+        const int c = threadIdx.x + h * 256;
+        if (c < nvec) {
+          hold[h] = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
+#pragma unroll
+          for (int i = 0; i < V; ++i) amax = fmaxf(amax, fabsf(to_f32(hold[h].v[i])));
+        }
+      }
+    } else {
+      for (int c = threadIdx.x; c < nvec; c += 256) {
+        const Vec16<T> v = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
+#pragma unroll
+        for (int i = 0; i < V; ++i) amax = fmaxf(amax, fabsf(to_f32(v.v[i])));
+      }
     }
     amax = block_max_256(amax, red);
     const float inv = amax > 0.f ? kE4M3Max / amax : 1.0f;
     if (threadIdx.x == 0) scales[r] = amax > 0.f ? amax / kE4M3Max : 1.0f;
-    for (int c = threadIdx.x; c < nvec; c += 256) {
-      const Vec16<T> v = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
+    auto convert = [&](const Vec16<T>& v, int c) {
       unsigned out[V / 4];
 #pragma unroll
       for (int i = 0; i < V / 4; ++i)
@@ -60,35 +76,65 @@ __global__ void __launch_bounds__(256) quant_rows_kernel(const T* __restrict__ s
       unsigned* dst = reinterpret_cast<unsigned*>(codes + (long)r * cols + (long)c * V);
 #pragma unroll
       for (int i = 0; i < V / 4; ++i) dst[i] = out[i];
+    };
+    if (in_regs) {
+#pragma unroll
+      for (int h = 0; h < kHold; ++h) {
+        const int c = threadIdx.x + h * 256;
+        if (c < nvec) convert(hold[h], c);
+      }
+    } else {
+      for (int c = threadIdx.x; c < nvec; c += 256) convert(*reinterpret_cast<const Vec16<T>*>(row + (long)c * V), c);
     }
   }
 }
 
-// One block per (128-row group, slab of 256*4 columns); a thread owns 4 adjacent columns.
+// One block per (128-row group, 64-column slab): thread (rg, cq) holds rows rg, rg+16, ... (8 rows) of the four
+// columns 4*cq..4*cq+3 in registers; the column maxima are combined through LDS.
 template <typename T>
 __global__ void __launch_bounds__(256) quant_colgroup_kernel(const T* __restrict__ src, int rows, int cols,
                                                              uint8_t* __restrict__ codes,
                                                              float* __restrict__ scales, int slabs) {
+  __shared__ float cmax[16][64];
   const int g = blockIdx.x / slabs;
-  const int c = ((blockIdx.x % slabs) * 256 + threadIdx.x) * 4;
-  if (c >= cols) return;
-  const int r0 = g * 128, r1 = min(r0 + 128, rows);
+  const int cq = threadIdx.x % 16, rg = threadIdx.x / 16;
+  const int c = (blockIdx.x % slabs) * 64 + cq * 4;
+  const int r0 = g * 128;
+  const bool col_ok = c < cols;
+  float v[8][4];
   float amax[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int r = r0; r < r1; ++r) {
-    const T* p = src + (long)r * cols + c;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) amax[i] = fmaxf(amax[i], fabsf(to_f32(p[i])));
+  for (int i = 0; i < 8; ++i) {
+    const int r = r0 + rg + 16 * i;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[i][j] = 0.f;
+    if (col_ok && r < rows) {
+      const T* p = src + (long)r * cols + c;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[i][j] = to_f32(p[j]);
+        amax[j] = fmaxf(amax[j], fabsf(v[i][j]));
+      }
+    }
   }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) cmax[rg][cq * 4 + j] = amax[j];
+  __syncthreads();
   float inv[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    inv[i] = amax[i] > 0.f ? kE4M3Max / amax[i] : 1.0f;
-    scales[(long)g * cols + c + i] = amax[i] > 0.f ? amax[i] / kE4M3Max : 1.0f;
+  for (int j = 0; j < 4; ++j) {
+    float m = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) m = fmaxf(m, cmax[q][cq * 4 + j]);
+    inv[j] = m > 0.f ? kE4M3Max / m : 1.0f;
+    if (rg == 0 && col_ok) scales[(long)g * cols + c + j] = m > 0.f ? m / kE4M3Max : 1.0f;
   }
-  for (int r = r0; r < r1; ++r) {
-    const T* p = src + (long)r * cols + c;
-    *reinterpret_cast<unsigned*>(codes + (long)r * cols + c) =
-        pack4_e4m3(to_f32(p[0]) * inv[0], to_f32(p[1]) * inv[1], to_f32(p[2]) * inv[2], to_f32(p[3]) * inv[3]);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = r0 + rg + 16 * i;
+    if (col_ok && r < rows)
+      *reinterpret_cast<unsigned*>(codes + (long)r * cols + c) =
+          pack4_e4m3(v[i][0] * inv[0], v[i][1] * inv[1], v[i][2] * inv[2], v[i][3] * inv[3]);
   }
 }
 
@@ -126,7 +172,7 @@ int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_
     if (src_dt == MOE_F32) quant_rows_kernel<float><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales);
     else quant_rows_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
   } else {
-    const int slabs = cdiv(cols, 1024);
+    const int slabs = cdiv(cols, 64);
     const int grid = cdiv(rows, 128) * slabs;
     if (src_dt == MOE_F32) quant_colgroup_kernel<float><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales, slabs);
     else quant_colgroup_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales, slabs);

@@ -111,20 +111,55 @@ __global__ void __launch_bounds__(256) router_dx_kernel(const T* __restrict__ w_
       }
     }
     __syncthreads();
-    for (int t = tg * 4 + wave; t < Tn; t += token_groups * 4) {
+    // a wave takes kTok tokens at a time: one LDS read of w_r feeds kTok x 8 FMAs
+    constexpr int kTok = 4;
+    for (int tb = (tg * 4 + wave) * kTok; tb < Tn; tb += token_groups * 4 * kTok) {
       if (!active) continue;
-      float acc[V];
-      T* dst = dx + (long)t * d + col;
+      float acc[kTok][V];
 #pragma unroll
-      for (int j = 0; j < V; ++j) acc[j] = to_f32(dst[j]);
-      const float* g = d_logits + (long)t * E + e0;      // wave-uniform: scalar loads
+      for (int q = 0; q < kTok; ++q) {
+        const int t = min(tb + q, Tn - 1);
+        const T* src = dx + (long)t * d + col;
+        if constexpr (sizeof(T) == 2) {
+          const Vec16<T> cur = *reinterpret_cast<const Vec16<T>*>(src);
+#pragma unroll
+          for (int j = 0; j < V; ++j) acc[q][j] = to_f32(cur.v[j]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < V; ++j) acc[q][j] = to_f32(src[j]);
+        }
+      }
       for (int e = 0; e < ne; ++e) {
-        const float gv = g[e];
+        float wv[V];
+        if constexpr (sizeof(T) == 2) {
+          const Vec16<T> w = *reinterpret_cast<const Vec16<T>*>(&w_lds[e][lane * V]);     // one ds_read_b128
 #pragma unroll
-        for (int j = 0; j < V; ++j) acc[j] = fmaf(gv, to_f32(w_lds[e][lane * V + j]), acc[j]);
+          for (int j = 0; j < V; ++j) wv[j] = to_f32(w.v[j]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < V; ++j) wv[j] = to_f32(w_lds[e][lane * V + j]);
+        }
+#pragma unroll
+        for (int q = 0; q < kTok; ++q) {
+          const float gv = d_logits[(long)min(tb + q, Tn - 1) * E + e0 + e];     // wave-uniform: scalar load
+#pragma unroll
+          for (int j = 0; j < V; ++j) acc[q][j] = fmaf(gv, wv[j], acc[q][j]);
+        }
       }
 #pragma unroll
-      for (int j = 0; j < V; ++j) dst[j] = from_f32<T>(acc[j]);
+      for (int q = 0; q < kTok; ++q) {
+        if (tb + q >= Tn) break;
+        T* dst = dx + (long)(tb + q) * d + col;
+        if constexpr (sizeof(T) == 2) {
+          Vec16<T> out;
+#pragma unroll
+          for (int j = 0; j < V; ++j) out.v[j] = from_f32<T>(acc[q][j]);
+          *reinterpret_cast<Vec16<T>*>(dst) = out;
+        } else {
+#pragma unroll
+          for (int j = 0; j < V; ++j) dst[j] = from_f32<T>(acc[q][j]);
+        }
+      }
     }
   }
 }
@@ -164,7 +199,7 @@ int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe
   if (dx && T > 0) {
     const int slabs = cdiv(d, kDxCols);
     int token_groups = cdiv(512, slabs);                 // about two blocks per CU
-    if (token_groups > cdiv(T, 4)) token_groups = cdiv(T, 4);
+    if (token_groups > cdiv(T, 16)) token_groups = cdiv(T, 16);
     const int blocks = slabs * token_groups;
     if (dt == MOE_F32) router_dx_kernel<float><<<blocks, 256, 0, s>>>((const float*)w_r, d_logits, T, d, E, token_groups, (float*)dx);
     else router_dx_kernel<bf16><<<blocks, 256, 0, s>>>((const bf16*)w_r, d_logits, T, d, E, token_groups, (bf16*)dx);
