@@ -76,7 +76,7 @@ int mfma_rowseg_nn(const void* A, const void* W, long w_es, const int32_t* offse
   a.A = (const bf16*)A; a.lda = K;
   a.B = (const bf16*)W; a.ldb = N; a.b_es = w_es;
   a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
-  return launch<256, 256, 32, 4, 4, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
+  return launch<256, 256, 64, 2, 2, 4, KMAJOR, MNMAJOR, ROWSEG, EPI_STORE, bf16>(a, rowseg_blocks(M, E, N, 256, 256), s);
 }
 
 // dA = d_yp * w2[e] fused with the SwiGLU derivative: reads H=[G|U], writes dH=[dG|dU] and (optionally) A
@@ -87,7 +87,7 @@ int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offs
   a.B = (const bf16*)w2; a.ldb = f; a.b_es = (long)d * f;
   a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d;
   a.H = (bf16*)const_cast<void*>(H); a.dH = (bf16*)dH; a.A_out = (bf16*)A_out;
-  return launch<256, 256, 32, 4, 4, 2, KMAJOR, MNMAJOR, ROWSEG, EPI_SWIGLU_BWD, bf16>(a, rowseg_blocks(M, E, f, 256, 256), s);
+  return launch<256, 256, 64, 2, 2, 4, KMAJOR, MNMAJOR, ROWSEG, EPI_SWIGLU_BWD, bf16>(a, rowseg_blocks(M, E, f, 256, 256), s);
 }
 
 // C[e][Mo,N] (+)= P[rows_e, Mo]^T * Q[rows_e, N]
