@@ -27,6 +27,15 @@ template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB,
           typename TIN = bf16>
 int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
   if (tiles_upper_bound <= 0) return MOE_OK;
+  {
+    // the kernel addresses each operand as a 64-bit tile base plus a 32-bit per-lane byte offset
+    const unsigned long long esz = sizeof(TIN), lim = 1ull << 32;
+    const unsigned long long a_span = (LA == KMAJOR) ? (unsigned long long)BM * a.lda * esz
+                                                     : ((unsigned long long)BKT * a.lda + a.M) * esz;
+    const unsigned long long b_rows = (EPI == EPI_SWIGLU) ? 2ull * a.f : (unsigned long long)a.N;
+    const unsigned long long b_span = (LB == KMAJOR) ? b_rows * a.ldb * esz : ((unsigned long long)BKT * a.ldb + a.N) * esz;
+    if (a_span >= lim || b_span >= lim) return MOE_ERR_UNSUPPORTED;
+  }
   int blocks = 0;
   const int rc = persistent_grid(&blocks);
   if (rc != MOE_OK) return rc;

@@ -35,6 +35,19 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "m0");
 }
 
+// The same load with the address split into a wave-uniform 64-bit base (scalar registers) and a 32-bit per-lane
+// byte offset: the per-k-step address update is then scalar arithmetic, and issuing the load needs no vector ALU
+// slot (those are what the SIMD partner's MFMAs compete for).
+__device__ __forceinline__ void dma16s(const char* sbase, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "m0");
+}
+
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<const char*>(((unsigned long long)hi << 32) | lo);
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]; other counters left open
@@ -169,12 +182,17 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr int A_BYTES = DmaTileBytes<LA, BM, BKT, ESZ>::value, B_BYTES = DmaTileBytes<LB, BN, BKT, ESZ>::value;
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
-  constexpr int A_DMA = A_BYTES / 1024 / NW, B_DMA = B_BYTES / 1024 / NW;     // loads per wave per stage
+  // With 8 waves (two per SIMD; waves w and w + 4 share one) only the upper four issue loads: a wave stalls while
+  // the texture-address queue is full (64 loads take ~1100 clocks), and this way its SIMD partner runs MFMAs
+  // meanwhile.  Smaller workgroups (one wave per SIMD) let every wave load.
+  constexpr bool SPLIT = (NW == 8);
+  constexpr int NL = SPLIT ? NW / 2 : NW;                                      // loader waves
+  constexpr int A_DMA = A_BYTES / 1024 / NL, B_DMA = B_BYTES / 1024 / NL;     // loads per loader wave per stage
   constexpr int LOADS = A_DMA + B_DMA;
   constexpr int KK = FP8 ? BKT / 64 : BKT / 16;    // MFMA sub-steps per k-step
   constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int GN = 4, XCDS = 8;
-  static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile does not split over the waves");
+  static_assert(A_BYTES % (1024 * NL) == 0 && B_BYTES % (1024 * NL) == 0, "tile does not split over the loader waves");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * LOADS < 64, "pipeline depth exceeds the vmcnt range");
   static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up MFMA tiles inside a wave");
   static_assert(NW <= 8, "LDS is budgeted for at most 8 epilogue patches");
@@ -210,7 +228,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       }
     }
     __syncthreads();
-    total_tiles = cum_tiles[p.E] * tiles_n;
+    total_tiles = __builtin_amdgcn_readfirstlane(cum_tiles[p.E]) * tiles_n;
   } else if constexpr (MODE == KSEG) {
     total_tiles = p.E * tiles_m_fixed * tiles_n;
   } else {
@@ -223,14 +241,17 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
   // tile state
   int e = 0, m0 = 0, m_end = 0, n0 = 0, klen = 0, nk = 0;
-  const char* a_src[A_DMA];
-  const char* b_src[B_DMA];
+  const bool is_loader = !SPLIT || wave >= NW / 2;       // wave-uniform
+  const int lw = SPLIT ? (wave & (NL - 1)) : wave;       // loader index (waves NW/2 .. NW-1 -> 0 .. NL-1)
+  const char* a_base = zero;        // wave-uniform: operand origin of the open tile at its first k
+  const char* b_base = zero;
+  unsigned a_off[A_DMA], b_off[B_DMA];   // this lane's byte offset from the base, fixed over the k loop
   int a_k[A_DMA], b_k[B_DMA];       // k coordinate (relative to the k-step start) this lane's chunk begins at
   const long a_step = (LA == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.lda * ESZ;   // bytes per k-step
   const long b_step = (LB == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.ldb * ESZ;
 
   // Decode slot -> tile and set up this lane's source pointers.  Returns false when the list is exhausted.
-  auto open_tile = [&](int sl) -> bool {
+  auto open_tile = [&](int sl) __attribute__((always_inline)) -> bool {
     int l = (sl * XCDS + xcd) * window + in_window;
     if (l >= total_tiles) return false;
     int mt_e, m_lo, m_hi;
@@ -241,9 +262,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         const int mid = (lo + hi) >> 1;
         if (cum_tiles[mid] * tiles_n <= l) lo = mid; else hi = mid;
       }
-      e = lo;
-      mt_e = cum_tiles[e + 1] - cum_tiles[e];
-      l -= cum_tiles[e] * tiles_n;
+      // everything about the tile is wave-uniform: keep it in scalar registers
+      e = __builtin_amdgcn_readfirstlane(lo);
+      mt_e = __builtin_amdgcn_readfirstlane(cum_tiles[e + 1] - cum_tiles[e]);
+      l = __builtin_amdgcn_readfirstlane(l - cum_tiles[e] * tiles_n);
       m_lo = p.offsets[e]; m_hi = p.offsets[e + 1];
     } else {
       mt_e = tiles_m_fixed;
@@ -262,33 +284,38 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     else { k_begin = 0; k_end = p.K; }
     klen = k_end - k_begin;
     nk = (klen + BKT - 1) / BKT;
-    const TIN* __restrict__ Ag = static_cast<const TIN*>(p.A);
-    const TIN* __restrict__ Bg = static_cast<const TIN*>(p.B) + (long)e * p.b_es;
+    const char* Ag = static_cast<const char*>(p.A);
+    const char* Bg = static_cast<const char*>(p.B) + (long)e * p.b_es * ESZ;
     const int real_m0 = m0, real_n0 = n0;
-    if constexpr (PROBE == 3) { m0 = 0; n0 = 0; Bg = static_cast<const TIN*>(p.B); }      // every tile loads the same panels (all L2 hits)
-    // load j of the wave covers DMA slot q = wave + j*NW of the tile (1 KiB of LDS each)
+    if constexpr (PROBE == 3) { m0 = 0; n0 = 0; Bg = static_cast<const char*>(p.B); }      // every tile loads the same panels (all L2 hits)
+    // Base of each operand at the tile's first k (wave-uniform) and this lane's fixed byte offset from it.
+    // Load j of loader wave lw fills DMA slot q = lw + j*NL of the tile (1 KiB of LDS each).
+    if constexpr (LA == KMAJOR) a_base = uniform_ptr(Ag + ((long)m0 * p.lda + k_begin) * ESZ);
+    else a_base = uniform_ptr(Ag + (long)k_begin * p.lda * ESZ);
+    if constexpr (LB == KMAJOR) b_base = uniform_ptr(Bg + (long)k_begin * ESZ);
+    else b_base = uniform_ptr(Bg + (long)k_begin * p.ldb * ESZ);
 #pragma unroll
     for (int j = 0; j < A_DMA; ++j) {
-      const int q = wave + j * NW;
+      const int q = lw + j * NL;
       if constexpr (LA == KMAJOR) {
         using TL = KTile<BM, BKT, ESZ>;
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
         const int lc = (lane % TL::CPR) ^ TL::swz(row);
-        const int gr = min(m0 + row, p.M - 1);
-        a_src[j] = reinterpret_cast<const char*>(Ag + (long)gr * p.lda + k_begin + lc * CHUNK);
+        const int rel = min(row, p.M - 1 - m0);                       // rows past the end of A repeat its last row
+        a_off[j] = (unsigned)rel * (unsigned)(p.lda * ESZ) + (unsigned)(lc * 16);
         a_k[j] = lc * CHUNK;
       } else {
         using TL = MNTile<BM, BKT>;
         const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
         const int lc = (lane % TL::CPR) ^ TL::swz(krow);
         const int col = min(m0 + lc * 8, p.M - 8);
-        a_src[j] = reinterpret_cast<const char*>(Ag + (long)(k_begin + krow) * p.lda + col);
+        a_off[j] = (unsigned)krow * (unsigned)(p.lda * ESZ) + (unsigned)(col * ESZ);
         a_k[j] = krow;
       }
     }
 #pragma unroll
     for (int j = 0; j < B_DMA; ++j) {
-      const int q = wave + j * NW;
+      const int q = lw + j * NL;
       if constexpr (LB == KMAJOR) {
         using TL = KTile<BN, BKT, ESZ>;
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
@@ -301,14 +328,14 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         } else {
           gr = min(n0 + row, p.N - 1);
         }
-        b_src[j] = reinterpret_cast<const char*>(Bg + (long)gr * p.ldb + k_begin + lc * CHUNK);
+        b_off[j] = (unsigned)gr * (unsigned)(p.ldb * ESZ) + (unsigned)(lc * 16);     // < 4 GiB: checked by the launcher
         b_k[j] = lc * CHUNK;
       } else {
         using TL = MNTile<BN, BKT>;
         const int krow = q * TL::ROWS_PER_DMA + lane / TL::CPR;
         const int lc = (lane % TL::CPR) ^ TL::swz(krow);
         const int col = min(n0 + lc * 8, p.N - 8);
-        b_src[j] = reinterpret_cast<const char*>(Bg + (long)(k_begin + krow) * p.ldb + col);
+        b_off[j] = (unsigned)krow * (unsigned)(p.ldb * ESZ) + (unsigned)(col * ESZ);
         b_k[j] = krow;
       }
     }
@@ -317,25 +344,27 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   };
 
   // Issue the loads of k-step `ks` of the open tile into ring slot ks % NSTAGE.  Only the last step can be ragged.
-  auto issue = [&](int ks) {
+  auto issue = [&](int ks) __attribute__((always_inline)) {
     if constexpr (PROBE == 1) return;
+    if (!is_loader) return;
     const unsigned stage = smem_lds + (unsigned)(ks % NSTAGE) * STAGE_BYTES;
     const int k_left = klen - ks * BKT;          // valid k in this step
-    const bool full = k_left >= BKT;
+    const char* ab = a_base + (long)ks * a_step;     // scalar arithmetic
+    const char* bb = b_base + (long)ks * b_step;
+    if (k_left >= BKT) {
 #pragma unroll
-    for (int j = 0; j < A_DMA; ++j) {
-      const char* src = a_src[j] + (long)ks * a_step;
-      if (!full && a_k[j] >= k_left) src = zero;
-      dma16(src, stage + (unsigned)(wave + j * NW) * 1024u);
-    }
+      for (int j = 0; j < A_DMA; ++j) dma16s(ab, a_off[j], stage + (unsigned)(lw + j * NL) * 1024u);
 #pragma unroll
-    for (int j = 0; j < B_DMA; ++j) {
-      const char* src = b_src[j] + (long)ks * b_step;
-      if (!full && b_k[j] >= k_left) src = zero;
-      dma16(src, stage + A_BYTES + (unsigned)(wave + j * NW) * 1024u);
+      for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + j * NL) * 1024u);
+    } else {
+      // ragged last step: chunks past the end of the contraction come from the zero block
+#pragma unroll
+      for (int j = 0; j < A_DMA; ++j) dma16(a_k[j] >= k_left ? zero : ab + a_off[j], stage + (unsigned)(lw + j * NL) * 1024u);
+#pragma unroll
+      for (int j = 0; j < B_DMA; ++j) dma16(b_k[j] >= k_left ? zero : bb + b_off[j], stage + A_BYTES + (unsigned)(lw + j * NL) * 1024u);
     }
   };
-  auto issue_prologue = [&]() {
+  auto issue_prologue = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s)
       if (s < nk) issue(s);
