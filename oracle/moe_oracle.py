@@ -19,7 +19,9 @@ backward, gate weight applied after FC2 in the FP8 variant).  The method reaches
 exactly the plain layer result, so every function below is the plain definition
 written out.  Readings where the paper is silent (softmax gate over the selected
 logits, ties toward the lower expert id, slot order by descending logit, stable
-order inside an expert's segment, dropless, scale = amax/448) are stated where
+order inside an expert's segment, dropless, scale = amax/448; for the FP8 backward
+GEMMs: a second quantisation of the weights along their other axis, and power-of-two
+group scales for the operands whose contraction index is the token) are stated where
 they are used.
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py against
@@ -439,3 +441,121 @@ def layer_bwd_fp8(x, logits, W1, W2, k: int, dy, fwd: dict, renorm: int = 1) -> 
     dx = combine(dxp, fwd["inv_perm"], None, T, k)
     dz = route_bwd(logits, fwd["idx"], fwd["w"], dw, renorm)
     return dict(dy_hat=dy_hat, dYp=dYp, dw=dw, dxp=dxp, dW1=dW1, dW2=dW2, dH=dH, dx=dx, dz=dz)
+
+
+# --------------------------------------------------------------------------
+# FP8 backward GEMMs: Section 7 "FP8 training" (per-token quantisation in the forward
+# orientation, per-channel quantisation within 128-token groups in the backward one)
+# --------------------------------------------------------------------------
+def pow2_exponent(amax) -> np.ndarray:
+    """Reading: a backward group scale is a power of two, 2^k with k the smallest integer for
+    which amax * 2^-k <= 448 (k = 0 for amax = 0), clamped to -126 <= k <= 127.  Such scales
+    are what block-scaled matrix hardware applies inside the contraction."""
+    a = np.asarray(amax, F64)
+    k = np.zeros(a.shape, dtype=np.int64)
+    pos = a > 0
+    if pos.any():
+        mant, ex = np.frexp(a[pos] / E4M3_MAX)        # a/448 = mant * 2^ex, mant in [0.5, 1)
+        k[pos] = np.where(mant == 0.5, ex - 1, ex)      # smallest k with a/448 <= 2^k
+    return np.clip(k, -126, 127)
+
+
+def token_groups(offsets, group: int = 128):
+    """Groups of `group` consecutive rows inside each expert's segment (a group never spans two
+    experts; the last group of a segment may be short).  Returns a list of (expert, lo, hi)."""
+    out = []
+    for e in range(len(offsets) - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        for g0 in range(lo, hi, group):
+            out.append((e, g0, min(g0 + group, hi)))
+    return out
+
+
+def quant_tokengroup_pow2(v, offsets, group: int = 128):
+    """Per-channel quantisation within 128-token groups of the dispatched (expert-ordered) rows,
+    power-of-two scales: codes uint8 [rows, cols] and exponents int64 [n_groups, cols]; the value
+    of an element is decode(code) * 2^k of its (group, column).  The product v * 2^-k is exact in
+    fp32, is clamped to +-448 and rounded to the nearest code (ties to even)."""
+    v32 = _f32(v)
+    rows, cols = v32.shape
+    groups = token_groups(offsets, group)
+    codes = np.zeros((rows, cols), dtype=np.uint8)
+    exps = np.zeros((len(groups), cols), dtype=np.int64)
+    for gi, (_, lo, hi) in enumerate(groups):
+        blk = v32[lo:hi].astype(F64)
+        k = pow2_exponent(np.abs(blk).max(axis=0))
+        exps[gi] = k
+        codes[lo:hi] = e4m3_encode(np.clip(blk * np.exp2(-k.astype(F64)), -E4M3_MAX, E4M3_MAX))
+    return codes, exps
+
+
+def dequant_tokengroup_pow2(codes, exps, offsets, group: int = 128) -> np.ndarray:
+    out = np.zeros(codes.shape, F64)
+    for gi, (_, lo, hi) in enumerate(token_groups(offsets, group)):
+        out[lo:hi] = e4m3_decode(codes[lo:hi]) * np.exp2(exps[gi].astype(F64))
+    return out
+
+
+def quant_weights_transposed(W1, W2):
+    """Second, transposed-orientation quantisation of the weights for the dgrad GEMMs: the
+    contraction of dA = dY * W2 runs over W2's output channels, so the scale must be constant
+    along them: one scale per input channel, i.e. per row of W2[e]^T ([f, d]); likewise per row
+    of W1[e]^T ([d, 2f]).  Returns the dequantised transposes, float64."""
+    E, two_f, d = W1.shape
+    f = W2.shape[2]
+    W1t = np.ascontiguousarray(np.transpose(_f32(W1), (0, 2, 1)))      # [E, d, 2f]
+    W2t = np.ascontiguousarray(np.transpose(_f32(W2), (0, 2, 1)))      # [E, f, d]
+    W1th = fake_quant_rows(W1t.reshape(E * d, two_f)).reshape(E, d, two_f)
+    W2th = fake_quant_rows(W2t.reshape(E * f, d)).reshape(E, f, d)
+    return W1th, W2th
+
+
+def expert_ffn_bwd_fp8(xp_hat, H, dYp, A_hat, offsets, W1, W2):
+    """The four backward GEMMs on E4M3 operands (float64 in between), straight-through casts.
+
+        dA  = Qrow(dY) * Q(W2^T)^T          per-token dY, per-input-channel W2
+        dH  = SwiGLU'(H, dA)                 on the saved pre-activations
+        dxp = Qrow(dH) * Q(W1^T)^T          per-token dH, per-input-channel W1
+        dW2[e] = Qg(dY_e)^T * Qg(A_e)        both per channel within 128-token groups (power-of-two
+        dW1[e] = Qg(dH_e)^T * Qg(xp_e)       scales), A and xp being what the forward GEMMs consumed
+    """
+    E, two_f, d = W1.shape
+    f = two_f // 2
+    M = dYp.shape[0]
+    W1th, W2th = quant_weights_transposed(W1, W2)
+    dYr = fake_quant_rows(dYp)
+    dA = np.zeros((M, f), F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        dA[lo:hi] = dYr[lo:hi] @ W2th[e].T
+    dG, dU = swiglu_bwd(H[:, :f], H[:, f:], dA)
+    dH = np.concatenate([dG, dU], axis=1)
+    dHr = fake_quant_rows(dH)
+    dxp = np.zeros((M, d), F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        dxp[lo:hi] = dHr[lo:hi] @ W1th[e].T
+    dYg = dequant_tokengroup_pow2(*quant_tokengroup_pow2(dYp, offsets), offsets)
+    dHg = dequant_tokengroup_pow2(*quant_tokengroup_pow2(dH, offsets), offsets)
+    Ag = dequant_tokengroup_pow2(*quant_tokengroup_pow2(A_hat, offsets), offsets)
+    Xg = dequant_tokengroup_pow2(*quant_tokengroup_pow2(xp_hat, offsets), offsets)
+    dW1 = np.zeros((E, two_f, d), F64)
+    dW2 = np.zeros((E, d, f), F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        dW2[e] = dYg[lo:hi].T @ Ag[lo:hi]
+        dW1[e] = dHg[lo:hi].T @ Xg[lo:hi]
+    return dict(dA=dA, dH=dH, dxp=dxp, dW1=dW1, dW2=dW2)
+
+
+def layer_bwd_fp8_gemm(x, logits, W1, W2, k: int, dy, fwd: dict, renorm: int = 1) -> dict:
+    """Backward of layer_fwd_fp8 with the backward GEMMs on E4M3 operands (expert_ffn_bwd_fp8);
+    everything outside the expert FFN is as in layer_bwd_fp8."""
+    T = x.shape[0]
+    dy_hat = dequant_colgroup128(*quant_colgroup128(dy))
+    dYp = dispatch(dy_hat, fwd["perm"], k, row_mul=fwd["w"])
+    dw = gate_grad(dy_hat, fwd["Y"], fwd["inv_perm"], T, k)
+    g = expert_ffn_bwd_fp8(fwd["xp"], fwd["H"], dYp, fwd["A"], fwd["offsets"], W1, W2)
+    dx = combine(g["dxp"], fwd["inv_perm"], None, T, k)
+    dz = route_bwd(logits, fwd["idx"], fwd["w"], dw, renorm)
+    return dict(dy_hat=dy_hat, dYp=dYp, dw=dw, dxp=g["dxp"], dW1=g["dW1"], dW2=g["dW2"], dH=g["dH"], dx=dx, dz=dz)

@@ -146,3 +146,107 @@ def test_fp8_layer_close_to_plain_layer_and_straight_through_backward():
     dYp = O.dispatch(dy_hat, q["perm"], cfg.k, row_mul=q["w"])
     dxp, dW1, dW2, _ = O.expert_ffn_bwd(q["xp"], q["H"], dYp, q["offsets"], inp["W1"], inp["W2"], A=q["A"])
     assert np.array_equal(g2["dW1"], dW1) and np.array_equal(g2["dW2"], dW2)
+
+
+# ---- FP8 backward GEMMs (Section 7: per-channel quantisation within 128-token groups) --------------------
+def test_pow2_exponent_is_the_smallest_power_of_two_that_fits():
+    # landmarks worked out by hand: 448 = 1.75 * 2^8
+    for amax, k in ((448.0, 0), (448.5, 1), (896.0, 1), (224.0, -1), (225.0, 0), (1.75, -8), (1.76, -7),
+                    (0.0, 0), (2.0 ** -20, -28), (3.0e38, 120)):
+        assert int(O.pow2_exponent(np.array([amax]))[0]) == k, amax
+    rng = np.random.default_rng(5)
+    a = np.abs(rng.standard_normal(2000)) * np.exp2(rng.integers(-30, 30, 2000))
+    k = O.pow2_exponent(a)
+    assert np.all(a * np.exp2(-k.astype(np.float64)) <= 448.0)
+    assert np.all(a * np.exp2(-(k - 1).astype(np.float64)) > 448.0)
+    assert int(O.pow2_exponent(np.array([1e-45]))[0]) == -126          # clamped
+
+
+def test_token_groups_never_span_experts():
+    assert O.token_groups([0, 130, 130, 386]) == [(0, 0, 128), (0, 128, 130), (2, 130, 258), (2, 258, 386)]
+    assert O.token_groups([0, 0, 5]) == [(1, 0, 5)]
+    assert O.token_groups([0, 0]) == []
+
+
+def _nearest_code_brute(p):
+    """Nearest e4m3 value by exhaustive search over the 256 codes, ties to the even mantissa."""
+    vals = O.e4m3_decode(np.arange(256, dtype=np.uint8))
+    best, bd = None, None
+    for c in range(256):
+        if np.isnan(vals[c]) or (c == 0x80 and p >= 0) or (c == 0x00 and (p < 0 or (p == 0 and np.signbit(p)))):
+            continue
+        dist = abs(vals[c] - p)
+        if bd is None or dist < bd or (dist == bd and (c & 1) == 0 and (best & 1) == 1):
+            best, bd = c, dist
+    return best
+
+
+def test_quant_tokengroup_pow2_against_brute_force():
+    rng = np.random.default_rng(11)
+    offsets = [0, 3, 3, 140, 150]
+    v = (rng.standard_normal((150, 5)) * np.exp2(rng.integers(-3, 6, (150, 5)))).astype(np.float32)
+    v[10:20, 2] = 0.0
+    v[3:140, 4] = 0.0                                     # a whole-zero (group, column): exponent 0, codes 0
+    codes, exps = O.quant_tokengroup_pow2(v, offsets)
+    groups = [(0, 3), (3, 131), (131, 140), (140, 150)]
+    assert exps.shape == (4, 5)
+    for gi, (lo, hi) in enumerate(groups):
+        for c in range(5):
+            amax = float(np.abs(v[lo:hi, c]).max())
+            k = 0
+            if amax > 0:
+                while amax * 2.0 ** -k > 448.0:
+                    k += 1
+                while amax * 2.0 ** -(k - 1) <= 448.0:
+                    k -= 1
+            assert exps[gi, c] == k
+            for t in range(lo, hi, 7):
+                assert codes[t, c] == _nearest_code_brute(float(v[t, c]) * 2.0 ** -k), (t, c)
+    deq = O.dequant_tokengroup_pow2(codes, exps, offsets)
+    assert np.all(np.abs(deq - v) <= np.abs(v) * 2.0 ** -4 + np.exp2(exps.max()) * 2.0 ** -9)
+
+
+def test_fp8_backward_gemms_exact_on_representable_operands_and_close_otherwise():
+    # (a) exactness: every operand of dA and dW2 lies on its e4m3 grid, so they equal the plain backward bit for bit
+    cfg = MoEConfig("t", T=40, d=16, E=3, k=2, f=8, dtype="f32", w_std=1.0, wr_std=1.0)
+    rng = np.random.default_rng(4)
+    grid = np.array([0, 1, 2, 3, 3.5, 4, 5, 6, 7, -1, -2, -3, -3.5, -4, -5, -6, -7], dtype=np.float32)
+    M = cfg.T * cfg.k
+    offsets = np.array([0, 30, 30, 80])
+    dYp = rng.choice(grid, size=(M, cfg.d)).astype(np.float32)
+    dYp[:, 0] = 7.0                                       # row amax 7 -> scale 1/64; column amax 7 -> 2^-6
+    dYp[0::2, :] *= 0.5
+    A = rng.choice(grid, size=(M, cfg.f)).astype(np.float32)
+    A[0, :] = 7.0; A[30, :] = 7.0
+    xp = rng.choice(grid, size=(M, cfg.d)).astype(np.float32)
+    H = rng.standard_normal((M, 2 * cfg.f))
+    W1 = rng.standard_normal((cfg.E, 2 * cfg.f, cfg.d)).astype(np.float32)
+    W2 = rng.choice(grid, size=(cfg.E, cfg.d, cfg.f)).astype(np.float32)
+    W2[:, 0, :] = 7.0                                     # every row of W2^T has amax 7
+    q = O.expert_ffn_bwd_fp8(xp, H, dYp, A, offsets, W1, W2)
+    dxp, dW1, dW2, dH = O.expert_ffn_bwd(xp, H, dYp.astype(np.float64), offsets, W1, W2, A=A.astype(np.float64))
+    dA_plain = np.zeros((M, cfg.f))
+    for e in range(cfg.E):
+        lo, hi = offsets[e], offsets[e + 1]
+        dA_plain[lo:hi] = dYp[lo:hi].astype(np.float64) @ W2[e].astype(np.float64)
+    assert np.array_equal(q["dA"], dA_plain)
+    assert np.array_equal(q["dW2"], dW2)
+    assert np.array_equal(q["dH"], dH)
+    # (b) the rest carries quantisation error only: a transposed operand, a dropped term or a wrong sign would be O(1)
+    for name, ref in (("dxp", dxp), ("dW1", dW1)):
+        e = np.abs(q[name] - ref).max() / np.abs(ref).max()
+        assert 1e-5 < e < 0.12, (name, e)
+
+
+def test_layer_bwd_fp8_gemm_close_to_straight_through_bf16_backward():
+    cfg = MoEConfig("t", T=96, d=32, E=4, k=2, f=24, dtype="bf16", w_std=0.2, wr_std=0.3)
+    inp = make_inputs(cfg, seed=2)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    q = O.layer_fwd_fp8(inp["x"], z, inp["W1"], inp["W2"], cfg.k)
+    g8 = O.layer_bwd_fp8_gemm(inp["x"], z, inp["W1"], inp["W2"], cfg.k, inp["dy"], q)
+    gs = O.layer_bwd_fp8(inp["x"], z, inp["W1"], inp["W2"], cfg.k, inp["dy"], q)
+    assert np.array_equal(g8["dw"], gs["dw"]) and np.array_equal(g8["dYp"], gs["dYp"])
+    for name in ("dx", "dW1", "dW2", "dH", "dz"):
+        e = np.abs(g8[name] - gs[name]).max() / max(np.abs(gs[name]).max(), 1e-30)
+        assert e < 0.12, (name, e)
+    assert np.abs(g8["dW1"] - gs["dW1"]).max() > 0
