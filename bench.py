@@ -18,6 +18,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_FP8_TFLOPS = 5000.0       # MI355X dense fp8 MFMA, published
 PEAK_HBM_GBPS = 8000.0
 # L2-fill + write-back bytes per grouped-GEMM launch (average of the six launches of one step) on the default
 # workload, from rocprofv3 --pmc FETCH_SIZE (x2.000, the factor a 1 GiB copy gives) and WRITE_SIZE (x1.000);
@@ -33,6 +34,8 @@ def parse():
     ap.add_argument("--config", default="mixtral", help="synthetic workload name (see synth/moe_inputs.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = T/8)")
+    ap.add_argument("--fp8-backward", action="store_true",
+                    help="fp8 configurations only: run the four backward GEMMs on e4m3 operands as well")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size reference for HBM byte counters")
     return ap.parse_args()
@@ -52,7 +55,7 @@ def to_dev_bf16(a, torch):
     return torch.from_numpy(bits).to("cuda:0").view(torch.bfloat16)
 
 
-def cpu_baseline_fp8(cfg, inp, tokens):
+def cpu_baseline_fp8(cfg, inp, tokens, fp8_backward=False):
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import moe_oracle as O
@@ -60,7 +63,7 @@ def cpu_baseline_fp8(cfg, inp, tokens):
     t0 = time.perf_counter()
     z = O.router_logits(x, inp["W_r"], inp["bias"]).astype(np.float32)
     fwd = O.layer_fwd_fp8(x, z, inp["W1"], inp["W2"], cfg.k, cfg.renorm)
-    O.layer_bwd_fp8(x, z, inp["W1"], inp["W2"], cfg.k, dy, fwd, cfg.renorm)
+    (O.layer_bwd_fp8_gemm if fp8_backward else O.layer_bwd_fp8)(x, z, inp["W1"], inp["W2"], cfg.k, dy, fwd, cfg.renorm)
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
@@ -115,13 +118,21 @@ def main():
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=fp8)
     if fp8:
         layer.set_fp8_weights(w1, w2)       # parameters are kept in E4M3 across steps (Section 7): outside the timed loop
+        if args.fp8_backward:
+            layer.set_fp8_backward_weights(w1, w2)
+    elif args.fp8_backward:
+        print("bench.py: --fp8-backward needs an fp8 configuration (--config mixtral_fp8)", file=sys.stderr)
+        sys.exit(2)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
     def step():
         if fp8:
             layer.forward_fp8(x, w_r, bias)
-            layer.backward_fp8(x, w_r, w1, w2, dy)
+            if args.fp8_backward:
+                layer.backward_fp8_gemm(x, w_r, dy)
+            else:
+                layer.backward_fp8(x, w_r, w1, w2, dy)
         else:
             layer.forward(x, w_r, bias, w1, w2)
             layer.backward(x, w_r, w1, w2, dy)
@@ -153,6 +164,8 @@ def main():
     # bf16 path: these two calls are exactly the six GEMM launches (fp8 path: plus the two row casts in the forward)
     gemm_ms = per_call["expert_ffn_fwd"] + per_call["expert_ffn_bwd"]
     gemm_tflops = gemm_flops / gemm_ms / 1e9
+    # all six GEMMs on the fp8 cores: price against the fp8 peak (the casts inside the two calls are counted as time)
+    peak = PEAK_FP8_TFLOPS if (fp8 and args.fp8_backward) else PEAK_BF16_TFLOPS
     row_bytes = (cfg.T + M) * cfg.d * 2.0
     counts = layer.counts.cpu().tolist()
 
@@ -164,13 +177,15 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8" if fp8 else "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d} E={cfg.E} top-{cfg.k} d_ff={cfg.f} SwiGLU, " +
-                               ("e4m3 dispatched activations / expert GEMMs / returned outputs forward, bf16 backward, "
+                               (("e4m3 dispatched activations / returned outputs, all six expert GEMMs on e4m3 operands, "
+                                 if args.fp8_backward else
+                                 "e4m3 dispatched activations / expert GEMMs / returned outputs forward, bf16 backward, ")
                                 if fp8 else "bf16 weights/activations, ") + "fp32 accumulate, fp32 weight gradients",
                    "tokens": cfg.T, "expert_rows": counts},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",
-                     "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_BF16_TFLOPS,
+                     "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s",
+                     "frac": gemm_tflops / peak,
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                      "flops_per_launch_avg": gemm_flops / 6, "launch_ms_avg": gemm_ms / 6},
         "gemm_tflops": {"fwd": 6.0 * M * cfg.d * cfg.f / per_call["expert_ffn_fwd"] / 1e9,
@@ -183,7 +198,8 @@ def main():
     }
     if not args.no_cpu_baseline:
         tokens = args.cpu_tokens or max(cfg.T // 8, 1)
-        out["cpu_baseline"] = (cpu_baseline_fp8 if fp8 else cpu_baseline)(cfg, inp, tokens)
+        out["cpu_baseline"] = (cpu_baseline_fp8(cfg, inp, tokens, args.fp8_backward) if fp8
+                               else cpu_baseline(cfg, inp, tokens))
     print(json.dumps(out))
 
 

@@ -173,6 +173,69 @@ int moe_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmo
 int moe_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols,
                     moe_qmode mode, void* dst, moe_dtype dst_dt, void* stream);
 
+/* ---- FP8 backward GEMMs of the expert FFN (Section 7 "FP8 training": per-token quantisation
+ * in the forward orientation, per-channel quantisation within 128-token groups for the
+ * backward pass; Section 5: E4M3 for all tensors) -------------------------------------------
+ * The four backward GEMMs on e4m3 operands with fp32 accumulation, straight-through casts:
+ *   dA    = Qrow(d_yp) * w2t[e]^T      d_yp cast per token; w2t[e] = W2[e]^T as [f,d] codes with one
+ *                                      scale per row (per input channel of W2: the second,
+ *                                      transposed-orientation quantisation of the weights)
+ *   dH    = SwiGLU'(h_save, dA)        bf16
+ *   d_xp  = Qrow(dH) * w1t[e]^T        w1t[e] = W1[e]^T as [d,2f] codes, one scale per row
+ *   d_w2[e] = Qg(d_yp_e)^T * Qg(a_deq_e),   d_w1[e] = Qg(dH_e)^T * Qg(xp_deq_e)
+ * Qg is moe_quant_fp8_tgroup below.  Every buffer is device memory owned by the caller; the
+ * intermediates are outputs too (they are what a parity check compares stage by stage) and
+ * none may alias another.  Requires offsets[E] = M, d and f multiples of 16, ldt >=
+ * moe_tgroup_tokens(M, E) and a multiple of 128.  Only enqueues work on `stream`. */
+typedef struct moe_ffn_bwd_fp8_args {
+  /* inputs */
+  const void* d_yp;            /* [M,d]  bf16: gradient of the FC2 output (already gate-weighted) */
+  const void* h_save;          /* [M,2f] bf16: [G|U] kept by the forward */
+  const void* xp_deq;          /* [M,d]  bf16: the dispatched activations FC1 consumed, dequantised */
+  const void* a_deq;           /* [M,f]  bf16: the FC2 input the forward consumed, dequantised */
+  const int32_t* offsets;      /* [E+1] */
+  const uint8_t* w1t;          /* [E,d,2f] e4m3 codes of W1[e]^T */
+  const float* w1t_scale;      /* [E,d] */
+  const uint8_t* w2t;          /* [E,f,d] e4m3 codes of W2[e]^T */
+  const float* w2t_scale;      /* [E,f] */
+  int M, d, E, f;
+  /* results */
+  void* d_xp;                  /* [M,d] bf16 */
+  void* d_w1;                  /* [E,2f,d] grad_dt */
+  void* d_w2;                  /* [E,d,f]  grad_dt */
+  moe_dtype grad_dt;           /* MOE_F32 | MOE_BF16 */
+  int accumulate;              /* as in moe_expert_ffn_bwd */
+  /* intermediates (all written) */
+  uint8_t* dy_codes; float* dy_scale;     /* [M,d], [M]: Qrow(d_yp) */
+  void* dh;                               /* [M,2f] bf16 */
+  uint8_t* dh_codes; float* dh_scale;     /* [M,2f], [M]: Qrow(dH) */
+  int32_t* pad_offsets;                   /* [E+1] */
+  long ldt;                               /* token stride of the transposed code matrices */
+  uint8_t* dy_t; uint8_t* dy_e8m0;        /* [d,ldt],  [ldt/128,d]  */
+  uint8_t* dh_t; uint8_t* dh_e8m0;        /* [2f,ldt], [ldt/128,2f] */
+  uint8_t* a_t;  uint8_t* a_e8m0;         /* [f,ldt],  [ldt/128,f]  */
+  uint8_t* x_t;  uint8_t* x_e8m0;         /* [d,ldt],  [ldt/128,d]  */
+} moe_ffn_bwd_fp8_args;
+int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* args, void* stream);
+
+/* Backward-orientation cast for the weight-gradient GEMMs (Section 7: per-channel quantisation
+ * within 128-token groups).  src [rows,cols] holds dispatched rows in expert order
+ * (offsets [E+1], offsets[E] = rows).  Groups are 128 consecutive rows inside one expert's
+ * segment (a group never spans two experts; a segment's last group may be short).  The
+ * paper gives no scale rule; here a group scale is the power of two 2^k with k the smallest
+ * integer such that amax * 2^-k <= 448 (k = 0 when amax = 0, clamped to [-126,127]), stored
+ * as the E8M0 byte k + 127, the form block-scaled matrix instructions apply inside the
+ * contraction; code = nearest-even e4m3 of clamp(v * 2^-k, +-448).  Codes are written
+ * transposed, codes_t[c*ldt + pad_offsets[e] + (r - offsets[e])], each expert's columns
+ * padded with zero codes to a multiple of 128 (pad_offsets [E+1] is written by this call;
+ * columns at or past pad_offsets[E] are not touched).  e8m0[(pad_offsets[e]/128 + j)*cols + c]
+ * is the scale of group j of expert e, column c.  ldt >= moe_tgroup_tokens(rows, E), ldt % 128
+ * = 0, cols % 16 = 0.  src_dt = MOE_F32 | MOE_BF16. */
+size_t moe_tgroup_tokens(int rows, int E);
+int moe_quant_fp8_tgroup(const void* src, moe_dtype src_dt, int rows, int cols,
+                         const int32_t* offsets, int E, int32_t* pad_offsets,
+                         uint8_t* codes_t, long ldt, uint8_t* e8m0, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

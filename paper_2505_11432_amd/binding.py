@@ -24,7 +24,21 @@ EXPORTS = (
     "moe_abi_version", "moe_last_hip_error", "moe_status_string", "moe_workspace_bytes",
     "moe_router_fwd", "moe_router_bwd", "moe_route", "moe_route_bwd", "moe_dispatch", "moe_combine",
     "moe_gate_grad", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_quant_fp8", "moe_dequant_fp8",
+    "moe_expert_ffn_bwd_fp8", "moe_tgroup_tokens", "moe_quant_fp8_tgroup",
 )
+
+
+class FfnBwdFp8Args(ctypes.Structure):
+    """Mirror of moe_ffn_bwd_fp8_args (include/moe.h), field for field."""
+    _fields_ = (
+        [(n, c_void_p) for n in ("d_yp", "h_save", "xp_deq", "a_deq", "offsets", "w1t", "w1t_scale", "w2t", "w2t_scale")]
+        + [(n, c_int) for n in ("M", "d", "E", "f")]
+        + [(n, c_void_p) for n in ("d_xp", "d_w1", "d_w2")]
+        + [("grad_dt", c_int), ("accumulate", c_int)]
+        + [(n, c_void_p) for n in ("dy_codes", "dy_scale", "dh", "dh_codes", "dh_scale", "pad_offsets")]
+        + [("ldt", ctypes.c_long)]
+        + [(n, c_void_p) for n in ("dy_t", "dy_e8m0", "dh_t", "dh_e8m0", "a_t", "a_e8m0", "x_t", "x_e8m0")]
+    )
 
 
 class MoEError(RuntimeError):
@@ -57,6 +71,9 @@ def _load() -> ctypes.CDLL:
         "moe_expert_ffn_bwd": (I, [P, P, P, P, P, P, P, I, I, I, I, I, P, P, P, I, I, P, Z, P]),
         "moe_quant_fp8": (I, [P, I, I, I, I, P, P, P]),
         "moe_dequant_fp8": (I, [P, P, I, I, I, P, I, P]),
+        "moe_expert_ffn_bwd_fp8": (I, [ctypes.POINTER(FfnBwdFp8Args), P]),
+        "moe_tgroup_tokens": (Z, [I, I]),
+        "moe_quant_fp8_tgroup": (I, [P, I, I, I, P, I, P, P, ctypes.c_long, P, P]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -179,3 +196,36 @@ def moe_dequant_fp8(codes, scales, mode, dst):
     rows, cols = codes.shape
     _check("moe_dequant_fp8", _lib.moe_dequant_fp8(_p(codes), _p(scales), rows, cols, mode, _p(dst),
                                                    dtype_code(dst.dtype), _stream()))
+
+
+def moe_tgroup_tokens(rows: int, E: int) -> int:
+    return _lib.moe_tgroup_tokens(rows, E)
+
+
+def moe_quant_fp8_tgroup(src, offsets, pad_offsets, codes_t, e8m0):
+    """src [rows, cols]; codes_t [cols, ldt] uint8; e8m0 [ldt/128, cols] uint8; pad_offsets [E+1] int32."""
+    rows, cols = src.shape
+    E = offsets.numel() - 1
+    ldt = codes_t.shape[1]
+    _check("moe_quant_fp8_tgroup", _lib.moe_quant_fp8_tgroup(_p(src), dtype_code(src.dtype), rows, cols, _p(offsets), E,
+                                                             _p(pad_offsets), _p(codes_t), ldt, _p(e8m0), _stream()))
+
+
+def moe_expert_ffn_bwd_fp8(d_yp, h_save, xp_deq, a_deq, offsets, w1t, w1t_scale, w2t, w2t_scale, d_xp, d_w1, d_w2,
+                           accumulate, inter):
+    """`inter` maps the names of the intermediate buffers of moe_ffn_bwd_fp8_args to tensors."""
+    M, d = d_yp.shape
+    f = a_deq.shape[1]
+    a = FfnBwdFp8Args()
+    for name, t in (("d_yp", d_yp), ("h_save", h_save), ("xp_deq", xp_deq), ("a_deq", a_deq), ("offsets", offsets),
+                    ("w1t", w1t), ("w1t_scale", w1t_scale), ("w2t", w2t), ("w2t_scale", w2t_scale), ("d_xp", d_xp),
+                    ("d_w1", d_w1), ("d_w2", d_w2)):
+        setattr(a, name, _p(t))
+    for name in ("dy_codes", "dy_scale", "dh", "dh_codes", "dh_scale", "pad_offsets", "dy_t", "dy_e8m0", "dh_t",
+                 "dh_e8m0", "a_t", "a_e8m0", "x_t", "x_e8m0"):
+        setattr(a, name, _p(inter[name]))
+    a.M, a.d, a.E, a.f = M, d, offsets.numel() - 1, f
+    a.grad_dt = dtype_code(d_w1.dtype)
+    a.accumulate = int(accumulate)
+    a.ldt = inter["dy_t"].shape[1]
+    _check("moe_expert_ffn_bwd_fp8", _lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), _stream()))

@@ -357,4 +357,66 @@ int moe_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int col
   return launch_dequant_fp8(codes, scales, rows, cols, mode, dst, dst_dt, as_stream(stream));
 }
 
+size_t moe_tgroup_tokens(int rows, int E) {
+  if (rows < 0 || E < 1) return 0;
+  return ((size_t)(rows + 127) / 128 + (size_t)E) * 128;
+}
+
+int moe_quant_fp8_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, const int32_t* offsets, int E,
+                         int32_t* pad_offsets, uint8_t* codes_t, long ldt, uint8_t* e8m0, void* stream) {
+  if (rows < 0 || cols < 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (src_dt != MOE_F32 && src_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (cols % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (!offsets || !pad_offsets) return MOE_ERR_INVALID;
+  if (ldt % 128 != 0 || ldt < (long)moe_tgroup_tokens(rows, E)) return MOE_ERR_INVALID;
+  if (cols > 0 && (!codes_t || !e8m0 || (rows > 0 && !src))) return MOE_ERR_INVALID;
+  if (!aligned16(src) || !aligned16(codes_t)) return MOE_ERR_UNSUPPORTED;
+  int rc = launch_tgroup_offsets(offsets, E, pad_offsets, as_stream(stream));
+  if (rc != MOE_OK) return rc;
+  return launch_quant_tgroup(src, src_dt, rows, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, as_stream(stream));
+}
+
+int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* a, void* stream) {
+  if (!a) return MOE_ERR_INVALID;
+  const int M = a->M, d = a->d, E = a->E, f = a->f;
+  if (M < 0 || d <= 0 || f <= 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (d % 16 != 0 || f % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if (a->grad_dt != MOE_F32 && a->grad_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (a->ldt % 128 != 0 || a->ldt < (long)moe_tgroup_tokens(M, E)) return MOE_ERR_INVALID;
+  const void* ptrs[] = {a->d_yp, a->h_save, a->xp_deq, a->a_deq, a->offsets, a->w1t, a->w1t_scale, a->w2t, a->w2t_scale,
+                        a->d_xp, a->d_w1, a->d_w2, a->dy_codes, a->dy_scale, a->dh, a->dh_codes, a->dh_scale,
+                        a->pad_offsets, a->dy_t, a->dy_e8m0, a->dh_t, a->dh_e8m0, a->a_t, a->a_e8m0, a->x_t, a->x_e8m0};
+  for (const void* q : ptrs)
+    if (!q) return MOE_ERR_INVALID;
+  const void* vec[] = {a->d_yp, a->h_save, a->xp_deq, a->a_deq, a->w1t, a->w2t, a->d_xp, a->d_w1, a->d_w2, a->dy_codes,
+                       a->dh, a->dh_codes, a->dy_t, a->dh_t, a->a_t, a->x_t};
+  for (const void* q : vec)
+    if (!aligned16(q)) return MOE_ERR_UNSUPPORTED;
+  hipStream_t s = as_stream(stream);
+  const int acc = a->accumulate != 0;
+  int rc = launch_quant_fp8(a->d_yp, MOE_BF16, M, d, MOE_Q_ROW, a->dy_codes, a->dy_scale, s);
+  if (rc != MOE_OK) return rc;
+  rc = mfma_dgrad2_swiglu_bwd_fp8(a->dy_codes, a->dy_scale, a->w2t, a->w2t_scale, a->offsets, M, d, E, f, a->h_save, a->dh,
+                                  nullptr, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_quant_fp8(a->dh, MOE_BF16, M, 2 * f, MOE_Q_ROW, a->dh_codes, a->dh_scale, s);
+  if (rc != MOE_OK) return rc;
+  rc = mfma_rowseg_nt_fp8(a->dh_codes, a->dh_scale, a->w1t, a->w1t_scale, (long)d * 2 * f, a->offsets, M, d, 2 * f, E,
+                          a->d_xp, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_tgroup_offsets(a->offsets, E, a->pad_offsets, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_quant_tgroup(a->d_yp, MOE_BF16, M, d, a->offsets, a->pad_offsets, E, a->dy_t, a->ldt, a->dy_e8m0, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_quant_tgroup(a->a_deq, MOE_BF16, M, f, a->offsets, a->pad_offsets, E, a->a_t, a->ldt, a->a_e8m0, s);
+  if (rc != MOE_OK) return rc;
+  rc = mfma_wgrad_fp8(a->dy_t, a->dy_e8m0, a->a_t, a->a_e8m0, a->ldt, a->pad_offsets, d, f, E, a->d_w2, a->grad_dt, acc, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_quant_tgroup(a->dh, MOE_BF16, M, 2 * f, a->offsets, a->pad_offsets, E, a->dh_t, a->ldt, a->dh_e8m0, s);
+  if (rc != MOE_OK) return rc;
+  rc = launch_quant_tgroup(a->xp_deq, MOE_BF16, M, d, a->offsets, a->pad_offsets, E, a->x_t, a->ldt, a->x_e8m0, s);
+  if (rc != MOE_OK) return rc;
+  return mfma_wgrad_fp8(a->dh_t, a->dh_e8m0, a->x_t, a->x_e8m0, a->ldt, a->pad_offsets, 2 * f, d, E, a->d_w1, a->grad_dt, acc, s);
+}
+
 }  // extern "C"

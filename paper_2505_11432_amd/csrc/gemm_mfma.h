@@ -38,6 +38,10 @@ struct Args {
   const float* bias;                 // EPI_BIAS_F32: per-column fp32 bias or NULL; C is fp32, any N
   const float* row_scale;            // e4m3 operands: per-row scale of A [rows] (NULL = 1)
   const float* col_scale; long cs_es; // e4m3 operands: per-output-channel scale of B [E, N(+f)] and its expert stride
+  // e4m3 weight-gradient GEMM (KSEG): power-of-two group scales, one E8M0 byte per (128-k group, row) of each
+  // operand, applied by the block-scaled MFMA; [groups, rows] with the given row counts as leading dimensions
+  const uint8_t* a_e8m0; long a_e8_ld;
+  const uint8_t* b_e8m0; long b_e8_ld;
   unsigned long long* clk_out;       // tuning aid (NULL in the library): per-block {core clocks, 100 MHz ticks}
 };
 

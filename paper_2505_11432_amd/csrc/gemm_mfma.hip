@@ -136,6 +136,38 @@ int mfma_rowseg_nt_fp8(const void* A, const float* a_scale, const void* W, const
   return launch<256, 256, 128, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_STORE, bf16, uint8_t>(a, rowseg_blocks(M, E, N, 256, 256), s);
 }
 
+
+// e4m3 dgrad2 fused with the SwiGLU derivative: dA = (d_yp*s_row) * (w2t[e]*s_ch)^T with w2t[e] = W2[e]^T stored
+// [f, d] (second, transposed-orientation quantisation of the weights); reads H, writes dH (and A when asked)
+int mfma_dgrad2_swiglu_bwd_fp8(const void* dyq, const float* dyq_scale, const void* w2t, const float* w2t_scale,
+                               const int32_t* offsets, int M, int d, int E, int f, const void* H, void* dH, void* A_out,
+                               hipStream_t s) {
+  Args a{};
+  a.A = dyq; a.lda = d;
+  a.B = w2t; a.ldb = d; a.b_es = (long)f * d;
+  a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d;
+  a.H = (bf16*)const_cast<void*>(H); a.dH = (bf16*)dH; a.A_out = (bf16*)A_out;
+  a.row_scale = dyq_scale; a.col_scale = w2t_scale; a.cs_es = f;
+  return launch<256, 256, 128, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_SWIGLU_BWD, bf16, uint8_t>(a, rowseg_blocks(M, E, f, 256, 256), s);
+}
+
+// e4m3 weight gradient: C[e][Mo,N] (+)= P_t[Mo, tokens_e] * Q_t[N, tokens_e]^T on transposed (token-minor) codes
+// whose expert segments are padded to whole 128-token groups (pad_offsets), with one power-of-two scale per
+// (group, channel) applied by the block-scaled MFMA
+int mfma_wgrad_fp8(const void* Pt, const uint8_t* p_e8m0, const void* Qt, const uint8_t* q_e8m0, long ldt,
+                   const int32_t* pad_offsets, int Mo, int N, int E, void* C, moe_dtype c_dt, int accumulate,
+                   hipStream_t s) {
+  Args a{};
+  a.A = Pt; a.lda = ldt;
+  a.B = Qt; a.ldb = ldt; a.b_es = 0;
+  a.C = C; a.ldc = N; a.c_es = (long)Mo * N; a.offsets = pad_offsets; a.E = E; a.M = Mo; a.N = N; a.K = 0;
+  a.accumulate = accumulate;
+  a.a_e8m0 = p_e8m0; a.a_e8_ld = Mo; a.b_e8m0 = q_e8m0; a.b_e8_ld = N;
+  const long blocks = (long)E * cdiv(Mo, 256) * cdiv(N, 256);
+  if (c_dt == MOE_F32) return launch<256, 256, 128, 2, 4, 2, KMAJOR, KMAJOR, KSEG, EPI_STORE, float, uint8_t>(a, blocks, s);
+  return launch<256, 256, 128, 2, 4, 2, KMAJOR, KMAJOR, KSEG, EPI_STORE, bf16, uint8_t>(a, blocks, s);
+}
+
 // logits[T,E] = x[T,d] * w_r[E,d]^T (+ bias), fp32 out
 int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, int d, int E, float* logits,
                     hipStream_t s) {

@@ -179,6 +179,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr bool FP8 = ESZ == 1;
   constexpr int CHUNK = 16 / ESZ;                     // elements per 16-byte chunk
   static_assert(!FP8 || (LA == KMAJOR && LB == KMAJOR), "e4m3 operands are K-major");
+  constexpr bool BSCALE = FP8 && MODE == KSEG;        // block-scaled contraction over tokens (weight gradients)
+  static_assert(!BSCALE || (BKT == 128 && NSTAGE == 2), "one 128-token scale group per k-step; scale loads rely on the vmcnt(0) wait");
   constexpr int A_BYTES = DmaTileBytes<LA, BM, BKT, ESZ>::value, B_BYTES = DmaTileBytes<LB, BN, BKT, ESZ>::value;
   constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;
@@ -247,6 +249,14 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   const char* b_base = zero;
   unsigned a_off[A_DMA], b_off[B_DMA];   // this lane's byte offset from the base, fixed over the k loop
   int a_k[A_DMA], b_k[B_DMA];       // k coordinate (relative to the k-step start) this lane's chunk begins at
+  // block scales of the current and the next k-step for this lane's fragment rows (byte 0 of each register)
+  int sa_cur[TM], sb_cur[TN], sa_nxt[TM], sb_nxt[TN];
+  const uint8_t* sa_ptr[TM];
+  const uint8_t* sb_ptr[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { sa_cur[i] = sa_nxt[i] = 127; sa_ptr[i] = nullptr; }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { sb_cur[j] = sb_nxt[j] = 127; sb_ptr[j] = nullptr; }
   const long a_step = (LA == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.lda * ESZ;   // bytes per k-step
   const long b_step = (LB == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.ldb * ESZ;
 
@@ -340,7 +350,25 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       }
     }
     m0 = real_m0; n0 = real_n0;
+    if constexpr (BSCALE) {
+      const long g0 = k_begin / BKT;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        sa_ptr[i] = p.a_e8m0 + g0 * p.a_e8_ld + min(m0 + wm * WTM + i * 32 + (lane & 31), p.M - 1);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        sb_ptr[j] = p.b_e8m0 + g0 * p.b_e8_ld + min(n0 + wn * WTN + j * 32 + (lane & 31), p.N - 1);
+    }
     return true;
+  };
+  // fetch the block scales of k-step ks of the open tile into the "next" registers
+  auto load_scales = [&](int ks) __attribute__((always_inline)) {
+    if constexpr (BSCALE) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) sa_nxt[i] = sa_ptr[i][(long)ks * p.a_e8_ld];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) sb_nxt[j] = sb_ptr[j][(long)ks * p.b_e8_ld];
+    }
   };
 
   // Issue the loads of k-step `ks` of the open tile into ring slot ks % NSTAGE.  Only the last step can be ragged.
@@ -372,6 +400,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
   if (!open_tile(slot)) return;
   issue_prologue();
+  if (nk > 0) load_scales(0);
 
   for (;;) {
     unsigned long long clk0 = 0, rt0 = 0;
@@ -392,6 +421,14 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       else wait_vmcnt<0>();
       __syncthreads();
       if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+      if constexpr (BSCALE) {
+        // the wait above covered the scale loads issued one step ago
+#pragma unroll
+        for (int i = 0; i < TM; ++i) sa_cur[i] = sa_nxt[i];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) sb_cur[j] = sb_nxt[j];
+        if (kt + 1 < nk) load_scales(kt + 1);
+      }
       const char* at = smem + (kt % NSTAGE) * STAGE_BYTES;
       const char* bt = at + A_BYTES;
       if constexpr (PROBE == 2) continue;
@@ -408,7 +445,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
           for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[j], af[i], acc[i][j], 0, 0, 0, 127, 0, 127);
+              if constexpr (BSCALE)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[j], af[i], acc[i][j], 0, 0, 0, sb_cur[j], 0, sa_cur[i]);
+              else
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[j], af[i], acc[i][j], 0, 0, 0, 127, 0, 127);
         } else {
           bf16x8 af[TM], bfr[TN];
 #pragma unroll
@@ -433,11 +473,14 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     slot += 1;
     __syncthreads();                      // every wave has read its last fragments: the ring is free
     const bool has_next = open_tile(slot);
-    if (has_next) issue_prologue();
+    if (has_next) {
+      issue_prologue();
+      if (nk > 0) load_scales(0);
+    }
     {
       const int e = ep_e, m0 = ep_m0, m_end = ep_m_end, n0 = ep_n0;
       (void)e;
-      if constexpr (FP8) {
+      if constexpr (FP8 && !BSCALE) {
         // dequantise: output = acc * scale of the row (token) * scale of the output channel
         const int lrow = lane & 31, lcol = (lane >> 5) << 2;
 #pragma unroll

@@ -80,6 +80,9 @@ int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_
                      float* scales, hipStream_t s);
 int launch_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols, moe_qmode mode, void* dst,
                        moe_dtype dst_dt, hipStream_t s);
+int launch_tgroup_offsets(const int32_t* offsets, int E, int32_t* pad_offsets, hipStream_t s);
+int launch_quant_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, const int32_t* offsets,
+                        const int32_t* pad_offsets, int E, uint8_t* codes_t, long ldt, uint8_t* e8m0, hipStream_t s);
 
 // bf16 grouped GEMMs on the matrix cores (gemm_mfma.hip)
 int mfma_fc1_swiglu(const void* xp, const void* w1, const int32_t* offsets, int M, int d, int E, int f, void* H,
@@ -97,6 +100,12 @@ int mfma_fc1_swiglu_fp8(const void* xp, const float* xp_scale, const void* w1, c
                         const int32_t* offsets, int M, int d, int E, int f, void* H, void* A_out, hipStream_t s);
 int mfma_rowseg_nt_fp8(const void* A, const float* a_scale, const void* W, const float* w_scale, long w_es,
                        const int32_t* offsets, int M, int N, int K, int E, void* C, hipStream_t s);
+int mfma_dgrad2_swiglu_bwd_fp8(const void* dyq, const float* dyq_scale, const void* w2t, const float* w2t_scale,
+                               const int32_t* offsets, int M, int d, int E, int f, const void* H, void* dH, void* A_out,
+                               hipStream_t s);
+int mfma_wgrad_fp8(const void* Pt, const uint8_t* p_e8m0, const void* Qt, const uint8_t* q_e8m0, long ldt,
+                   const int32_t* pad_offsets, int Mo, int N, int E, void* C, moe_dtype c_dt, int accumulate,
+                   hipStream_t s);
 int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, int d, int E, float* logits,
                     hipStream_t s);
 size_t router_bwd_ws_bytes(int T, int d, int E);

@@ -138,6 +138,105 @@ __global__ void __launch_bounds__(256) quant_colgroup_kernel(const T* __restrict
   }
 }
 
+
+// ---- backward-orientation cast for the weight-gradient GEMMs ---------------------------------------------
+// Section 7 "FP8 training": per-channel quantisation within 128-token groups for the backward pass.  The
+// contraction index of a weight-gradient GEMM is the token, so the codes are written transposed ([channel]
+// [token], K-major for the matrix cores) and every expert's segment is padded with zero codes to a multiple
+// of 128 tokens: a group never spans two experts, every k-step of the GEMM is one whole group, and the group
+// scale is a power of two (E8M0 byte), which the block-scaled MFMA applies inside the contraction.
+// Scale rule: k = smallest integer with amax * 2^-k <= 448 (448 = 1.75 * 2^8), k = 0 for amax = 0,
+// clamped to [-126, 127]; byte = k + 127; code = nearest-even e4m3 of clamp(v * 2^-k, +-448).
+
+// pad_offsets[e] = first padded token column of expert e (a multiple of 128); pad_offsets[E] = total.
+__global__ void tgroup_offsets_kernel(const int32_t* __restrict__ offsets, int E, int32_t* __restrict__ pad_offsets) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    int run = 0;
+    pad_offsets[0] = 0;
+    for (int e = 0; e < E; ++e) {
+      run += (offsets[e + 1] - offsets[e] + 127) / 128 * 128;
+      pad_offsets[e + 1] = run;
+    }
+  }
+}
+
+// One block per (padded 128-token group, 64-channel slab).  Thread (rg, cq) holds rows rg, rg+16, ... (8 rows)
+// of four channels; channel maxima go through LDS; the codes are transposed through LDS so that global
+// memory sees 16-byte lanes forming 128-byte rows (one channel x 128 tokens).
+template <typename T>
+__global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__ src, int cols,
+                                                           const int32_t* __restrict__ offsets,
+                                                           const int32_t* __restrict__ pad_offsets, int E,
+                                                           uint8_t* __restrict__ codes_t, long ldt,
+                                                           uint8_t* __restrict__ e8m0, int slabs) {
+  __shared__ float cmax[16][64];
+  __shared__ __attribute__((aligned(16))) uint8_t tile[64][128 + 16];
+  const int g = blockIdx.x / slabs;
+  const int tok0 = g * 128;                         // padded token column of this group
+  if (tok0 >= pad_offsets[E]) return;
+  int lo = 0, hi = E;                               // expert whose padded range holds tok0
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (pad_offsets[mid] <= tok0) lo = mid; else hi = mid;
+  }
+  const int e = lo;
+  const int r0 = offsets[e] + (tok0 - pad_offsets[e]);      // first source row of the group
+  const int r_end = offsets[e + 1];
+  const int cq = threadIdx.x % 16, rg = threadIdx.x / 16;
+  const int c0 = (blockIdx.x % slabs) * 64;
+  const int c = c0 + cq * 4;
+  const bool col_ok = c < cols;
+  float v[8][4];
+  float amax[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = r0 + rg + 16 * i;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[i][j] = 0.f;
+    if (col_ok && r < r_end) {
+      const T* p = src + (long)r * cols + c;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[i][j] = to_f32(p[j]);
+        amax[j] = fmaxf(amax[j], fabsf(v[i][j]));
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) cmax[rg][cq * 4 + j] = amax[j];
+  __syncthreads();
+  float inv[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float m = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) m = fmaxf(m, cmax[q][cq * 4 + j]);
+    int k = 0;
+    if (m > 0.f) {
+      const unsigned bits = __float_as_uint(m);
+      k = (int)((bits >> 23) & 0xffu) - 127 - 8 + ((bits & 0x7fffffu) > 0x600000u ? 1 : 0);
+      k = max(-126, min(127, k));
+    }
+    inv[j] = __uint_as_float((unsigned)(127 - k) << 23);          // 2^-k, exact
+    if (rg == 0 && col_ok) e8m0[(long)g * cols + c + j] = (uint8_t)(k + 127);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const unsigned w = pack4_e4m3(v[i][0] * inv[0], v[i][1] * inv[1], v[i][2] * inv[2], v[i][3] * inv[3]);
+    const int t = rg + 16 * i;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tile[cq * 4 + j][t] = (uint8_t)(w >> (8 * j));
+  }
+  __syncthreads();
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int ch = pass * 32 + threadIdx.x / 8, seg = threadIdx.x % 8;
+    if (c0 + ch < cols)
+      *reinterpret_cast<uint4*>(codes_t + (long)(c0 + ch) * ldt + tok0 + seg * 16) =
+          *reinterpret_cast<const uint4*>(&tile[ch][seg * 16]);
+  }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256) dequant_kernel(const uint8_t* __restrict__ codes,
                                                       const float* __restrict__ scales, int rows, int cols, int mode,
@@ -177,6 +276,27 @@ int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_
     if (src_dt == MOE_F32) quant_colgroup_kernel<float><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales, slabs);
     else quant_colgroup_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales, slabs);
   }
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
+int launch_tgroup_offsets(const int32_t* offsets, int E, int32_t* pad_offsets, hipStream_t s) {
+  tgroup_offsets_kernel<<<1, 64, 0, s>>>(offsets, E, pad_offsets);
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
+int launch_quant_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, const int32_t* offsets,
+                        const int32_t* pad_offsets, int E, uint8_t* codes_t, long ldt, uint8_t* e8m0, hipStream_t s) {
+  if (cols == 0) return MOE_OK;
+  const int slabs = cdiv(cols, 64);
+  const int groups = cdiv(rows, 128) + E;              // upper bound on the padded group count
+  const long grid = (long)groups * slabs;
+  if (grid <= 0 || grid > 0x7fffffffL) return MOE_ERR_UNSUPPORTED;
+  if (src_dt == MOE_F32)
+    quant_tgroup_kernel<float><<<(int)grid, 256, 0, s>>>((const float*)src, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, slabs);
+  else
+    quant_tgroup_kernel<bf16><<<(int)grid, 256, 0, s>>>((const bf16*)src, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, slabs);
   MOE_LAUNCH_CHECK();
   return MOE_OK;
 }

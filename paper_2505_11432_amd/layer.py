@@ -93,6 +93,57 @@ class MoELayer:
         B.moe_quant_fp8(w1.view(E * two_f, d), B.Q_ROW, self.w1_codes.view(E * two_f, d), self.w1_scale.view(-1))
         B.moe_quant_fp8(w2.view(E * d, f), B.Q_ROW, self.w2_codes.view(E * d, f), self.w2_scale.view(-1))
 
+    def set_fp8_backward_weights(self, w1, w2):
+        """Second, transposed-orientation E4M3 copies of the weights for the dgrad GEMMs (one scale per input
+        channel), also kept across steps, and the buffers the FP8 backward writes.  The transposition is a
+        layout change of a parameter done once at set-up (torch), not a step of the timed path."""
+        E, two_f, d = w1.shape
+        f = two_f // 2
+        M = self.M
+        dev = dict(device=w1.device)
+        u8 = dict(dtype=torch.uint8, **dev)
+        f32 = dict(dtype=torch.float32, **dev)
+        w1t = w1.transpose(1, 2).contiguous()          # [E, d, 2f]
+        w2t = w2.transpose(1, 2).contiguous()          # [E, f, d]
+        self.w1t_codes = torch.empty((E, d, two_f), **u8)
+        self.w1t_scale = torch.empty((E, d), **f32)
+        self.w2t_codes = torch.empty((E, f, d), **u8)
+        self.w2t_scale = torch.empty((E, f), **f32)
+        B.moe_quant_fp8(w1t.view(E * d, two_f), B.Q_ROW, self.w1t_codes.view(E * d, two_f), self.w1t_scale.view(-1))
+        B.moe_quant_fp8(w2t.view(E * f, d), B.Q_ROW, self.w2t_codes.view(E * f, d), self.w2t_scale.view(-1))
+        del w1t, w2t
+        ldt = B.moe_tgroup_tokens(M, E)
+        G = ldt // 128
+        self.bwd8 = dict(
+            dy_codes=torch.empty((M, d), **u8), dy_scale=torch.empty((M,), **f32),
+            dh=torch.empty((M, two_f), dtype=torch.bfloat16, **dev),
+            dh_codes=torch.empty((M, two_f), **u8), dh_scale=torch.empty((M,), **f32),
+            pad_offsets=torch.empty((E + 1,), dtype=torch.int32, **dev),
+            dy_t=torch.zeros((d, ldt), **u8), dy_e8m0=torch.zeros((G, d), **u8),
+            dh_t=torch.zeros((two_f, ldt), **u8), dh_e8m0=torch.zeros((G, two_f), **u8),
+            a_t=torch.zeros((f, ldt), **u8), a_e8m0=torch.zeros((G, f), **u8),
+            x_t=torch.zeros((d, ldt), **u8), x_e8m0=torch.zeros((G, d), **u8))
+
+    def backward_fp8_gemm(self, x, w_r, dy, with_router: bool = True):
+        """Backward of forward_fp8 with the four expert GEMMs on E4M3 operands (Section 7: per-channel
+        quantisation within 128-token groups for the backward pass); everything else as in backward_fp8."""
+        c = self._call
+        c("quant_dy", B.moe_quant_fp8, dy, B.Q_COLGROUP128, self.dy_codes, self.dy_scale)
+        c("dequant_dy", B.moe_dequant_fp8, self.dy_codes, self.dy_scale, B.Q_COLGROUP128, self.dy_deq)
+        c("gate_grad", B.moe_gate_grad, self.dy_deq, self.yp, self.yp_scale, self.inv_perm, self.k, self.d_topk_w)
+        c("dispatch_bwd_of_combine", B.moe_dispatch, self.dy_deq, None, self.inv_perm, self.topk_w.view(-1), self.k,
+          self.d_yp, None)
+        c("dequant_xp", B.moe_dequant_fp8, self.xp, self.xp_scale, B.Q_ROW, self.xp_deq)
+        c("dequant_a", B.moe_dequant_fp8, self.a_codes, self.a_scale, B.Q_ROW, self.a_deq)
+        c("expert_ffn_bwd", B.moe_expert_ffn_bwd_fp8, self.d_yp, self.h_save, self.xp_deq, self.a_deq, self.offsets,
+          self.w1t_codes, self.w1t_scale, self.w2t_codes, self.w2t_scale, self.d_xp, self.d_w1, self.d_w2, 0, self.bwd8)
+        c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, None, self.k, self.dx)
+        c("route_bwd", B.moe_route_bwd, self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E,
+          self.renorm, self.d_logits)
+        if with_router:
+            c("router_bwd", B.moe_router_bwd, x, w_r, self.d_logits, self.d_w_r, self.dx, self.workspace)
+        return self.dx
+
     def forward_fp8(self, x, w_r, bias, logits=None):
         """Forward with E4M3 dispatched activations and returned expert outputs (per-token scales), e4m3 expert
         GEMMs, gate weight applied after FC2 on the dequantised outputs."""

@@ -86,3 +86,35 @@ def test_argument_errors_without_gpu(lib):
     assert lib.moe_quant_fp8(fake, 1, 4, 32, 5, fake, fake, null) == -1
     assert lib.moe_quant_fp8(fake, 1, 4, 20, 0, fake, fake, null) == -2
     assert lib.moe_quant_fp8(null, 1, 0, 32, 0, null, null, null) == 0
+
+
+def test_fp8_backward_argument_errors_without_gpu(lib):
+    from paper_2505_11432_amd.binding import FfnBwdFp8Args
+    P, L = ctypes.c_void_p, ctypes.c_long
+    null, fake = P(0), P(4096)
+    lib.moe_tgroup_tokens.restype = ctypes.c_size_t
+    assert lib.moe_tgroup_tokens(16384, 8) == (128 + 8) * 128
+    assert lib.moe_tgroup_tokens(130, 3) == (2 + 3) * 128
+    assert lib.moe_tgroup_tokens(-1, 3) == 0
+    # token-group cast: leading dimension too small / not a multiple of 128, columns not a multiple of 16, NULL offsets
+    assert lib.moe_quant_fp8_tgroup(fake, 1, 256, 64, fake, 2, fake, fake, L(384), fake, null) == -1
+    assert lib.moe_quant_fp8_tgroup(fake, 1, 256, 64, fake, 2, fake, fake, L(520), fake, null) == -1
+    assert lib.moe_quant_fp8_tgroup(fake, 1, 256, 24, fake, 2, fake, fake, L(512), fake, null) == -2
+    assert lib.moe_quant_fp8_tgroup(fake, 1, 256, 64, null, 2, fake, fake, L(512), fake, null) == -1
+    lib.moe_expert_ffn_bwd_fp8.argtypes = [ctypes.POINTER(FfnBwdFp8Args), P]
+    assert lib.moe_expert_ffn_bwd_fp8(None, null) == -1
+    a = FfnBwdFp8Args()
+    for name, _ in FfnBwdFp8Args._fields_:
+        if name not in ("M", "d", "E", "f", "grad_dt", "accumulate", "ldt"):
+            setattr(a, name, 4096)
+    a.M, a.d, a.E, a.f, a.grad_dt, a.accumulate, a.ldt = 256, 64, 2, 32, 0, 0, 512
+    a.ldt = 384                                       # too small for 256 rows and 2 experts
+    assert lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), null) == -1
+    a.ldt = 512
+    a.f = 24
+    assert lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), null) == -2
+    a.f = 32
+    a.dh_t = None
+    assert lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), null) == -1
+    a.dh_t = 4100                                     # misaligned
+    assert lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), null) == -2

@@ -365,3 +365,137 @@ def test_layer_fp8_forward_backward(B, cfg):
     plain = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], k)
     print("   y end to end vs fp8 oracle:", f"{max_norm_err(to_np(layer.y), fwd['y']):.2e}",
           " vs unquantised oracle:", f"{max_norm_err(to_np(layer.y), plain['y']):.2e}")
+
+
+# ---- FP8 backward GEMMs -------------------------------------------------------------------------------------
+def _check_tgroup(codes_t, e8m0, pad_offsets, src, offsets):
+    """HIP transposed / padded codes and E8M0 bytes against the oracle's token-group quantiser, bit for bit."""
+    c_ref, k_ref = O.quant_tokengroup_pow2(src, offsets)
+    E = len(offsets) - 1
+    po = [0]
+    for e in range(E):
+        po.append(po[-1] + (int(offsets[e + 1] - offsets[e]) + 127) // 128 * 128)
+    assert list(pad_offsets) == po
+    gi = 0
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        n = hi - lo
+        blk = codes_t[:, po[e]:po[e + 1]]
+        assert np.array_equal(blk[:, :n].T, c_ref[lo:hi]), e
+        assert not blk[:, n:].any(), e                      # zero codes in the padding
+        ng = (n + 127) // 128
+        assert np.array_equal(e8m0[po[e] // 128: po[e] // 128 + ng].astype(np.int64) - 127, k_ref[gi:gi + ng]), e
+        gi += ng
+    return c_ref, k_ref
+
+
+@pytest.mark.parametrize("rows,cols,counts,src_dtype", [
+    (0, 64, [0, 0], "bf16"), (300, 80, [130, 0, 170], "bf16"), (1000, 272, [1, 255, 256, 257, 231], "bf16"),
+    (384, 64, [128, 256], "f32")])
+def test_quant_fp8_tgroup_bit_exact(B, rows, cols, counts, src_dtype):
+    rng = np.random.default_rng(rows + cols)
+    v = (rng.standard_normal((rows, cols)) * np.exp2(rng.integers(-12, 12, (rows, cols)))).astype(np.float32)
+    if rows:
+        v[:, 3] = 0.0
+        v[rows // 2, 5] = 448.0 * 2.0 ** 3
+        v[rows // 2, 6] = 448.0 * 2.0 ** 3 * (1 + 2.0 ** -7)
+    if src_dtype == "bf16":
+        v = bf16_round(v)
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    E = len(counts)
+    ldt = B.moe_tgroup_tokens(rows, E)
+    codes_t = torch.full((cols, ldt), 0x55, dtype=torch.uint8, device=DEV)
+    e8 = torch.full((ldt // 128, cols), 0xEE, dtype=torch.uint8, device=DEV)
+    po = torch.full((E + 1,), -5, dtype=torch.int32, device=DEV)
+    src = to_dev(v, torch_dtype(src_dtype)) if rows else torch.empty((0, cols), dtype=torch_dtype(src_dtype), device=DEV)
+    B.moe_quant_fp8_tgroup(src, to_dev(offsets), po, codes_t, e8)
+    torch.cuda.synchronize()
+    ct, pz = to_np(codes_t), to_np(po)
+    _check_tgroup(ct, to_np(e8), pz, v, offsets)
+    assert np.all(ct[:, pz[-1]:] == 0x55)                   # columns past the padded total are not touched
+
+
+@pytest.mark.parametrize("cfg", FP8_CASES, ids=lambda c: c.name)
+def test_layer_fp8_backward_gemms(B, cfg):
+    """The four backward GEMMs on e4m3 operands, stage by stage as in the forward test: every cast is compared bit for
+    bit with the oracle's quantiser applied to the kernel's own pre-cast tensor, every GEMM with the oracle fed the
+    kernel's codes."""
+    from paper_2505_11432_amd.layer import MoELayer
+    inp = make_inputs(cfg, seed=3)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    if cfg.name == "fp8_ragged":
+        z[:, 4] = -1e4
+    td = torch.bfloat16
+    T, k, d, f, E = cfg.T, cfg.k, cfg.d, cfg.f, cfg.E
+    layer = MoELayer(T, d, E, k, f, dtype=td, fp8=True)
+    x, dy = to_dev(inp["x"], td), to_dev(inp["dy"], td)
+    wr = to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"], td), to_dev(inp["W2"], td)
+    layer.set_fp8_weights(w1, w2)
+    layer.set_fp8_backward_weights(w1, w2)
+    layer.forward_fp8(x, wr, None, logits=to_dev(z))
+    layer.backward_fp8_gemm(x, wr, dy, with_router=False)
+    torch.cuda.synchronize()
+    offsets = to_np(layer.offsets).astype(np.int64)
+    counts = np.diff(offsets)
+    tol = TOL["fp8"]
+    errs = {}
+    I = {n: to_np(t) for n, t in layer.bwd8.items()}
+    # (1) transposed-orientation weight casts: bit-exact
+    W1t = np.ascontiguousarray(np.transpose(inp["W1"], (0, 2, 1))).reshape(-1, 2 * f)
+    W2t = np.ascontiguousarray(np.transpose(inp["W2"], (0, 2, 1))).reshape(-1, d)
+    c1, s1 = O.quant_rows(W1t)
+    c2, s2 = O.quant_rows(W2t)
+    assert np.array_equal(to_np(layer.w1t_codes).reshape(-1, 2 * f), c1) and np.array_equal(to_np(layer.w2t_codes).reshape(-1, d), c2)
+    assert np.array_equal(to_np(layer.w1t_scale).reshape(-1).astype(np.float32), s1)
+    assert np.array_equal(to_np(layer.w2t_scale).reshape(-1).astype(np.float32), s2)
+    W1th = O.dequant_rows(c1, s1).reshape(E, d, 2 * f)
+    W2th = O.dequant_rows(c2, s2).reshape(E, f, d)
+    # (2) per-token cast of the kernel's own dY: bit-exact
+    dyp = to_np(layer.d_yp)
+    cdy, sdy = O.quant_rows(dyp.astype(np.float32))
+    assert np.array_equal(I["dy_codes"], cdy) and np.array_equal(I["dy_scale"].astype(np.float32), sdy)
+    # (3) dgrad2 + SwiGLU' on those codes
+    H = to_np(layer.h_save)
+    dYr = O.dequant_rows(cdy, sdy)
+    dA = np.zeros((layer.M, f))
+    for e in range(E):
+        lo, hi = offsets[e], offsets[e + 1]
+        dA[lo:hi] = dYr[lo:hi] @ W2th[e].T
+    dG, dU = O.swiglu_bwd(H[:, :f], H[:, f:], dA)
+    errs["dH"] = max_norm_err(I["dh"], np.concatenate([dG, dU], axis=1))
+    # (4) per-token cast of the kernel's own dH: bit-exact; dgrad1 on those codes
+    cdh, sdh = O.quant_rows(I["dh"].astype(np.float32))
+    assert np.array_equal(I["dh_codes"], cdh) and np.array_equal(I["dh_scale"].astype(np.float32), sdh)
+    dHr = O.dequant_rows(cdh, sdh)
+    dxp = np.zeros((layer.M, d))
+    for e in range(E):
+        lo, hi = offsets[e], offsets[e + 1]
+        dxp[lo:hi] = dHr[lo:hi] @ W1th[e].T
+    errs["dxp"] = max_norm_err(to_np(layer.d_xp), dxp)
+    # (5) token-group casts of the four wgrad operands: bit-exact, padded and transposed as documented
+    deq = {}
+    for name, src in (("dy", dyp), ("dh", I["dh"]), ("a", to_np(layer.a_deq)), ("x", to_np(layer.xp_deq))):
+        c_ref, k_ref = _check_tgroup(I[name + "_t"], I[name + "_e8m0"], I["pad_offsets"], src.astype(np.float32), offsets)
+        deq[name] = O.dequant_tokengroup_pow2(c_ref, k_ref, offsets)
+    # (6) the weight gradients on those codes
+    dW1, dW2 = to_np(layer.d_w1), to_np(layer.d_w2)
+    for e in range(E):
+        lo, hi = offsets[e], offsets[e + 1]
+        if counts[e] == 0:
+            assert np.all(dW1[e] == 0) and np.all(dW2[e] == 0)
+        else:
+            errs[f"dW2[{e}]"] = max_norm_err(dW2[e], deq["dy"][lo:hi].T @ deq["a"][lo:hi])
+            errs[f"dW1[{e}]"] = max_norm_err(dW1[e], deq["dh"][lo:hi].T @ deq["x"][lo:hi])
+    # (7) the rest of the backward on the kernel's d_xp
+    fwd = O.layer_fwd_fp8(inp["x"], z, inp["W1"], inp["W2"], k)
+    errs["dx"] = max_norm_err(to_np(layer.dx), O.combine(to_np(layer.d_xp), fwd["inv_perm"], None, T, k))
+    print(cfg.name, {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < tol}
+    assert not bad, bad
+    # information only: distance to the straight-through bf16 backward of the same forward
+    dx8 = to_np(layer.dx)
+    layer.backward_fp8(x, wr, w1, w2, dy, with_router=False)
+    torch.cuda.synchronize()
+    print("   vs bf16 backward GEMMs: dx", f"{max_norm_err(dx8, to_np(layer.dx)):.2e}",
+          "dW1", f"{max_norm_err(dW1, to_np(layer.d_w1)):.2e}", "dW2", f"{max_norm_err(dW2, to_np(layer.d_w2)):.2e}")
