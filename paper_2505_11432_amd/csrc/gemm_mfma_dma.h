@@ -132,6 +132,31 @@ __device__ __forceinline__ void stage_load_bf16(char* stg, bf16x4 (&v)[4], const
   for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2);
 }
 
+// The same load in two phases, so that the global reads of the next 32x32 block can be in flight while the
+// current block is processed: fetch (global -> registers, zero where masked) and unpack (registers -> LDS patch ->
+// accumulator lane layout).
+struct StageFetch { uint4 v[2]; };
+__device__ __forceinline__ StageFetch stage_fetch_bf16(const bf16* g, long ld, int rows_valid, int cols_valid, int lane) {
+  StageFetch f;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    f.v[pass] = make_uint4(0, 0, 0, 0);
+    if (r < rows_valid && c < cols_valid) f.v[pass] = *reinterpret_cast<const uint4*>(g + (long)r * ld + c);
+  }
+  return f;
+}
+__device__ __forceinline__ void stage_unpack_bf16(char* stg, const StageFetch& f, bf16x4 (&v)[4], int lane) {
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    *reinterpret_cast<uint4*>(stg + r * STG_STRIDE + c * 2) = f.v[pass];
+  }
+  const int row = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2);
+}
+
 // 32 rows x 32 fp32 columns, as two halves of 16 columns; optional read-modify-write accumulation.
 __device__ __forceinline__ void stage_store_f32(char* stg, const f32x16& acc, float* g, long ld, int rows_valid,
                                                 int cols_valid, bool accumulate, int lane) {
@@ -587,35 +612,73 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         }
       } else {
         // acc = dA; read G|U, write dG|dU and the recomputed SwiGLU output
+        auto swiglu_bwd_block = [&](const f32x16& dacc, const bf16x4 (&g)[4], const bf16x4 (&u)[4], int mb, int nb,
+                                    int rows_valid, int cols_valid) __attribute__((always_inline)) {
+          bf16x4 dg[4], du[4], a[4];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int mb = m0 + wm * WTM + i * 32;
-          const int rows_valid = m_end - mb;
-          if (rows_valid <= 0) continue;
+          for (int q = 0; q < 4; ++q)
 #pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int nb = n0 + wn * WTN + j * 32;
-            const int cols_valid = p.N - nb;
-            if (cols_valid <= 0) continue;
-            bf16x4 g[4], u[4], dg[4], du[4], a[4];
+            for (int t = 0; t < 4; ++t) {
+              const float gf = static_cast<float>(g[q][t]), uf = static_cast<float>(u[q][t]);
+              const float d = static_cast<float>(static_cast<bf16>(dacc[4 * q + t]));
+              const float sg = sigmoid_f32(gf);
+              dg[q][t] = static_cast<bf16>(d * uf * sg * (1.0f + gf * (1.0f - sg)));
+              du[q][t] = static_cast<bf16>(d * gf * sg);
+              a[q][t] = static_cast<bf16>(gf * sg * uf);
+            }
+          bf16* drow = p.dH + (long)mb * 2 * p.N + nb;
+          stage_store_bf16(stg, dg, drow, 2L * p.N, rows_valid, cols_valid, lane);
+          stage_store_bf16(stg, du, drow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
+          if (p.A_out) stage_store_bf16(stg, a, p.A_out + (long)mb * p.N + nb, p.N, rows_valid, cols_valid, lane);
+        };
+        if constexpr (FP8) {
+          // (the e4m3 instantiation has no registers to spare for reading ahead)
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            const int mb = m0 + wm * WTM + i * 32;
+            const int rows_valid = m_end - mb;
+            if (rows_valid <= 0) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+              const int nb = n0 + wn * WTN + j * 32;
+              const int cols_valid = p.N - nb;
+              if (cols_valid <= 0) continue;
+              bf16x4 g[4], u[4];
+              const bf16* hrow = p.H + (long)mb * 2 * p.N + nb;
+              stage_load_bf16(stg, g, hrow, 2L * p.N, rows_valid, cols_valid, lane);
+              stage_load_bf16(stg, u, hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
+              swiglu_bwd_block(acc[i][j], g, u, mb, nb, rows_valid, cols_valid);
+            }
+          }
+        } else {
+          // the G and U reads of block b+1 are issued before block b is processed
+          constexpr int NB = TM * TN;
+          auto block_geom = [&](int b, int& mb, int& nb, int& rows_valid, int& cols_valid) __attribute__((always_inline)) {
+            const int i = b / TN, j = b % TN;
+            mb = m0 + wm * WTM + i * 32;
+            nb = n0 + wn * WTN + j * 32;
+            rows_valid = m_end - mb;
+            cols_valid = p.N - nb;
+          };
+          auto fetch_block = [&](int b, StageFetch& fg, StageFetch& fu) __attribute__((always_inline)) {
+            int mb, nb, rows_valid, cols_valid;
+            block_geom(b, mb, nb, rows_valid, cols_valid);
             const bf16* hrow = p.H + (long)mb * 2 * p.N + nb;
-            stage_load_bf16(stg, g, hrow, 2L * p.N, rows_valid, cols_valid, lane);
-            stage_load_bf16(stg, u, hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
+            fg = stage_fetch_bf16(hrow, 2L * p.N, rows_valid, cols_valid, lane);
+            fu = stage_fetch_bf16(hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
+          };
+          StageFetch fg[2], fu[2];
+          fetch_block(0, fg[0], fu[0]);
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-              for (int t = 0; t < 4; ++t) {
-                const float gf = static_cast<float>(g[q][t]), uf = static_cast<float>(u[q][t]);
-                const float d = static_cast<float>(static_cast<bf16>(acc[i][j][4 * q + t]));
-                const float sg = sigmoid_f32(gf);
-                dg[q][t] = static_cast<bf16>(d * uf * sg * (1.0f + gf * (1.0f - sg)));
-                du[q][t] = static_cast<bf16>(d * gf * sg);
-                a[q][t] = static_cast<bf16>(gf * sg * uf);
-              }
-            bf16* drow = p.dH + (long)mb * 2 * p.N + nb;
-            stage_store_bf16(stg, dg, drow, 2L * p.N, rows_valid, cols_valid, lane);
-            stage_store_bf16(stg, du, drow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
-            if (p.A_out) stage_store_bf16(stg, a, p.A_out + (long)mb * p.N + nb, p.N, rows_valid, cols_valid, lane);
+          for (int b = 0; b < NB; ++b) {
+            if (b + 1 < NB) fetch_block(b + 1, fg[(b + 1) & 1], fu[(b + 1) & 1]);
+            int mb, nb, rows_valid, cols_valid;
+            block_geom(b, mb, nb, rows_valid, cols_valid);
+            if (rows_valid <= 0 || cols_valid <= 0) continue;
+            bf16x4 g[4], u[4];
+            stage_unpack_bf16(stg, fg[b & 1], g, lane);
+            stage_unpack_bf16(stg, fu[b & 1], u, lane);
+            swiglu_bwd_block(acc[b / TN][b % TN], g, u, mb, nb, rows_valid, cols_valid);
           }
         }
       }

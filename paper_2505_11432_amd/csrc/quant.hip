@@ -22,27 +22,30 @@ __device__ __forceinline__ unsigned pack4_e4m3(float a, float b, float c, float 
   return (unsigned)w;
 }
 
-__device__ __forceinline__ float block_max_256(float v, float* red) {
+template <int THREADS>
+__device__ __forceinline__ float block_max(float v, float* red) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
   if (threadIdx.x % 64 == 0) red[threadIdx.x / 64] = v;
   __syncthreads();
-  v = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  v = red[0];
+#pragma unroll
+  for (int w = 1; w < THREADS / 64; ++w) v = fmaxf(v, red[w]);
   __syncthreads();
   return v;
 }
 
-// One 256-thread block per row.  Rows of up to 256 x 8 vectors (16384 bf16 / 8192 fp32 columns) stay in
-// registers between the amax pass and the convert pass, so HBM sees each element once; longer rows are
-// read a second time (from L2).
-template <typename T>
-__global__ void __launch_bounds__(256) quant_rows_kernel(const T* __restrict__ src, int rows, int cols,
-                                                         uint8_t* __restrict__ codes, float* __restrict__ scales) {
-  __shared__ float red[4];
+// One block per row.  A row of up to THREADS x 8 vectors stays in registers between the amax pass and the
+// convert pass, so HBM sees each element once (256 threads: 16384 bf16 columns; 1024 threads, used for wider
+// rows: 65536); longer rows are read a second time (from L2).
+template <typename T, int THREADS>
+__global__ void __launch_bounds__(THREADS) quant_rows_kernel(const T* __restrict__ src, int rows, int cols,
+                                                             uint8_t* __restrict__ codes, float* __restrict__ scales) {
+  __shared__ float red[THREADS / 64];
   constexpr int V = 16 / sizeof(T);
   constexpr int kHold = 8;                       // vectors held per thread
   const int nvec = cols / V;
-  const bool in_regs = nvec <= 256 * kHold;
+  const bool in_regs = nvec <= THREADS * kHold;
   for (int r = blockIdx.x; r < rows; r += gridDim.x) {
     const T* row = src + (long)r * cols;
     Vec16<T> hold[kHold];
@@ -50,7 +53,7 @@ __global__ void __launch_bounds__(256) quant_rows_kernel(const T* __restrict__ s
     if (in_regs) {
 #pragma unroll
       for (int h = 0; h < kHold; ++h) {
-        const int c = threadIdx.x + h * 256;
+        const int c = threadIdx.x + h * THREADS;
         if (c < nvec) {
           hold[h] = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
 #pragma unroll
@@ -58,13 +61,13 @@ __global__ void __launch_bounds__(256) quant_rows_kernel(const T* __restrict__ s
         }
       }
     } else {
-      for (int c = threadIdx.x; c < nvec; c += 256) {
+      for (int c = threadIdx.x; c < nvec; c += THREADS) {
         const Vec16<T> v = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
 #pragma unroll
         for (int i = 0; i < V; ++i) amax = fmaxf(amax, fabsf(to_f32(v.v[i])));
       }
     }
-    amax = block_max_256(amax, red);
+    amax = block_max<THREADS>(amax, red);
     const float inv = amax > 0.f ? kE4M3Max / amax : 1.0f;
     if (threadIdx.x == 0) scales[r] = amax > 0.f ? amax / kE4M3Max : 1.0f;
     auto convert = [&](const Vec16<T>& v, int c) {
@@ -80,11 +83,11 @@ __global__ void __launch_bounds__(256) quant_rows_kernel(const T* __restrict__ s
     if (in_regs) {
 #pragma unroll
       for (int h = 0; h < kHold; ++h) {
-        const int c = threadIdx.x + h * 256;
+        const int c = threadIdx.x + h * THREADS;
         if (c < nvec) convert(hold[h], c);
       }
     } else {
-      for (int c = threadIdx.x; c < nvec; c += 256) convert(*reinterpret_cast<const Vec16<T>*>(row + (long)c * V), c);
+      for (int c = threadIdx.x; c < nvec; c += THREADS) convert(*reinterpret_cast<const Vec16<T>*>(row + (long)c * V), c);
     }
   }
 }
@@ -268,8 +271,14 @@ int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_
   if (rows == 0 || cols == 0) return MOE_OK;
   if (mode == MOE_Q_ROW) {
     const int grid = rows < 256 * 16 ? rows : 256 * 16;
-    if (src_dt == MOE_F32) quant_rows_kernel<float><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales);
-    else quant_rows_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
+    const bool wide = cols / (16 / (int)dtype_size(src_dt)) > 256 * 8;     // more vectors than 256 threads can hold
+    if (src_dt == MOE_F32) {
+      if (wide) quant_rows_kernel<float, 1024><<<grid, 1024, 0, s>>>((const float*)src, rows, cols, codes, scales);
+      else quant_rows_kernel<float, 256><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales);
+    } else {
+      if (wide) quant_rows_kernel<bf16, 1024><<<grid, 1024, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
+      else quant_rows_kernel<bf16, 256><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
+    }
   } else {
     const int slabs = cdiv(cols, 64);
     const int grid = cdiv(rows, 128) * slabs;
