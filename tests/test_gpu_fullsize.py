@@ -132,3 +132,112 @@ def test_full_size_is_deterministic():
     b = run_full(cfg, inp)
     assert torch.equal(ya, b.y) and torch.equal(dxa, b.dx)
     assert torch.equal(g1a, b.d_w1) and torch.equal(g2a, b.d_w2)
+
+
+def test_full_size_fp8_forward_and_fp8_backward_sampled():
+    """mixtral_fp8 with all six expert GEMMs on e4m3 operands, at full size.  Stage by stage on samples: casts bit for
+    bit against the oracle's quantisers applied to the kernel's own pre-cast rows / column slices, GEMM outputs against
+    the oracle's arithmetic on the kernel's codes (sampled rows x sampled columns; weight gradients on slices, summed
+    over all rows of the expert)."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = CONFIGS["mixtral_fp8"]
+    inp = make_inputs(cfg, seed=0)
+    T, k, d, f, E = cfg.T, cfg.k, cfg.d, cfg.f, cfg.E
+    layer = MoELayer(T, d, E, k, f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=True)
+    x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
+    w_r = dev_bf16(np.ascontiguousarray(inp["W_r"].T))
+    w1, w2 = dev_bf16(inp["W1"]), dev_bf16(inp["W2"])
+    layer.set_fp8_weights(w1, w2)
+    layer.set_fp8_backward_weights(w1, w2)
+    layer.forward_fp8(x, w_r, None)
+    layer.backward_fp8_gemm(x, w_r, dy)
+    torch.cuda.synchronize()
+    tol = 6e-2
+    offsets = to_np(layer.offsets).astype(np.int64)
+    rng = np.random.default_rng(11)
+    rows = np.sort(rng.choice(layer.M, size=96, replace=False))
+    row_e = np.searchsorted(offsets, rows, side="right") - 1
+    cf = np.sort(rng.choice(f, size=48, replace=False))          # columns of the expert width
+    cd = np.sort(rng.choice(d, size=48, replace=False))          # columns of the model width
+    I = layer.bwd8
+    g = lambda t, r=None, c=None: to_np(t if r is None else t[torch.as_tensor(r, device=DEV)] if c is None
+                                        else t[torch.as_tensor(r, device=DEV)][:, torch.as_tensor(c, device=DEV)])
+    errs = {}
+
+    def wslice(codes, scales, e, rsel):      # dequantised rows rsel of expert e of a [E, R, C] code tensor
+        c = g(codes[e], rsel)
+        s = g(scales[e], rsel).astype(np.float32)
+        return O.dequant_rows(c, s)
+
+    # weight casts (both orientations) on sampled rows: bit-exact
+    for e in (0, E - 1):
+        for codes, scales, W in ((layer.w1_codes, layer.w1_scale, inp["W1"][e]), (layer.w2_codes, layer.w2_scale, inp["W2"][e]),
+                                 (layer.w1t_codes, layer.w1t_scale, inp["W1"][e].T), (layer.w2t_codes, layer.w2t_scale, inp["W2"][e].T)):
+            rs = np.sort(rng.choice(W.shape[0], size=8, replace=False))
+            c_ref, s_ref = O.quant_rows(np.ascontiguousarray(W[rs]))
+            assert np.array_equal(g(codes[e], rs), c_ref) and np.array_equal(g(scales[e], rs).astype(np.float32), s_ref)
+    # forward: FC1 on the kernel's xp codes, FC2 on the kernel's A codes
+    xp_hat = O.dequant_rows(g(layer.xp, rows), g(layer.xp_scale, rows).astype(np.float32))
+    a_hat = O.dequant_rows(g(layer.a_codes, rows), g(layer.a_scale, rows).astype(np.float32))
+    H_s = np.zeros((len(rows), 2 * len(cf)))
+    Y_s = np.zeros((len(rows), len(cd)))
+    hcols = np.concatenate([cf, f + cf])
+    for e in np.unique(row_e):
+        m = row_e == e
+        H_s[m] = xp_hat[m] @ wslice(layer.w1_codes, layer.w1_scale, e, hcols).T
+        Y_s[m] = a_hat[m] @ wslice(layer.w2_codes, layer.w2_scale, e, cd).T
+    H_gpu = g(layer.h_save, rows, hcols)
+    errs["H"] = max_norm_err(H_gpu, H_s)
+    cy, sy = g(layer.yp, rows), g(layer.yp_scale, rows).astype(np.float32)
+    errs["Y"] = max_norm_err(O.dequant_rows(cy, sy)[:, cd], Y_s)          # includes the per-token cast of Y (<= 2^-4 relative)
+    # backward, per-token operands
+    dyp = g(layer.d_yp, rows).astype(np.float32)
+    c_ref, s_ref = O.quant_rows(dyp)
+    assert np.array_equal(g(I["dy_codes"], rows), c_ref) and np.array_equal(g(I["dy_scale"], rows).astype(np.float32), s_ref)
+    dY_hat = O.dequant_rows(c_ref, s_ref)
+    dA = np.zeros((len(rows), len(cf)))
+    for e in np.unique(row_e):
+        m = row_e == e
+        dA[m] = dY_hat[m] @ wslice(layer.w2t_codes, layer.w2t_scale, e, cf).T
+    dG, dU = O.swiglu_bwd(H_gpu[:, :len(cf)], H_gpu[:, len(cf):], dA)
+    errs["dH"] = max_norm_err(g(I["dh"], rows, hcols), np.concatenate([dG, dU], axis=1))
+    dh_rows = g(I["dh"], rows).astype(np.float32)
+    c_ref, s_ref = O.quant_rows(dh_rows)
+    assert np.array_equal(g(I["dh_codes"], rows), c_ref) and np.array_equal(g(I["dh_scale"], rows).astype(np.float32), s_ref)
+    dH_hat = O.dequant_rows(c_ref, s_ref)
+    dxp = np.zeros((len(rows), len(cd)))
+    for e in np.unique(row_e):
+        m = row_e == e
+        dxp[m] = dH_hat[m] @ wslice(layer.w1t_codes, layer.w1t_scale, e, cd).T
+    errs["dxp"] = max_norm_err(g(layer.d_xp, rows, cd), dxp)
+    # token-group casts on column slices (columns are independent), then the weight gradients of those slices
+    po = to_np(I["pad_offsets"]).astype(np.int64)
+    assert np.array_equal(po, np.concatenate([[0], np.cumsum((np.diff(offsets) + 127) // 128 * 128)]))
+    allr = np.arange(layer.M)
+
+    def tg_slice(src_t, name, cols):
+        src = g(src_t, allr, cols).astype(np.float32)
+        c_ref, k_ref = O.quant_tokengroup_pow2(src, offsets)
+        ct = g(I[name + "_t"], cols)                                   # [len(cols), ldt]
+        e8 = to_np(I[name + "_e8m0"][:, torch.as_tensor(cols, device=DEV)]).astype(np.int64)
+        gi = 0
+        for e in range(E):
+            n = offsets[e + 1] - offsets[e]
+            assert np.array_equal(ct[:, po[e]:po[e] + n].T, c_ref[offsets[e]:offsets[e + 1]]), (name, e)
+            assert not ct[:, po[e] + n:po[e + 1]].any()
+            ng = (n + 127) // 128
+            assert np.array_equal(e8[po[e] // 128:po[e] // 128 + ng] - 127, k_ref[gi:gi + ng]), (name, e)
+            gi += ng
+        return O.dequant_tokengroup_pow2(c_ref, k_ref, offsets)
+
+    dy_g = tg_slice(layer.d_yp, "dy", cd)
+    a_g = tg_slice(layer.a_deq, "a", cf)
+    dh_g = tg_slice(I["dh"], "dh", hcols)
+    x_g = tg_slice(layer.xp_deq, "x", cd)
+    for e in (0, 3, E - 1):
+        lo, hi = offsets[e], offsets[e + 1]
+        errs[f"dW2[{e}]"] = max_norm_err(g(layer.d_w2[e], cd, cf), dy_g[lo:hi].T @ a_g[lo:hi])
+        errs[f"dW1[{e}]"] = max_norm_err(g(layer.d_w1[e], hcols, cd), dh_g[lo:hi].T @ x_g[lo:hi])
+    print("mixtral_fp8 full size:", {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < tol}
+    assert not bad, bad
