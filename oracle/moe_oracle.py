@@ -101,6 +101,49 @@ def route(logits: np.ndarray, k: int, renorm: int = 1) -> dict:
     return dict(idx=idx, w=w, counts=counts, offsets=offsets, perm=perm, inv_perm=inv_perm)
 
 
+def route_range(logits: np.ndarray, k: int, e_lo: int, e_hi: int, renorm: int = 1) -> dict:
+    """One GPU's expert-parallel share (Section 3.2: after the all-gather a local scatter keeps only the
+    tokens routed to local experts).  The gate runs over all E experts as in route(); only assignments
+    whose expert lies in [e_lo, e_hi) get a row.  counts [E] stays global; offsets [e_hi-e_lo+1] and
+    perm [M_local] cover the local experts (same order: by expert, then ascending assignment id);
+    inv_perm [T*k] is -1 for assignments that were dropped."""
+    idx = topk_select(logits, k)
+    w = gate_weights(logits, idx, renorm)
+    E = logits.shape[1]
+    e_of_a = idx.reshape(-1).astype(np.int64)
+    counts = np.array([np.count_nonzero(e_of_a == e) for e in range(E)], dtype=np.int32)
+    offsets = np.zeros(e_hi - e_lo + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(counts[e_lo:e_hi])
+    perm = np.concatenate([np.flatnonzero(e_of_a == e) for e in range(e_lo, e_hi)] + [np.zeros(0, np.int64)])
+    inv_perm = np.full(e_of_a.size, -1, dtype=np.int64)
+    inv_perm[perm] = np.arange(perm.size)
+    return dict(idx=idx, w=w, counts=counts, offsets=offsets.astype(np.int32), perm=perm.astype(np.int32),
+                inv_perm=inv_perm.astype(np.int32))
+
+
+def layer_fwd_range(x, logits, W1_local, W2_local, k: int, e_lo: int, e_hi: int, renorm: int = 1) -> dict:
+    """Forward of one expert-parallel share: W1_local / W2_local hold experts e_lo..e_hi-1; y is the partial
+    sum over the local experts (what a reduce-scatter would add up across the ranks)."""
+    T = x.shape[0]
+    r = route_range(logits, k, e_lo, e_hi, renorm)
+    xp = dispatch(x, r["perm"], k)
+    H, A, Y = expert_ffn_fwd(xp, r["offsets"], W1_local, W2_local)
+    y = combine(Y, r["inv_perm"], r["w"], T, k)
+    r.update(xp=xp, H=H, A=A, Y=Y, y=y)
+    return r
+
+
+def layer_bwd_range(x, logits, W1_local, W2_local, k: int, dy, fwd: dict) -> dict:
+    """Backward of layer_fwd_range: gradients of the local experts, the local part of dx and of the gate-weight
+    gradient (zero for dropped assignments); the gate's own backward needs the sum of dw over all shares."""
+    T = x.shape[0]
+    dYp = dispatch(dy, fwd["perm"], k, row_mul=fwd["w"])
+    dw = gate_grad(dy, fwd["Y"], fwd["inv_perm"], T, k)
+    dxp, dW1, dW2, dH = expert_ffn_bwd(fwd["xp"], fwd["H"], dYp, fwd["offsets"], W1_local, W2_local)
+    dx = combine(dxp, fwd["inv_perm"], None, T, k)
+    return dict(dYp=dYp, dw=dw, dxp=dxp, dW1=dW1, dW2=dW2, dH=dH, dx=dx)
+
+
 def route_bwd(logits, idx, w, dw, renorm: int = 1) -> np.ndarray:
     """d(loss)/d(logits) float64 [T, E] given d(loss)/d(w); the selection is constant."""
     T, E = np.asarray(logits).shape
@@ -156,12 +199,15 @@ def dispatch(x, perm, k: int, row_mul=None) -> np.ndarray:
 
 
 def combine(Y, inv_perm, w, T: int, k: int) -> np.ndarray:
-    """y[t,:] = sum_j w[t,j] * Y[inv_perm[t*k+j], :], slots in ascending j.  w=None: unweighted."""
+    """y[t,:] = sum_j w[t,j] * Y[inv_perm[t*k+j], :], slots in ascending j.  w=None: unweighted.
+    An assignment without a row (inv_perm < 0: its expert is not local, see route_range) adds nothing."""
     Y = np.asarray(Y, F64)
     rows = inv_perm.astype(np.int64).reshape(T, k)
     y = np.zeros((T, Y.shape[1]), dtype=F64)
     for j in range(k):
-        term = Y[rows[:, j], :]
+        has = rows[:, j] >= 0
+        term = np.zeros_like(y)
+        term[has] = Y[rows[has, j], :]
         if w is not None:
             term = term * np.asarray(w, F64)[:, j][:, None]
         y += term
@@ -173,9 +219,10 @@ def gate_grad(dy, Y, inv_perm, T: int, k: int) -> np.ndarray:
     dy = np.asarray(dy, F64)
     Y = np.asarray(Y, F64)
     rows = inv_perm.astype(np.int64).reshape(T, k)
-    dw = np.empty((T, k), dtype=F64)
+    dw = np.zeros((T, k), dtype=F64)
     for j in range(k):
-        dw[:, j] = np.einsum("td,td->t", dy, Y[rows[:, j], :])
+        has = rows[:, j] >= 0                      # assignments without a local row get no gradient here
+        dw[has, j] = np.einsum("td,td->t", dy[has], Y[rows[has, j], :])
     return dw
 
 

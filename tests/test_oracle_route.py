@@ -5,7 +5,7 @@ import pytest
 from scipy.special import softmax as scipy_softmax
 
 from oracle import moe_oracle as O
-from synth.moe_inputs import random_logits
+from synth.moe_inputs import MoEConfig, make_inputs, random_logits
 
 
 def brute_topk(z_row, k):
@@ -199,3 +199,42 @@ def test_router_matmul_and_bwd():
     xp = rng.standard_normal((5, 4))
     assert np.isclose((dz * (x @ Wp)).sum(), (dW * Wp).sum())
     assert np.isclose((dz * (xp @ W)).sum(), (dx * xp).sum())
+
+
+# ---- expert-parallel share (Section 3.2: local scatter after the all-gather) -------------------------------
+def test_route_range_is_the_filtered_full_route():
+    z = random_logits(257, 12, seed=5, quantum=0.5)
+    full = O.route(z, 3)
+    for lo, hi in ((0, 12), (0, 4), (4, 9), (9, 12), (5, 5)):
+        r = O.route_range(z, 3, lo, hi)
+        assert np.array_equal(r["idx"], full["idx"]) and np.array_equal(r["w"], full["w"])
+        assert np.array_equal(r["counts"], full["counts"])
+        keep = full["perm"][full["offsets"][lo]:full["offsets"][hi]]          # the full map's rows of the local experts
+        assert np.array_equal(r["perm"], keep)
+        assert np.array_equal(r["offsets"], full["offsets"][lo:hi + 1] - full["offsets"][lo])
+        e_of_a = full["idx"].reshape(-1)
+        local = (e_of_a >= lo) & (e_of_a < hi)
+        assert np.all(r["inv_perm"][~local] == -1)
+        assert np.array_equal(r["inv_perm"][local], full["inv_perm"][local] - full["offsets"][lo])
+
+
+def test_expert_parallel_shares_add_up_to_the_full_layer():
+    """Partition invariance: partial outputs and partial input gradients of disjoint expert ranges sum to the
+    full layer's; expert gradients and gate-weight gradients are those of the full layer, range by range."""
+    cfg = MoEConfig("t", T=96, d=24, E=6, k=3, f=16, dtype="f32", w_std=0.3, wr_std=0.8)
+    inp = make_inputs(cfg, seed=4)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    full = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k)
+    gfull = O.layer_bwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k, inp["dy"], full)
+    y = np.zeros_like(full["y"]); dx = np.zeros_like(gfull["dx"]); dw = np.zeros_like(gfull["dw"])
+    for lo, hi in ((0, 2), (2, 3), (3, 6)):
+        f = O.layer_fwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, lo, hi)
+        g = O.layer_bwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, inp["dy"], f)
+        y += f["y"]; dx += g["dx"]; dw += g["dw"]
+        assert np.allclose(g["dW1"], gfull["dW1"][lo:hi], rtol=1e-12, atol=1e-12)
+        assert np.allclose(g["dW2"], gfull["dW2"][lo:hi], rtol=1e-12, atol=1e-12)
+        e_of = full["idx"]
+        assert np.all(g["dw"][(e_of < lo) | (e_of >= hi)] == 0)
+    assert np.allclose(y, full["y"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(dx, gfull["dx"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(dw, gfull["dw"], rtol=1e-12, atol=1e-12)
