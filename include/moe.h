@@ -89,6 +89,21 @@ int moe_route(const float* logits /*[T,E]*/, int T, int E, int k, int renorm,
               int32_t* perm /*[T*k]*/, int32_t* inv_perm /*[T*k]*/,
               void* workspace, size_t ws_bytes, void* stream);
 
+/* The same for one GPU's expert-parallel share (Section 3.2: after the all-gather of the tokens a
+ * local scatter keeps only those routed to local experts; Section 3.1: each rank holds E/n
+ * experts).  The gate runs over all E experts; only assignments whose expert lies in
+ * [e_lo, e_hi) get a row.  counts [E] stays global.  offsets has e_hi - e_lo + 1 entries and
+ * covers the local experts (offsets[e_hi - e_lo] = number of local rows); perm [T*k] is written
+ * for the local rows only; inv_perm [T*k] = -1 for an assignment without a row.  moe_dispatch,
+ * moe_combine and moe_gate_grad skip such assignments: the combine then yields the partial sum
+ * over the local experts (what a reduce-scatter adds up across ranks), the gate gradient is 0
+ * there.  The expert FFN calls take the local weights, E = e_hi - e_lo and M = T*k as the row
+ * bound (they touch no row at or past offsets[E]).  e_lo = 0, e_hi = E is moe_route. */
+int moe_route_range(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi,
+                    int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets,
+                    int32_t* perm, int32_t* inv_perm, void* workspace, size_t ws_bytes,
+                    void* stream);
+
 /* Derivative of the gate weights w.r.t. the logits with the selection held constant.
  * d_logits [T,E] is fully written (zeros at unselected experts when renorm=1).
  * `logits` is only read when renorm=0 and may be NULL otherwise. */

@@ -24,7 +24,7 @@ EXPORTS = (
     "moe_abi_version", "moe_last_hip_error", "moe_status_string", "moe_workspace_bytes",
     "moe_router_fwd", "moe_router_bwd", "moe_route", "moe_route_bwd", "moe_dispatch", "moe_combine",
     "moe_gate_grad", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_quant_fp8", "moe_dequant_fp8",
-    "moe_expert_ffn_bwd_fp8", "moe_tgroup_tokens", "moe_quant_fp8_tgroup",
+    "moe_expert_ffn_bwd_fp8", "moe_tgroup_tokens", "moe_quant_fp8_tgroup", "moe_route_range",
 )
 
 
@@ -63,6 +63,7 @@ def _load() -> ctypes.CDLL:
         "moe_router_fwd": (I, [P, P, P, I, I, I, I, P, P]),
         "moe_router_bwd": (I, [P, P, P, I, I, I, I, P, P, P, Z, P]),
         "moe_route": (I, [P, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
+        "moe_route_range": (I, [P, I, I, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
         "moe_route_bwd": (I, [P, P, P, P, I, I, I, I, P, P]),
         "moe_dispatch": (I, [P, P, I, P, P, I, I, I, P, P, P]),
         "moe_combine": (I, [P, P, I, P, P, I, I, I, P, I, P]),
@@ -229,3 +230,10 @@ def moe_expert_ffn_bwd_fp8(d_yp, h_save, xp_deq, a_deq, offsets, w1t, w1t_scale,
     a.accumulate = int(accumulate)
     a.ldt = inter["dy_t"].shape[1]
     _check("moe_expert_ffn_bwd_fp8", _lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), _stream()))
+
+
+def moe_route_range(logits, k, renorm, e_lo, e_hi, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace):
+    T, E = logits.shape
+    _check("moe_route_range", _lib.moe_route_range(_p(logits), T, E, k, renorm, e_lo, e_hi, _p(topk_idx), _p(topk_w),
+                                                   _p(counts), _p(offsets), _p(perm), _p(inv_perm), _p(workspace),
+                                                   workspace.numel(), _stream()))

@@ -221,8 +221,20 @@ int moe_route(const float* logits, int T, int E, int k, int renorm, int32_t* top
   if (T == 0) return MOE_OK;
   if (!logits || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID;
   if (!workspace || ws_bytes < route_ws_bytes(T, E)) return MOE_ERR_WORKSPACE;
-  return launch_route(logits, T, E, k, renorm != 0, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace,
+  return launch_route(logits, T, E, k, renorm != 0, 0, E, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace,
                       as_stream(stream));
+}
+
+int moe_route_range(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi, int32_t* topk_idx,
+                    float* topk_w, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                    void* workspace, size_t ws_bytes, void* stream) {
+  if (!sizes_ok(T, 16, E, k, 16)) return MOE_ERR_INVALID;
+  if (e_lo < 0 || e_hi > E || e_lo > e_hi) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_OK;
+  if (!logits || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID;
+  if (!workspace || ws_bytes < route_ws_bytes(T, E)) return MOE_ERR_WORKSPACE;
+  return launch_route(logits, T, E, k, renorm != 0, e_lo, e_hi, topk_idx, topk_w, counts, offsets, perm, inv_perm,
+                      workspace, as_stream(stream));
 }
 
 int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* topk_w, const float* d_topk_w, int T,

@@ -33,10 +33,11 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) dispatch_kernel(const T* 
     int my_row = 0;
     float my_mul = 1.f;
     if (lane < k) {
-      my_row = inv_perm[(long)t * k + lane];
+      my_row = inv_perm[(long)t * k + lane];          // < 0: the expert is not local, no copy
       if constexpr (kScaled) my_mul = row_mul[(long)t * k + lane];
-      if (x_scale != nullptr) xp_scale[my_row] = x_scale[t];
+      if (x_scale != nullptr && my_row >= 0) xp_scale[my_row] = x_scale[t];
     }
+    if (__ballot(lane < k && my_row >= 0) == 0) continue;      // no local expert wants this token: do not read it
     for (int c0 = 0; c0 < nvec; c0 += 64) {
       const int c = c0 + lane;
       const bool active = c < nvec;
@@ -50,7 +51,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) dispatch_kernel(const T* 
 #pragma unroll
           for (int i = 0; i < V; ++i) o.v[i] = from_f32<T>(to_f32(v.v[i]) * m);
         }
-        if (active)
+        if (active && r >= 0)
           __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o), reinterpret_cast<u32x4*>(xp + (long)r * d + (long)c * V));
       }
     }
@@ -99,7 +100,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) combine_kernel(const TIN*
     if (lane < k) {
       my_row = inv_perm[(long)t * k + lane];
       if (topk_w != nullptr) my_w = topk_w[(long)t * k + lane];
-      if (yp_scale != nullptr) my_w *= yp_scale[my_row];
+      if (yp_scale != nullptr && my_row >= 0) my_w *= yp_scale[my_row];
     }
     for (int c0 = 0; c0 < nvec; c0 += 64) {
       const int c = c0 + lane;
@@ -110,7 +111,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) combine_kernel(const TIN*
       for (int j = 0; j < k; ++j) {
         const int r = bcast(my_row, j);
         const float w = bcast(my_w, j);
-        if (active) {
+        if (active && r >= 0) {                  // r < 0: no local row, the term is left to another share
           float v[V];
           RowLoader<TIN>::load(yp + (long)r * d + (long)c * V, v);
 #pragma unroll
@@ -142,7 +143,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) gate_grad_kernel(const TD
     float my_scale = 1.f;
     if (lane < k) {
       my_row = inv_perm[(long)t * k + lane];
-      if (yp_scale != nullptr) my_scale = yp_scale[my_row];
+      if (yp_scale != nullptr && my_row >= 0) my_scale = yp_scale[my_row];
     }
     float acc[MOE_MAX_TOPK];
 #pragma unroll
@@ -162,7 +163,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) gate_grad_kernel(const TD
       for (int j = 0; j < MOE_MAX_TOPK; ++j) {
         if (j < k) {
           const int r = bcast(my_row, j);
-          if (active) {
+          if (active && r >= 0) {
             float v[V];
             RowLoader<TIN>::load(yp + (long)r * d + (long)c * V, v);
             float s = 0.f;

@@ -130,8 +130,10 @@ __global__ void __launch_bounds__(64) route_scan_kernel(int32_t* __restrict__ ch
 
 // One wave per chunk walks its assignments in order, 64 at a time.  Lanes with the same expert are found with
 // one ballot per bit of the expert id; the rank inside the group is a popcount of the lower lanes.
+// Only experts in [e_lo, e_hi) get rows (one GPU's expert-parallel share: the local scatter of Section 3.2);
+// assignments to other experts get inv_perm = -1.  offsets has e_hi - e_lo + 1 entries.
 __global__ void __launch_bounds__(64) route_rank_kernel(const int32_t* __restrict__ topk_idx, int T, int E, int k,
-                                                        int chunk_tokens, int nchunks,
+                                                        int e_lo, int e_hi, int chunk_tokens, int nchunks,
                                                         const int32_t* __restrict__ chunk_base,
                                                         const int32_t* __restrict__ counts,
                                                         int32_t* __restrict__ offsets,
@@ -143,7 +145,7 @@ __global__ void __launch_bounds__(64) route_rank_kernel(const int32_t* __restric
   int run = 0;
   for (int e0 = 0; e0 < E; e0 += 64) {
     const int e = e0 + lane;
-    const int c = e < E ? counts[e] : 0;
+    const int c = (e >= e_lo && e < e_hi) ? counts[e] : 0;
     int incl = c;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -156,7 +158,7 @@ __global__ void __launch_bounds__(64) route_rank_kernel(const int32_t* __restric
   if (lane == 0) expert_off[E] = run;
   __syncthreads();
   if (blockIdx.x == 0)
-    for (int e = lane; e <= E; e += 64) offsets[e] = expert_off[e];
+    for (int e = e_lo + lane; e <= e_hi; e += 64) offsets[e - e_lo] = expert_off[e];
   for (int e = lane; e < E; e += 64) next_row[e] = expert_off[e] + chunk_base[(long)e * nchunks + blockIdx.x];
   __syncthreads();
 
@@ -175,11 +177,15 @@ __global__ void __launch_bounds__(64) route_rank_kernel(const int32_t* __restric
       same &= ((e >> b) & 1) ? mb : ~mb;
     }
     if (valid) {
-      const int start = next_row[e];
-      const int r = start + __popcll(same & lt_mask);
-      inv_perm[a] = r;
-      perm[r] = (int)a;
-      if ((same >> lane) >> 1 == 0) next_row[e] = start + __popcll(same);   // the group's highest lane advances the row
+      if (e >= e_lo && e < e_hi) {
+        const int start = next_row[e];
+        const int r = start + __popcll(same & lt_mask);
+        inv_perm[a] = r;
+        perm[r] = (int)a;
+        if ((same >> lane) >> 1 == 0) next_row[e] = start + __popcll(same);   // the group's highest lane advances the row
+      } else {
+        inv_perm[a] = -1;
+      }
     }
     __syncthreads();
   }
@@ -234,8 +240,8 @@ size_t route_ws_bytes(int T, int E) {
   return align_up((size_t)cdiv(T, tb) * E * sizeof(int32_t), 256);
 }
 
-int launch_route(const float* logits, int T, int E, int k, int renorm, int32_t* idx, float* w, int32_t* counts,
-                 int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t s) {
+int launch_route(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi, int32_t* idx, float* w,
+                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t s) {
   const int tb = route_chunk_tokens(T);
   const int nchunks = cdiv(T, tb);
   int32_t* hist = static_cast<int32_t*>(ws);
@@ -253,7 +259,7 @@ int launch_route(const float* logits, int T, int E, int k, int renorm, int32_t* 
   if (rc != MOE_OK) return rc;
   route_scan_kernel<<<E, 64, 0, s>>>(hist, nchunks, counts);
   MOE_LAUNCH_CHECK();
-  route_rank_kernel<<<nchunks, 64, 0, s>>>(idx, T, E, k, tb, nchunks, hist, counts, offsets, perm, inv_perm);
+  route_rank_kernel<<<nchunks, 64, 0, s>>>(idx, T, E, k, e_lo, e_hi, tb, nchunks, hist, counts, offsets, perm, inv_perm);
   MOE_LAUNCH_CHECK();
   return MOE_OK;
 }

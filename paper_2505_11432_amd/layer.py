@@ -13,9 +13,15 @@ from . import binding as B
 
 class MoELayer:
     def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype=torch.bfloat16, renorm: int = 1,
-                 fp8: bool = False, grad_dtype=torch.float32, device="cuda:0"):
+                 fp8: bool = False, grad_dtype=torch.float32, device="cuda:0", expert_range=None):
+        """expert_range = (e_lo, e_hi): this GPU's expert-parallel share (Section 3.2): x holds the all-gathered
+        tokens, only rows routed to experts e_lo..e_hi-1 are dispatched, w1/w2 and their gradients hold those
+        experts only, and y / dx are the partial sums over them.  Row buffers keep the bound T*k."""
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
         self.M = T * k
+        self.expert_range = expert_range
+        self.E_local = E if expert_range is None else expert_range[1] - expert_range[0]
+        assert not (fp8 and expert_range is not None), "the fp8 path needs offsets[E] = M"
         self.dtype, self.renorm, self.fp8, self.device = dtype, renorm, fp8, device
         M = self.M
         dev = dict(device=device)
@@ -26,7 +32,7 @@ class MoELayer:
         self.topk_idx = torch.empty((T, k), **i32)
         self.topk_w = torch.empty((T, k), **f32)
         self.counts = torch.empty((E,), **i32)
-        self.offsets = torch.empty((E + 1,), **i32)
+        self.offsets = torch.empty((self.E_local + 1,), **i32)
         self.perm = torch.empty((M,), **i32)
         self.inv_perm = torch.empty((M,), **i32)
         self.h_save = torch.empty((M, 2 * f), **act)
@@ -37,8 +43,8 @@ class MoELayer:
         self.dx = torch.empty((T, d), **act)
         self.d_logits = torch.empty((T, E), **f32)
         self.d_w_r = torch.empty((E, d), **f32)
-        self.d_w1 = torch.empty((E, 2 * f, d), dtype=grad_dtype, **dev)
-        self.d_w2 = torch.empty((E, d, f), dtype=grad_dtype, **dev)
+        self.d_w1 = torch.empty((self.E_local, 2 * f, d), dtype=grad_dtype, **dev)
+        self.d_w2 = torch.empty((self.E_local, d, f), dtype=grad_dtype, **dev)
         if fp8:
             u8 = dict(dtype=torch.uint8, **dev)
             self.x_codes = torch.empty((T, d), **u8)
@@ -191,8 +197,12 @@ class MoELayer:
             c("router_fwd", B.moe_router_fwd, x, w_r, bias, self.logits)
         else:
             self.logits.copy_(logits)
-        c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
-          self.offsets, self.perm, self.inv_perm, self.workspace)
+        if self.expert_range is None:
+            c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
+              self.offsets, self.perm, self.inv_perm, self.workspace)
+        else:
+            c("route", B.moe_route_range, self.logits, self.k, self.renorm, self.expert_range[0], self.expert_range[1],
+              self.topk_idx, self.topk_w, self.counts, self.offsets, self.perm, self.inv_perm, self.workspace)
         c("dispatch", B.moe_dispatch, x, None, self.inv_perm, None, self.k, self.xp, None)
         c("expert_ffn_fwd", B.moe_expert_ffn_fwd, self.xp, None, self.offsets, w1, None, w2, None, self.h_save,
           self.yp, None, self.workspace)

@@ -499,3 +499,71 @@ def test_layer_fp8_backward_gemms(B, cfg):
     torch.cuda.synchronize()
     print("   vs bf16 backward GEMMs: dx", f"{max_norm_err(dx8, to_np(layer.dx)):.2e}",
           "dW1", f"{max_norm_err(dW1, to_np(layer.d_w1)):.2e}", "dW2", f"{max_norm_err(dW2, to_np(layer.d_w2)):.2e}")
+
+
+# ---- expert-parallel share: routing restricted to an expert range ---------------------------------------------
+@pytest.mark.parametrize("T,E,k,lo,hi", [(300, 12, 3, 4, 9), (1000, 32, 3, 8, 12), (257, 8, 2, 0, 8), (129, 6, 2, 3, 3),
+                                         (64, 5, 5, 4, 5), (2000, 64, 8, 56, 64)])
+def test_route_range_bit_exact(B, T, E, k, lo, hi):
+    z = random_logits(T, E, seed=T + E, quantum=0.5)
+    M = T * k
+    i32 = dict(dtype=torch.int32, device=DEV)
+    out = dict(idx=torch.full((T, k), -7, **i32), w=torch.full((T, k), -7.0, device=DEV),
+               counts=torch.full((E,), -7, **i32), offsets=torch.full((hi - lo + 1,), -7, **i32),
+               perm=torch.full((M,), -7, **i32), inv_perm=torch.full((M,), -7, **i32))
+    ws = torch.empty(max(B.moe_workspace_bytes(T, 16, E, k, 16, B.F32), 256), dtype=torch.uint8, device=DEV)
+    B.moe_route_range(to_dev(z), k, 1, lo, hi, out["idx"], out["w"], out["counts"], out["offsets"], out["perm"],
+                      out["inv_perm"], ws)
+    torch.cuda.synchronize()
+    ref = O.route_range(z, k, lo, hi)
+    for name in ("idx", "counts", "offsets", "inv_perm"):
+        assert np.array_equal(to_np(out[name]), ref[name]), name
+    n = int(ref["offsets"][-1])
+    assert np.array_equal(to_np(out["perm"])[:n], ref["perm"])
+    assert np.all(to_np(out["perm"])[n:] == -7)                     # rows past the local count are not touched
+    assert np.allclose(to_np(out["w"]), ref["w"], rtol=2e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_expert_parallel_share(B, dtype):
+    """One GPU's share (local experts only): every tensor against the oracle's layer_fwd_range / layer_bwd_range, and
+    the partial outputs of the shares add up to the full layer's output."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = MoEConfig("ep", T=520, d=128, E=12, k=3, f=160, dtype=dtype, w_std=0.09, wr_std=0.6)
+    inp = make_inputs(cfg, seed=6)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    z[:, 7] = -1e4                                               # an empty expert inside a range
+    td = torch_dtype(dtype)
+    tol = TOL[dtype]
+    x, dy, wr = to_dev(inp["x"], td), to_dev(inp["dy"], td), to_dev(inp["W_r"].T, td)
+    full = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k)
+    y_sum = np.zeros_like(full["y"])
+    for lo, hi in ((0, 5), (5, 9), (9, 12)):
+        layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, expert_range=(lo, hi))
+        for t in (layer.xp, layer.yp, layer.d_yp, layer.d_xp, layer.h_save):
+            t.fill_(float("nan"))                                # rows past the local count must never be read
+        w1, w2 = to_dev(inp["W1"][lo:hi], td), to_dev(inp["W2"][lo:hi], td)
+        layer.forward(x, wr, None, w1, w2, logits=to_dev(z))
+        layer.backward(x, wr, w1, w2, dy, with_router=False)
+        torch.cuda.synchronize()
+        fwd = O.layer_fwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, lo, hi)
+        bwd = O.layer_bwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, inp["dy"], fwd)
+        n = int(fwd["offsets"][-1])
+        assert np.array_equal(to_np(layer.offsets), fwd["offsets"]) and np.array_equal(to_np(layer.inv_perm), fwd["inv_perm"])
+        assert np.array_equal(to_np(layer.perm)[:n], fwd["perm"])
+        errs = {"xp": max_norm_err(to_np(layer.xp)[:n], fwd["xp"]), "H": max_norm_err(to_np(layer.h_save)[:n], fwd["H"]),
+                "Y": max_norm_err(to_np(layer.yp)[:n], fwd["Y"]), "y": max_norm_err(to_np(layer.y), fwd["y"]),
+                "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]), "dxp": max_norm_err(to_np(layer.d_xp)[:n], bwd["dxp"]),
+                "dx": max_norm_err(to_np(layer.dx), bwd["dx"])}
+        dW1, dW2 = to_np(layer.d_w1), to_np(layer.d_w2)
+        for e in range(hi - lo):
+            if fwd["counts"][lo + e] == 0:
+                assert np.all(dW1[e] == 0) and np.all(dW2[e] == 0)
+            else:
+                errs[f"dW1[{lo + e}]"] = max_norm_err(dW1[e], bwd["dW1"][e])
+                errs[f"dW2[{lo + e}]"] = max_norm_err(dW2[e], bwd["dW2"][e])
+        assert np.all(to_np(layer.d_topk_w)[(fwd["idx"] < lo) | (fwd["idx"] >= hi)] == 0)
+        bad = {k_: v for k_, v in errs.items() if not v < tol}
+        assert not bad, ((lo, hi), bad)
+        y_sum += to_np(layer.y)
+    assert max_norm_err(y_sum, full["y"]) < 2 * tol
