@@ -80,12 +80,17 @@ def cpu_baseline(cfg, inp, tokens):
     dy = inp["dy"][:tokens]
     t0 = time.perf_counter()
     z = O.router_logits(x, inp["W_r"], inp["bias"]).astype(np.float32)
-    fwd = O.layer_fwd(x, z, inp["W1"], inp["W2"], cfg.k, cfg.renorm)
-    O.layer_bwd(x, z, inp["W1"], inp["W2"], cfg.k, dy, fwd, cfg.renorm, W_r=inp["W_r"])
+    if cfg.expert_range is None:
+        fwd = O.layer_fwd(x, z, inp["W1"], inp["W2"], cfg.k, cfg.renorm)
+        O.layer_bwd(x, z, inp["W1"], inp["W2"], cfg.k, dy, fwd, cfg.renorm, W_r=inp["W_r"])
+    else:
+        lo, hi = cfg.expert_range
+        fwd = O.layer_fwd_range(x, z, inp["W1"], inp["W2"], cfg.k, lo, hi, cfg.renorm)
+        O.layer_bwd_range(x, z, inp["W1"], inp["W2"], cfg.k, dy, fwd)
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {tokens} of {cfg.T} tokens, all {cfg.E} experts and full d, d_ff; "
+            "sample": f"first {tokens} of {cfg.T} tokens, all {len(cfg.local_experts)} local experts and full d, d_ff; "
                       f"numpy float64 forward+backward, {dt:.1f} s"}
 
 
@@ -115,7 +120,8 @@ def main():
     w_r = to_dev_bf16(np.ascontiguousarray(inp["W_r"].T), torch)
     bias = torch.from_numpy(inp["bias"]).to("cuda:0") if cfg.bias != "none" else None
     w1, w2 = to_dev_bf16(inp["W1"], torch), to_dev_bf16(inp["W2"], torch)
-    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=fp8)
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=fp8,
+                     expert_range=cfg.expert_range)
     if fp8:
         layer.set_fp8_weights(w1, w2)       # parameters are kept in E4M3 across steps (Section 7): outside the timed loop
         if args.fp8_backward:
@@ -159,7 +165,9 @@ def main():
     layer.timers = None
     ms_per_step = total_ms / args.steps
 
-    M = cfg.M
+    counts = layer.counts.cpu().tolist()
+    # dispatched rows: all T*k, or the rows of the local experts for an expert-parallel share
+    M = cfg.M if cfg.expert_range is None else int(sum(counts[e] for e in cfg.local_experts))
     gemm_flops = 18.0 * M * cfg.d * cfg.f                      # three matmuls per routed token, fwd + 2x bwd
     # bf16 path: these two calls are exactly the six GEMM launches (fp8 path: plus the two row casts in the forward)
     gemm_ms = per_call["expert_ffn_fwd"] + per_call["expert_ffn_bwd"]
@@ -167,7 +175,6 @@ def main():
     # all six GEMMs on the fp8 cores: price against the fp8 peak (the casts inside the two calls are counted as time)
     peak = PEAK_FP8_TFLOPS if (fp8 and args.fp8_backward) else PEAK_BF16_TFLOPS
     row_bytes = (cfg.T + M) * cfg.d * 2.0
-    counts = layer.counts.cpu().tolist()
 
     out = {
         "metric": "MoE layer fwd+bwd tokens/s; grouped-GEMM TFLOPS as % of MI355X MFMA peak",
@@ -180,7 +187,9 @@ def main():
                                (("e4m3 dispatched activations / returned outputs, all six expert GEMMs on e4m3 operands, "
                                  if args.fp8_backward else
                                  "e4m3 dispatched activations / expert GEMMs / returned outputs forward, bf16 backward, ")
-                                if fp8 else "bf16 weights/activations, ") + "fp32 accumulate, fp32 weight gradients",
+                                if fp8 else "bf16 weights/activations, ") + "fp32 accumulate, fp32 weight gradients" +
+                               (f"; expert-parallel share: experts {cfg.expert_range[0]}..{cfg.expert_range[1] - 1} local, "
+                                f"{M} of {cfg.M} dispatched rows, tokens = the all-gathered tokens" if cfg.expert_range else ""),
                    "tokens": cfg.T, "expert_rows": counts},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",

@@ -37,10 +37,15 @@ class MoEConfig:
     bias: str = "none"    # "none" | "linear" | "zipf"
     bias_gamma: float = 0.0
     renorm: int = 1
+    expert_range: tuple | None = None     # (e_lo, e_hi): one GPU's expert-parallel share; weights only for these experts
 
     @property
     def M(self) -> int:
         return self.T * self.k
+
+    @property
+    def local_experts(self) -> range:
+        return range(self.E) if self.expert_range is None else range(*self.expert_range)
 
     def with_tokens(self, T: int) -> "MoEConfig":
         return replace(self, T=T)
@@ -61,6 +66,10 @@ CONFIGS = {
     "skewed": MoEConfig("skewed", T=16384, d=4096, E=32, k=4, f=2048, dtype="bf16",
                         w_std=0.02, wr_std=1.0 / math.sqrt(4096), bias="zipf",
                         bias_gamma=1.2),
+    # One GPU's expert-parallel share of the paper's Internal-352B layer (Table 2: h=4096, h_ffn=14336, 32 experts,
+    # top-3; SP8+EP8 inside a node): the 8 x 1024 all-gathered tokens of one 8192-token sequence, 4 of the 32 experts local.
+    "ep352b_share": MoEConfig("ep352b_share", T=8192, d=4096, E=32, k=3, f=14336, dtype="bf16",
+                              w_std=0.02, wr_std=1.0 / math.sqrt(4096), expert_range=(8, 12)),
     # Mixtral shapes with fp8 (e4m3) dispatched activations / returned outputs.
     "mixtral_fp8": MoEConfig("mixtral_fp8", T=8192, d=4096, E=8, k=2, f=14336, dtype="fp8",
                              w_std=0.02, wr_std=0.02),
@@ -124,13 +133,16 @@ def make_inputs(cfg: MoEConfig, seed: int = 0, with_weights: bool = True) -> dic
         "bias": router_bias(cfg, seed),
     }
     if with_weights:
-        w1 = np.empty((cfg.E, 2 * cfg.f, cfg.d), dtype=np.float32)
-        w2 = np.empty((cfg.E, cfg.d, cfg.f), dtype=np.float32)
+        # with an expert range, W1 / W2 hold the local experts only (index 0 = expert e_lo), drawn from the same
+        # per-expert streams as in the full layer
+        local = cfg.local_experts
+        w1 = np.empty((len(local), 2 * cfg.f, cfg.d), dtype=np.float32)
+        w2 = np.empty((len(local), cfg.d, cfg.f), dtype=np.float32)
         jobs = []
-        for e in range(cfg.E):
-            jobs.append(((seed, TENSOR_IDS["W_g"], e), (cfg.f, cfg.d), w1[e, :cfg.f, :]))
-            jobs.append(((seed, TENSOR_IDS["W_u"], e), (cfg.f, cfg.d), w1[e, cfg.f:, :]))
-            jobs.append(((seed, TENSOR_IDS["W_d"], e), (cfg.d, cfg.f), w2[e]))
+        for i, e in enumerate(local):
+            jobs.append(((seed, TENSOR_IDS["W_g"], e), (cfg.f, cfg.d), w1[i, :cfg.f, :]))
+            jobs.append(((seed, TENSOR_IDS["W_u"], e), (cfg.f, cfg.d), w1[i, cfg.f:, :]))
+            jobs.append(((seed, TENSOR_IDS["W_d"], e), (cfg.d, cfg.f), w2[i]))
         with ThreadPoolExecutor(max_workers=8) as pool:
             list(pool.map(lambda j: _normal(j[0], j[1], cfg.w_std, st, out=j[2]), jobs))
         out["W1"], out["W2"] = w1, w2
