@@ -241,3 +241,70 @@ def test_full_size_fp8_forward_and_fp8_backward_sampled():
     print("mixtral_fp8 full size:", {k_: f"{v:.2e}" for k_, v in errs.items()})
     bad = {k_: v for k_, v in errs.items() if not v < tol}
     assert not bad, bad
+
+
+def test_full_size_expert_parallel_share():
+    """ep352b_share (4 of 32 experts local, all-gathered tokens) at full size: routing bit-exact, sampled tokens'
+    local rows, partial outputs and partial input gradients, and weight-gradient slices of two local experts."""
+    cfg = CONFIGS["ep352b_share"]
+    inp = make_inputs(cfg, seed=0)
+    from paper_2505_11432_amd.layer import MoELayer
+    lo_e, hi_e = cfg.expert_range
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, expert_range=cfg.expert_range)
+    x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
+    w_r = dev_bf16(np.ascontiguousarray(inp["W_r"].T))
+    w1, w2 = dev_bf16(inp["W1"]), dev_bf16(inp["W2"])
+    layer.forward(x, w_r, None, w1, w2)
+    layer.backward(x, w_r, w1, w2, dy, with_router=False)
+    torch.cuda.synchronize()
+    T, k, d, f = cfg.T, cfg.k, cfg.d, cfg.f
+    z = layer.logits.cpu().numpy()
+    r = O.route_range(z, k, lo_e, hi_e, cfg.renorm)
+    n = int(r["offsets"][-1])
+    for nm, got in (("idx", layer.topk_idx), ("counts", layer.counts), ("offsets", layer.offsets), ("inv_perm", layer.inv_perm)):
+        assert np.array_equal(to_np(got), r[nm]), nm
+    assert np.array_equal(to_np(layer.perm)[:n], r["perm"])
+    print(f"ep352b_share: {n} of {T * k} rows local, per local expert {np.diff(r['offsets']).tolist()}")
+    rng = np.random.default_rng(9)
+    toks = np.sort(rng.choice(T, size=256, replace=False))
+    a_ids = (toks[:, None] * k + np.arange(k)[None, :]).reshape(-1)
+    rows_all = r["inv_perm"][a_ids].astype(np.int64)
+    keep = rows_all >= 0
+    a_l, rows_l = a_ids[keep], rows_all[keep]
+    e_l = r["idx"].reshape(-1)[a_l] - lo_e
+    order = np.argsort(e_l, kind="stable")
+    a_s, rows_s, e_s = a_l[order], rows_l[order], e_l[order]
+    offs = np.concatenate([[0], np.cumsum(np.bincount(e_s, minlength=hi_e - lo_e))]).astype(np.int32)
+    xp_s = inp["x"][a_s // k].astype(np.float64)
+    H, A, Y = O.expert_ffn_fwd(xp_s, offs, inp["W1"], inp["W2"])
+    w_s = r["w"].reshape(-1)[a_s]
+    dY_s = inp["dy"][a_s // k].astype(np.float64) * w_s[:, None]
+    dxp_s, _, _, _ = O.expert_ffn_bwd(xp_s, H, dY_s, offs, inp["W1"], inp["W2"])
+    rows_t = torch.from_numpy(rows_s).to(DEV)
+    errs = {"xp": max_norm_err(to_np(layer.xp[rows_t]), xp_s), "H": max_norm_err(to_np(layer.h_save[rows_t]), H),
+            "Y": max_norm_err(to_np(layer.yp[rows_t]), Y), "dxp": max_norm_err(to_np(layer.d_xp[rows_t]), dxp_s)}
+    y_ref = np.zeros((T, d)); dx_ref = np.zeros((T, d)); dw_ref = np.zeros((T, k))
+    np.add.at(y_ref, a_s // k, Y * w_s[:, None])
+    np.add.at(dx_ref, a_s // k, dxp_s)
+    dw_ref[a_s // k, a_s % k] = np.einsum("rd,rd->r", inp["dy"][a_s // k].astype(np.float64), Y)
+    tt = torch.from_numpy(toks).to(DEV)
+    errs["y (partial)"] = max_norm_err(to_np(layer.y[tt]), y_ref[toks])
+    errs["dx (partial)"] = max_norm_err(to_np(layer.dx[tt]), dx_ref[toks])
+    errs["dw"] = max_norm_err(to_np(layer.d_topk_w[tt]), dw_ref[toks])
+    assert np.all(to_np(layer.d_topk_w[tt])[rows_all.reshape(-1, k) < 0] == 0)
+    for e in (0, hi_e - lo_e - 1):
+        lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
+        j0 = int(rng.integers(0, f // 64)) * 64
+        sl = np.r_[j0:j0 + 64, f + j0:f + j0 + 64]
+        W1s, W2s = inp["W1"][e:e + 1, sl, :], inp["W2"][e:e + 1, :, j0:j0 + 64]
+        a_e = r["perm"][lo:hi].astype(np.int64)
+        xp_e = inp["x"][a_e // k].astype(np.float64)
+        dY_e = inp["dy"][a_e // k].astype(np.float64) * r["w"].reshape(-1)[a_e][:, None]
+        off_e = np.array([0, hi - lo], dtype=np.int32)
+        H_e, _, _ = O.expert_ffn_fwd(xp_e, off_e, W1s, W2s)
+        _, dW1s, dW2s, _ = O.expert_ffn_bwd(xp_e, H_e, dY_e, off_e, W1s, W2s)
+        errs[f"dW1[{lo_e + e}]"] = max_norm_err(to_np(layer.d_w1[e][torch.from_numpy(sl).to(DEV)]), dW1s[0])
+        errs[f"dW2[{lo_e + e}]"] = max_norm_err(to_np(layer.d_w2[e][:, j0:j0 + 64]), dW2s[0])
+    print("ep352b_share", {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < TOL}
+    assert not bad, bad
