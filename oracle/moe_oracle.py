@@ -606,3 +606,77 @@ def layer_bwd_fp8_gemm(x, logits, W1, W2, k: int, dy, fwd: dict, renorm: int = 1
     dx = combine(g["dxp"], fwd["inv_perm"], None, T, k)
     dz = route_bwd(logits, fwd["idx"], fwd["w"], dw, renorm)
     return dict(dy_hat=dy_hat, dYp=dYp, dw=dw, dxp=g["dxp"], dW1=g["dW1"], dW2=g["dW2"], dH=g["dH"], dx=dx, dz=dz)
+
+
+# --------------------------------------------------------------------------
+# Load balance: Section 3.2 "Load balance" (auxiliary loss and token dropping, both per device:
+# the experts placed on one GPU form a group, as in DeepSeek-V2)
+# --------------------------------------------------------------------------
+def softmax_all(logits) -> np.ndarray:
+    """Affinity s[t,e]: softmax of a token's logits over all E experts."""
+    z = np.asarray(logits, F64)
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    return p / p.sum(axis=1, keepdims=True)
+
+
+def balance_loss(logits, idx, n_groups: int, alpha: float):
+    """Device-level balance loss.  Reading (the paper names DeepSeek-V2's scheme and gives no formula):
+    with f_e = E/(k*T) * #{assignments to e}, P_e = mean_t s[t,e], experts e of group g = the E/n_groups
+    consecutive experts on device g:  f'_g = mean_{e in g} f_e,  P'_g = sum_{e in g} P_e,
+    loss = alpha * sum_g f'_g * P'_g.  Returns (loss, f' [n_groups], P' [n_groups])."""
+    T, E = logits.shape
+    k = idx.shape[1]
+    per = E // n_groups
+    counts = np.bincount(np.asarray(idx).reshape(-1), minlength=E).astype(F64)
+    f = counts * E / (k * T)
+    P = softmax_all(logits).mean(axis=0)
+    fg = f.reshape(n_groups, per).mean(axis=1)
+    Pg = P.reshape(n_groups, per).sum(axis=1)
+    return float(alpha * np.sum(fg * Pg)), fg, Pg
+
+
+def balance_loss_bwd(logits, idx, n_groups: int, alpha: float) -> np.ndarray:
+    """d loss / d logits with the selection counts f treated as constants (they are piecewise constant):
+    dz[t,c] = alpha/T * s[t,c] * (F_c - sum_e s[t,e] F_e),  F_e = f' of e's group."""
+    T, E = logits.shape
+    _, fg, _ = balance_loss(logits, idx, n_groups, 1.0)
+    F = np.repeat(fg, E // n_groups)
+    s = softmax_all(logits)
+    return alpha / T * s * (F[None, :] - (s * F[None, :]).sum(axis=1, keepdims=True))
+
+
+def capacity_keep(logits, idx, n_groups: int, capacity: int) -> np.ndarray:
+    """Device-level token dropping.  Reading (after DeepSeek-V2, which the paper follows): each device keeps at
+    most `capacity` assignments; when more arrive, those with the lowest affinity s[t, e] are dropped; among
+    equal affinities (compared as float32) the higher assignment id goes first.  Returns keep [T,k] bool."""
+    T, E = logits.shape
+    k = idx.shape[1]
+    per = E // n_groups
+    s32 = softmax_all(logits).astype(np.float32)
+    score = np.take_along_axis(s32, np.asarray(idx, np.int64), axis=1).reshape(-1)
+    grp = (np.asarray(idx).reshape(-1) // per)
+    keep = np.zeros(T * k, dtype=bool)
+    for g in range(n_groups):
+        a = np.flatnonzero(grp == g)
+        order = np.lexsort((a, -score[a].astype(F64)))          # best first: score descending, id ascending
+        keep[a[order[:capacity]]] = True
+    return keep.reshape(T, k)
+
+
+def route_capacity(logits, k: int, n_groups: int, capacity: int, renorm: int = 1) -> dict:
+    """route() with device-level token dropping: a dropped assignment keeps its slot in idx / w (the weights are
+    not renormalised) but gets no row (inv_perm = -1); counts, offsets and perm cover the kept assignments."""
+    idx = topk_select(logits, k)
+    w = gate_weights(logits, idx, renorm)
+    keep = capacity_keep(logits, idx, n_groups, capacity)
+    E = logits.shape[1]
+    e_of_a = idx.reshape(-1).astype(np.int64)
+    kf = keep.reshape(-1)
+    counts = np.array([np.count_nonzero((e_of_a == e) & kf) for e in range(E)], dtype=np.int32)
+    offsets = np.zeros(E + 1, dtype=np.int64)
+    offsets[1:] = np.cumsum(counts)
+    perm = np.concatenate([np.flatnonzero((e_of_a == e) & kf) for e in range(E)] + [np.zeros(0, np.int64)])
+    inv_perm = np.full(e_of_a.size, -1, dtype=np.int64)
+    inv_perm[perm] = np.arange(perm.size)
+    return dict(idx=idx, w=w, keep=keep, counts=counts, offsets=offsets.astype(np.int32), perm=perm.astype(np.int32),
+                inv_perm=inv_perm.astype(np.int32))

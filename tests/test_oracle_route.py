@@ -238,3 +238,73 @@ def test_expert_parallel_shares_add_up_to_the_full_layer():
     assert np.allclose(y, full["y"], rtol=1e-12, atol=1e-12)
     assert np.allclose(dx, gfull["dx"], rtol=1e-12, atol=1e-12)
     assert np.allclose(dw, gfull["dw"], rtol=1e-12, atol=1e-12)
+
+
+# ---- load balance (Section 3.2: auxiliary loss and token dropping per device) ------------------------------------
+def test_balance_loss_closed_forms_and_gradient():
+    T, E, k, G = 64, 8, 2, 4
+    # uniform logits: s = 1/E, P'_g = per/E; f'_g depends on the selection only; sum_g f'_g = G * (E/(kT)) * kT / E / ... = G
+    z = np.zeros((T, E), dtype=np.float32)
+    idx = O.topk_select(z, k)                              # ties -> experts 0 and 1 for every token
+    loss, fg, Pg = O.balance_loss(z, idx, G, alpha=0.5)
+    assert np.allclose(Pg, 2 / 8) and np.allclose(fg, [E / (k * T) * T * 2 / 2, 0, 0, 0])     # all assignments on device 0
+    assert np.isclose(loss, 0.5 * fg[0] * 0.25)
+    # perfectly balanced selection and uniform affinities give alpha (the textbook minimum of this loss)
+    idx_bal = np.stack([np.arange(T) % E, (np.arange(T) + 4) % E], axis=1)
+    loss_bal, fg_bal, _ = O.balance_loss(z, idx_bal, G, alpha=1.0)
+    assert np.allclose(fg_bal, 1.0) and np.isclose(loss_bal, 1.0)
+    # gradient against central differences (f held fixed, as the analytic form assumes)
+    rng = np.random.default_rng(2)
+    z = rng.standard_normal((12, E))
+    idx = O.topk_select(z.astype(np.float32), k)
+    g = O.balance_loss_bwd(z, idx, G, alpha=0.7)
+    num = np.zeros_like(z)
+    for t in range(12):
+        for c in range(E):
+            zp, zm = z.copy(), z.copy()
+            zp[t, c] += 1e-6; zm[t, c] -= 1e-6
+            num[t, c] = (O.balance_loss(zp, idx, G, 0.7)[0] - O.balance_loss(zm, idx, G, 0.7)[0]) / 2e-6
+    assert np.allclose(g, num, rtol=1e-5, atol=1e-9)
+    assert np.allclose(g.sum(axis=1), 0, atol=1e-15)          # softmax gradients sum to zero per token
+
+
+def test_capacity_keep_drops_the_lowest_affinities_per_device():
+    rng = np.random.default_rng(8)
+    T, E, k, G, cap = 50, 6, 2, 3, 20
+    z = rng.standard_normal((T, E)).astype(np.float32)
+    z[:, 0] += 1.5                                          # device 0 is overloaded
+    idx = O.topk_select(z, k)
+    keep = O.capacity_keep(z, idx, G, cap)
+    s = O.softmax_all(z).astype(np.float32)
+    score = np.take_along_axis(s, idx.astype(np.int64), axis=1)
+    grp = idx // (E // G)
+    for g in range(G):
+        m = grp == g
+        assert keep[m].sum() == min(cap, m.sum())
+        if m.sum() > cap:                                   # every kept score >= every dropped score of the device
+            assert score[m & keep].min() >= score[m & ~keep].max()
+    # brute force on a tiny case with ties: equal affinities -> the lower assignment id stays
+    z2 = np.zeros((4, 2), dtype=np.float32)
+    keep2 = O.capacity_keep(z2, O.topk_select(z2, 1), 1, 2)
+    assert keep2.reshape(-1).tolist() == [True, True, False, False]
+    assert O.capacity_keep(z, idx, G, T * k).all()          # capacity never reached: nothing dropped
+
+
+def test_route_capacity_row_map():
+    z = random_logits(200, 8, seed=3)
+    z[:, 1] += 2.0
+    full = O.route(z, 2)
+    r = O.route_capacity(z, 2, n_groups=4, capacity=60)
+    assert np.array_equal(r["idx"], full["idx"]) and np.array_equal(r["w"], full["w"])
+    kf = r["keep"].reshape(-1)
+    assert np.all(r["inv_perm"][~kf] == -1)
+    assert np.array_equal(np.sort(r["perm"]), np.flatnonzero(kf))
+    e_rows = full["idx"].reshape(-1)[r["perm"]]
+    assert np.all(np.diff(e_rows) >= 0)                       # grouped by expert
+    for e in range(8):
+        seg = r["perm"][r["offsets"][e]:r["offsets"][e + 1]]
+        assert np.all(np.diff(seg) > 0) and r["counts"][e] == seg.size
+    assert r["counts"].reshape(4, 2).sum(axis=1).max() <= 60
+    big = O.route_capacity(z, 2, n_groups=4, capacity=10 ** 6)
+    for nm in ("counts", "offsets", "perm", "inv_perm"):
+        assert np.array_equal(big[nm], full[nm]), nm
