@@ -104,6 +104,37 @@ int moe_route_range(const float* logits, int T, int E, int k, int renorm, int e_
                     int32_t* perm, int32_t* inv_perm, void* workspace, size_t ws_bytes,
                     void* stream);
 
+/* ---- load balance (Section 3.2 "Load balance": auxiliary loss and token dropping, both per
+ * device: the experts placed on one GPU form a group, as in DeepSeek-V2) --------------------
+ * Device g holds the E / n_groups consecutive experts g*E/n_groups ...; E % n_groups = 0.
+ *
+ * moe_route_capacity: moe_route with device-level token dropping.  The affinity of an
+ * assignment is the softmax of its token's logits over all E experts, read at the selected
+ * expert (fp32; written to score [T,k]).  A device keeps at most `capacity` assignments; when
+ * more arrive the ones with the lowest affinity are dropped, among equal affinities the higher
+ * assignment id first.  A dropped assignment keeps its slot in topk_idx / topk_w (the weights
+ * are not renormalised) and gets inv_perm = -1; counts [E], offsets [E+1] and perm cover the
+ * kept assignments (perm past offsets[E] is not written).  Workspace:
+ * moe_route_capacity_workspace_bytes(T, E, k). */
+size_t moe_route_capacity_workspace_bytes(int T, int E, int k);
+int moe_route_capacity(const float* logits, int T, int E, int k, int renorm, int n_groups,
+                       int capacity, int32_t* topk_idx, float* topk_w, float* score,
+                       int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                       void* workspace, size_t ws_bytes, void* stream);
+
+/* Device-level balance loss.  With s[t,e] the affinity above, f_e = E/(k*T) * counts[e]
+ * (counts = assignments per expert before any dropping, as moe_route writes them),
+ * P_e = mean_t s[t,e]:  f'_g = mean of f_e over device g,  P'_g = sum of P_e over device g,
+ * loss[0] = alpha * sum_g f'_g * P'_g; group_f [n_groups] = f', group_p [n_groups] = P'.
+ * The sums over tokens run in a fixed order (reproducible).  workspace: moe_workspace_bytes.
+ * moe_balance_loss_bwd ADDS d loss / d logits into d_logits [T,E], f' held constant:
+ *   d_logits[t,c] += alpha/T * s[t,c] * (F_c - sum_e s[t,e] * F_e),  F_e = f' of e's device. */
+int moe_balance_loss(const float* logits, const int32_t* counts, int T, int E, int k,
+                     int n_groups, float alpha, float* loss, float* group_f, float* group_p,
+                     void* workspace, size_t ws_bytes, void* stream);
+int moe_balance_loss_bwd(const float* logits, const float* group_f, int T, int E, int n_groups,
+                         float alpha, float* d_logits, void* stream);
+
 /* Derivative of the gate weights w.r.t. the logits with the selection held constant.
  * d_logits [T,E] is fully written (zeros at unselected experts when renorm=1).
  * `logits` is only read when renorm=0 and may be NULL otherwise. */

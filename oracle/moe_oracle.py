@@ -124,16 +124,26 @@ def route_range(logits: np.ndarray, k: int, e_lo: int, e_hi: int, renorm: int = 
 def layer_fwd_range(x, logits, W1_local, W2_local, k: int, e_lo: int, e_hi: int, renorm: int = 1) -> dict:
     """Forward of one expert-parallel share: W1_local / W2_local hold experts e_lo..e_hi-1; y is the partial
     sum over the local experts (what a reduce-scatter would add up across the ranks)."""
+    return layer_fwd_routed(x, route_range(logits, k, e_lo, e_hi, renorm), W1_local, W2_local, k)
+
+
+def layer_fwd_routed(x, r: dict, W1, W2, k: int) -> dict:
+    """Forward from a routing result r (route_range or route_capacity): assignments without a row contribute
+    nothing; W1 / W2 hold the experts that r's offsets cover."""
     T = x.shape[0]
-    r = route_range(logits, k, e_lo, e_hi, renorm)
+    r = dict(r)
     xp = dispatch(x, r["perm"], k)
-    H, A, Y = expert_ffn_fwd(xp, r["offsets"], W1_local, W2_local)
+    H, A, Y = expert_ffn_fwd(xp, r["offsets"], W1, W2)
     y = combine(Y, r["inv_perm"], r["w"], T, k)
     r.update(xp=xp, H=H, A=A, Y=Y, y=y)
     return r
 
 
 def layer_bwd_range(x, logits, W1_local, W2_local, k: int, dy, fwd: dict) -> dict:
+    return layer_bwd_routed(x, W1_local, W2_local, k, dy, fwd)
+
+
+def layer_bwd_routed(x, W1_local, W2_local, k: int, dy, fwd: dict) -> dict:
     """Backward of layer_fwd_range: gradients of the local experts, the local part of dx and of the gate-weight
     gradient (zero for dropped assignments); the gate's own backward needs the sum of dw over all shares."""
     T = x.shape[0]
@@ -645,15 +655,19 @@ def balance_loss_bwd(logits, idx, n_groups: int, alpha: float) -> np.ndarray:
     return alpha / T * s * (F[None, :] - (s * F[None, :]).sum(axis=1, keepdims=True))
 
 
-def capacity_keep(logits, idx, n_groups: int, capacity: int) -> np.ndarray:
-    """Device-level token dropping.  Reading (after DeepSeek-V2, which the paper follows): each device keeps at
-    most `capacity` assignments; when more arrive, those with the lowest affinity s[t, e] are dropped; among
-    equal affinities (compared as float32) the higher assignment id goes first.  Returns keep [T,k] bool."""
-    T, E = logits.shape
-    k = idx.shape[1]
-    per = E // n_groups
+def affinity_scores(logits, idx) -> np.ndarray:
+    """s[t, idx[t,j]] as float32 [T,k]: the precision in which the drop decision is taken."""
     s32 = softmax_all(logits).astype(np.float32)
-    score = np.take_along_axis(s32, np.asarray(idx, np.int64), axis=1).reshape(-1)
+    return np.take_along_axis(s32, np.asarray(idx, np.int64), axis=1)
+
+
+def capacity_keep(score, idx, E: int, n_groups: int, capacity: int) -> np.ndarray:
+    """Device-level token dropping.  Reading (after DeepSeek-V2, which the paper follows): each device keeps at
+    most `capacity` assignments; when more arrive, those with the lowest affinity score[t,j] (float32) are
+    dropped; among equal affinities the higher assignment id goes first.  Returns keep [T,k] bool."""
+    T, k = idx.shape
+    per = E // n_groups
+    score = np.asarray(score, np.float32).reshape(-1)
     grp = (np.asarray(idx).reshape(-1) // per)
     keep = np.zeros(T * k, dtype=bool)
     for g in range(n_groups):
@@ -663,13 +677,16 @@ def capacity_keep(logits, idx, n_groups: int, capacity: int) -> np.ndarray:
     return keep.reshape(T, k)
 
 
-def route_capacity(logits, k: int, n_groups: int, capacity: int, renorm: int = 1) -> dict:
+def route_capacity(logits, k: int, n_groups: int, capacity: int, renorm: int = 1, score=None) -> dict:
     """route() with device-level token dropping: a dropped assignment keeps its slot in idx / w (the weights are
-    not renormalised) but gets no row (inv_perm = -1); counts, offsets and perm cover the kept assignments."""
+    not renormalised) but gets no row (inv_perm = -1); counts, offsets and perm cover the kept assignments.
+    `score` overrides the affinities the decision is taken from (a parity test passes the kernel's own)."""
     idx = topk_select(logits, k)
     w = gate_weights(logits, idx, renorm)
-    keep = capacity_keep(logits, idx, n_groups, capacity)
     E = logits.shape[1]
+    if score is None:
+        score = affinity_scores(logits, idx)
+    keep = capacity_keep(score, idx, E, n_groups, capacity)
     e_of_a = idx.reshape(-1).astype(np.int64)
     kf = keep.reshape(-1)
     counts = np.array([np.count_nonzero((e_of_a == e) & kf) for e in range(E)], dtype=np.int32)
@@ -678,5 +695,5 @@ def route_capacity(logits, k: int, n_groups: int, capacity: int, renorm: int = 1
     perm = np.concatenate([np.flatnonzero((e_of_a == e) & kf) for e in range(E)] + [np.zeros(0, np.int64)])
     inv_perm = np.full(e_of_a.size, -1, dtype=np.int64)
     inv_perm[perm] = np.arange(perm.size)
-    return dict(idx=idx, w=w, keep=keep, counts=counts, offsets=offsets.astype(np.int32), perm=perm.astype(np.int32),
+    return dict(idx=idx, w=w, keep=keep, score=np.asarray(score, np.float32).reshape(idx.shape), counts=counts, offsets=offsets.astype(np.int32), perm=perm.astype(np.int32),
                 inv_perm=inv_perm.astype(np.int32))

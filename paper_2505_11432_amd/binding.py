@@ -25,6 +25,7 @@ EXPORTS = (
     "moe_router_fwd", "moe_router_bwd", "moe_route", "moe_route_bwd", "moe_dispatch", "moe_combine",
     "moe_gate_grad", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_quant_fp8", "moe_dequant_fp8",
     "moe_expert_ffn_bwd_fp8", "moe_tgroup_tokens", "moe_quant_fp8_tgroup", "moe_route_range",
+    "moe_route_capacity_workspace_bytes", "moe_route_capacity", "moe_balance_loss", "moe_balance_loss_bwd",
 )
 
 
@@ -64,6 +65,10 @@ def _load() -> ctypes.CDLL:
         "moe_router_bwd": (I, [P, P, P, I, I, I, I, P, P, P, Z, P]),
         "moe_route": (I, [P, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
         "moe_route_range": (I, [P, I, I, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
+        "moe_route_capacity_workspace_bytes": (Z, [I, I, I]),
+        "moe_route_capacity": (I, [P, I, I, I, I, I, I, P, P, P, P, P, P, P, P, Z, P]),
+        "moe_balance_loss": (I, [P, P, I, I, I, I, ctypes.c_float, P, P, P, P, Z, P]),
+        "moe_balance_loss_bwd": (I, [P, P, I, I, I, ctypes.c_float, P, P]),
         "moe_route_bwd": (I, [P, P, P, P, I, I, I, I, P, P]),
         "moe_dispatch": (I, [P, P, I, P, P, I, I, I, P, P, P]),
         "moe_combine": (I, [P, P, I, P, P, I, I, I, P, I, P]),
@@ -237,3 +242,28 @@ def moe_route_range(logits, k, renorm, e_lo, e_hi, topk_idx, topk_w, counts, off
     _check("moe_route_range", _lib.moe_route_range(_p(logits), T, E, k, renorm, e_lo, e_hi, _p(topk_idx), _p(topk_w),
                                                    _p(counts), _p(offsets), _p(perm), _p(inv_perm), _p(workspace),
                                                    workspace.numel(), _stream()))
+
+
+def moe_route_capacity_workspace_bytes(T, E, k) -> int:
+    return _lib.moe_route_capacity_workspace_bytes(T, E, k)
+
+
+def moe_route_capacity(logits, k, renorm, n_groups, capacity, topk_idx, topk_w, score, counts, offsets, perm, inv_perm,
+                       workspace):
+    T, E = logits.shape
+    _check("moe_route_capacity", _lib.moe_route_capacity(
+        _p(logits), T, E, k, renorm, n_groups, capacity, _p(topk_idx), _p(topk_w), _p(score), _p(counts), _p(offsets),
+        _p(perm), _p(inv_perm), _p(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_balance_loss(logits, counts, k, n_groups, alpha, loss, group_f, group_p, workspace):
+    T, E = logits.shape
+    _check("moe_balance_loss", _lib.moe_balance_loss(_p(logits), _p(counts), T, E, k, n_groups, alpha, _p(loss), _p(group_f),
+                                                     _p(group_p), _p(workspace),
+                                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_balance_loss_bwd(logits, group_f, n_groups, alpha, d_logits):
+    T, E = logits.shape
+    _check("moe_balance_loss_bwd", _lib.moe_balance_loss_bwd(_p(logits), _p(group_f), T, E, n_groups, alpha, _p(d_logits),
+                                                             _stream()))

@@ -221,8 +221,8 @@ int moe_route(const float* logits, int T, int E, int k, int renorm, int32_t* top
   if (T == 0) return MOE_OK;
   if (!logits || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID;
   if (!workspace || ws_bytes < route_ws_bytes(T, E)) return MOE_ERR_WORKSPACE;
-  return launch_route(logits, T, E, k, renorm != 0, 0, E, topk_idx, topk_w, counts, offsets, perm, inv_perm, workspace,
-                      as_stream(stream));
+  return launch_route(logits, T, E, k, renorm != 0, 0, E, 0, 0, topk_idx, topk_w, nullptr, counts, offsets, perm, inv_perm,
+                      workspace, as_stream(stream));
 }
 
 int moe_route_range(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi, int32_t* topk_idx,
@@ -233,8 +233,45 @@ int moe_route_range(const float* logits, int T, int E, int k, int renorm, int e_
   if (T == 0) return MOE_OK;
   if (!logits || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID;
   if (!workspace || ws_bytes < route_ws_bytes(T, E)) return MOE_ERR_WORKSPACE;
-  return launch_route(logits, T, E, k, renorm != 0, e_lo, e_hi, topk_idx, topk_w, counts, offsets, perm, inv_perm,
-                      workspace, as_stream(stream));
+  return launch_route(logits, T, E, k, renorm != 0, e_lo, e_hi, 0, 0, topk_idx, topk_w, nullptr, counts, offsets, perm,
+                      inv_perm, workspace, as_stream(stream));
+}
+
+int moe_balance_loss(const float* logits, const int32_t* counts, int T, int E, int k, int n_groups, float alpha,
+                     float* loss, float* group_f, float* group_p, void* workspace, size_t ws_bytes, void* stream) {
+  if (!sizes_ok(T, 16, E, k, 16)) return MOE_ERR_INVALID;
+  if (n_groups < 1 || n_groups > E || E % n_groups != 0) return MOE_ERR_INVALID;
+  if (!loss || !group_f || !group_p) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_ERR_INVALID;                 // the loss is a mean over tokens
+  if (!logits || !counts) return MOE_ERR_INVALID;
+  if (!workspace || ws_bytes < balance_ws_bytes(T, E)) return MOE_ERR_WORKSPACE;
+  return launch_balance_loss(logits, counts, T, E, k, n_groups, alpha, loss, group_f, group_p, workspace, as_stream(stream));
+}
+
+int moe_balance_loss_bwd(const float* logits, const float* group_f, int T, int E, int n_groups, float alpha,
+                         float* d_logits, void* stream) {
+  if (T < 0 || E < 1 || E > MOE_MAX_EXPERTS) return MOE_ERR_INVALID;
+  if (n_groups < 1 || n_groups > E || E % n_groups != 0) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_OK;
+  if (!logits || !group_f || !d_logits) return MOE_ERR_INVALID;
+  return launch_balance_loss_bwd(logits, group_f, T, E, n_groups, alpha, d_logits, as_stream(stream));
+}
+
+size_t moe_route_capacity_workspace_bytes(int T, int E, int k) {
+  if (!sizes_ok(T, 16, E, k, 16)) return 0;
+  return route_capacity_ws_bytes(T, E, k);
+}
+
+int moe_route_capacity(const float* logits, int T, int E, int k, int renorm, int n_groups, int capacity,
+                       int32_t* topk_idx, float* topk_w, float* score, int32_t* counts, int32_t* offsets,
+                       int32_t* perm, int32_t* inv_perm, void* workspace, size_t ws_bytes, void* stream) {
+  if (!sizes_ok(T, 16, E, k, 16)) return MOE_ERR_INVALID;
+  if (n_groups < 1 || n_groups > E || E % n_groups != 0 || capacity < 0) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_OK;
+  if (!logits || !topk_idx || !topk_w || !score || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID;
+  if (!workspace || ws_bytes < route_capacity_ws_bytes(T, E, k)) return MOE_ERR_WORKSPACE;
+  return launch_route(logits, T, E, k, renorm != 0, 0, E, n_groups, capacity, topk_idx, topk_w, score, counts, offsets, perm,
+                      inv_perm, workspace, as_stream(stream));
 }
 
 int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* topk_w, const float* d_topk_w, int T,

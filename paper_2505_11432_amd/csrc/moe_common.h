@@ -71,8 +71,15 @@ struct GemmProblem {
 };
 int launch_gemm_generic(const GemmProblem& p, moe_dtype a_dt, moe_dtype b_dt, moe_dtype c_dt, hipStream_t s);
 
-int launch_route(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi, int32_t* idx, float* w,
-                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t s);
+int launch_route(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi, int n_groups, int capacity,
+                 int32_t* idx, float* w, float* score, int32_t* counts, int32_t* offsets, int32_t* perm,
+                 int32_t* inv_perm, void* ws, hipStream_t s);
+size_t route_capacity_ws_bytes(int T, int E, int k);
+size_t balance_ws_bytes(int T, int E);
+int launch_balance_loss(const float* logits, const int32_t* counts, int T, int E, int k, int n_groups, float alpha,
+                        float* loss, float* group_f, float* group_p, void* ws, hipStream_t s);
+int launch_balance_loss_bwd(const float* logits, const float* group_f, int T, int E, int n_groups, float alpha,
+                            float* d_logits, hipStream_t s);
 int launch_route_bwd(const float* logits, const int32_t* idx, const float* w, const float* dw, int T, int E, int k,
                      int renorm, float* d_logits, hipStream_t s);
 int launch_dispatch(const void* x, const float* x_scale, moe_dtype dt, const int32_t* inv_perm, const float* row_mul,

@@ -25,7 +25,8 @@ template <int G, int VPL>
 __global__ void __launch_bounds__(256) route_topk_kernel(const float* __restrict__ logits, int T, int E, int k,
                                                          int renorm, int chunk_tokens, int nchunks,
                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                                                         int32_t* __restrict__ chunk_hist) {
+                                                         int32_t* __restrict__ chunk_hist,
+                                                         float* __restrict__ score) {
   __shared__ int hist[MOE_MAX_EXPERTS];
   for (int e = threadIdx.x; e < MOE_MAX_EXPERTS; e += blockDim.x) hist[e] = 0;
   __syncthreads();
@@ -78,20 +79,25 @@ __global__ void __launch_bounds__(256) route_topk_kernel(const float* __restrict
     // weights: softmax over the selected logits (renorm) or over all logits read at the selected ones
     const bool holds_slot = sub < k;
     const float ex = holds_slot ? expf(my_z - top_z) : 0.f;
-    float den;
-    if (renorm) {
-      den = ex;
-    } else {
-      den = 0.f;
+    float den, den_all = 0.f;
+    if (!renorm || score != nullptr) {
 #pragma unroll
       for (int i = 0; i < VPL; ++i)
-        if (sub + i * G < E) den += expf(v[i] - top_z);
-    }
+        if (sub + i * G < E) den_all += expf(v[i] - top_z);
 #pragma unroll
-    for (int off = G / 2; off >= 1; off >>= 1) den += __shfl_xor(den, off, G);
+      for (int off = G / 2; off >= 1; off >>= 1) den_all += __shfl_xor(den_all, off, G);
+    }
+    if (renorm) {
+      den = ex;
+#pragma unroll
+      for (int off = G / 2; off >= 1; off >>= 1) den += __shfl_xor(den, off, G);
+    } else {
+      den = den_all;
+    }
     if (live && holds_slot) {
       topk_idx[(long)t * k + sub] = my_e;
       topk_w[(long)t * k + sub] = ex / den;
+      if (score != nullptr) score[(long)t * k + sub] = ex / den_all;     // affinity: softmax over all experts
       atomicAdd(&hist[my_e], 1);     // integer count: the sum does not depend on the order
     }
   }
@@ -137,7 +143,8 @@ __global__ void __launch_bounds__(64) route_rank_kernel(const int32_t* __restric
                                                         const int32_t* __restrict__ chunk_base,
                                                         const int32_t* __restrict__ counts,
                                                         int32_t* __restrict__ offsets,
-                                                        int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm) {
+                                                        int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
+                                                        const uint8_t* __restrict__ keep) {
   __shared__ int next_row[MOE_MAX_EXPERTS];
   __shared__ int expert_off[MOE_MAX_EXPERTS + 1];
   const int lane = threadIdx.x;
@@ -171,13 +178,14 @@ __global__ void __launch_bounds__(64) route_rank_kernel(const int32_t* __restric
     const long a = base + lane;
     const bool valid = a < a_end;
     const int e = valid ? topk_idx[a] : 0;
-    unsigned long long same = __ballot(valid);
+    const bool gets_row = valid && e >= e_lo && e < e_hi && (keep == nullptr || keep[a] != 0);
+    unsigned long long same = __ballot(gets_row);
     for (int b = 0; b < ebits; ++b) {
       const unsigned long long mb = __ballot((e >> b) & 1);
       same &= ((e >> b) & 1) ? mb : ~mb;
     }
     if (valid) {
-      if (e >= e_lo && e < e_hi) {
+      if (gets_row) {
         const int start = next_row[e];
         const int r = start + __popcll(same & lt_mask);
         inv_perm[a] = r;
@@ -225,10 +233,95 @@ __global__ void __launch_bounds__(256) route_bwd_kernel(const float* __restrict_
   }
 }
 
+
+// ---- device-level token dropping (Section 3.2 "Load balance": capacity per device, the experts of one GPU form
+// a group, as in DeepSeek-V2: when a device gets more than `capacity` assignments the ones with the lowest
+// affinity are dropped) -------------------------------------------------------------------------------------
+// Order of an assignment inside its device: key = affinity bits (positive floats order like integers) in the
+// high word, ~assignment id in the low word, so larger key = kept first and equal affinities keep the lower id.
+// The capacity-th largest key of every device is found by a most-significant-digit radix select, 8 bits per
+// pass: one kernel counts the digit of every key that still matches the device's prefix (integer atomics: the
+// counts do not depend on the order), one small kernel picks the digit and narrows the prefix.
+struct SelectState {
+  unsigned long long prefix[MOE_MAX_EXPERTS];     // high bits of the threshold found so far, per device
+  int remaining[MOE_MAX_EXPERTS];                 // rank of the threshold among the keys that match the prefix
+  int all_kept[MOE_MAX_EXPERTS];                  // device has no more than `capacity` assignments
+  int hist[MOE_MAX_EXPERTS][256];
+};
+
+__device__ __forceinline__ unsigned long long drop_key(float score, long a) {
+  return ((unsigned long long)__float_as_uint(score) << 32) | (unsigned long long)(0xffffffffu - (unsigned)a);
+}
+
+__global__ void __launch_bounds__(256) select_init_kernel(SelectState* st, int n_groups, int capacity) {
+  for (int i = threadIdx.x; i < MOE_MAX_EXPERTS * 256; i += blockDim.x) (&st->hist[0][0])[i] = 0;
+  for (int g = threadIdx.x; g < n_groups; g += blockDim.x) {
+    st->prefix[g] = 0ull;
+    st->remaining[g] = capacity;
+    st->all_kept[g] = 0;
+  }
+}
+
+__global__ void __launch_bounds__(256) select_count_kernel(const int32_t* __restrict__ topk_idx,
+                                                           const float* __restrict__ score, long M, int per_group,
+                                                           int pass, SelectState* st) {
+  const int shift = 56 - 8 * pass;
+  for (long a = blockIdx.x * (long)blockDim.x + threadIdx.x; a < M; a += (long)gridDim.x * blockDim.x) {
+    const int g = topk_idx[a] / per_group;
+    if (st->all_kept[g]) continue;
+    const unsigned long long key = drop_key(score[a], a);
+    const bool match = pass == 0 || (key >> (shift + 8)) == st->prefix[g];
+    if (match) atomicAdd(&st->hist[g][(int)((key >> shift) & 0xffull)], 1);
+  }
+}
+
+__global__ void __launch_bounds__(256) select_pick_kernel(SelectState* st, int n_groups, int pass) {
+  for (int g = threadIdx.x; g < n_groups; g += blockDim.x) {
+    if (st->all_kept[g]) continue;
+    int total = 0;
+    for (int d = 0; d < 256; ++d) total += st->hist[g][d];
+    if (pass == 0 && total <= st->remaining[g]) {
+      st->all_kept[g] = 1;                         // threshold 0: every key passes
+      st->prefix[g] = 0ull;
+    } else {
+      int cum = 0, d = 255;
+      for (; d > 0; --d) {
+        if (cum + st->hist[g][d] >= st->remaining[g]) break;
+        cum += st->hist[g][d];
+      }
+      st->prefix[g] = (st->prefix[g] << 8) | (unsigned long long)d;
+      st->remaining[g] -= cum;
+    }
+    for (int d = 0; d < 256; ++d) st->hist[g][d] = 0;
+  }
+}
+
+// keep[a] and the per-chunk expert histogram of the kept assignments (same layout as route_topk_kernel's)
+__global__ void __launch_bounds__(256) keep_hist_kernel(const int32_t* __restrict__ topk_idx,
+                                                        const float* __restrict__ score, int T, int E, int k,
+                                                        int per_group, int chunk_tokens, int nchunks,
+                                                        const SelectState* __restrict__ st,
+                                                        uint8_t* __restrict__ keep, int32_t* __restrict__ chunk_hist) {
+  __shared__ int hist[MOE_MAX_EXPERTS];
+  for (int e = threadIdx.x; e < MOE_MAX_EXPERTS; e += blockDim.x) hist[e] = 0;
+  __syncthreads();
+  const long a_begin = (long)blockIdx.x * chunk_tokens * k;
+  const long a_end = min((long)(blockIdx.x + 1) * chunk_tokens, (long)T) * k;
+  for (long a = a_begin + threadIdx.x; a < a_end; a += blockDim.x) {
+    const int e = topk_idx[a];
+    const int g = e / per_group;
+    const bool kp = st->all_kept[g] || drop_key(score[a], a) >= st->prefix[g];
+    keep[a] = kp ? 1 : 0;
+    if (kp) atomicAdd(&hist[e], 1);
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += blockDim.x) chunk_hist[(long)e * nchunks + blockIdx.x] = hist[e];
+}
+
 template <int G, int VPL>
 int launch_topk(const float* logits, int T, int E, int k, int renorm, int chunk_tokens, int nchunks, int32_t* idx,
-                float* w, int32_t* hist, hipStream_t s) {
-  route_topk_kernel<G, VPL><<<nchunks, 256, 0, s>>>(logits, T, E, k, renorm, chunk_tokens, nchunks, idx, w, hist);
+                float* w, int32_t* hist, float* score, hipStream_t s) {
+  route_topk_kernel<G, VPL><<<nchunks, 256, 0, s>>>(logits, T, E, k, renorm, chunk_tokens, nchunks, idx, w, hist, score);
   MOE_LAUNCH_CHECK();
   return MOE_OK;
 }
@@ -240,26 +333,54 @@ size_t route_ws_bytes(int T, int E) {
   return align_up((size_t)cdiv(T, tb) * E * sizeof(int32_t), 256);
 }
 
-int launch_route(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi, int32_t* idx, float* w,
-                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* ws, hipStream_t s) {
+size_t route_capacity_ws_bytes(int T, int E, int k) {
+  return route_ws_bytes(T, E) + align_up(sizeof(SelectState), 256) + align_up((size_t)T * k, 256);
+}
+
+// n_groups = 0: no dropping.  Otherwise `score` [T,k] must be given and ws holds route_capacity_ws_bytes.
+int launch_route(const float* logits, int T, int E, int k, int renorm, int e_lo, int e_hi, int n_groups, int capacity,
+                 int32_t* idx, float* w, float* score, int32_t* counts, int32_t* offsets, int32_t* perm,
+                 int32_t* inv_perm, void* ws, hipStream_t s) {
   const int tb = route_chunk_tokens(T);
   const int nchunks = cdiv(T, tb);
   int32_t* hist = static_cast<int32_t*>(ws);
   int rc;
   // lanes per token G = min(16, pow2 >= E) (so G >= k: one slot per lane); experts beyond 16 go VPL per lane
-  if (E <= 1) rc = launch_topk<1, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 2) rc = launch_topk<2, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 4) rc = launch_topk<4, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 8) rc = launch_topk<8, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 16) rc = launch_topk<16, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 32) rc = launch_topk<16, 2>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 64) rc = launch_topk<16, 4>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else if (E <= 128) rc = launch_topk<16, 8>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
-  else rc = launch_topk<16, 16>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, s);
+  if (E <= 1) rc = launch_topk<1, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else if (E <= 2) rc = launch_topk<2, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else if (E <= 4) rc = launch_topk<4, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else if (E <= 8) rc = launch_topk<8, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else if (E <= 16) rc = launch_topk<16, 1>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else if (E <= 32) rc = launch_topk<16, 2>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else if (E <= 64) rc = launch_topk<16, 4>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else if (E <= 128) rc = launch_topk<16, 8>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
+  else rc = launch_topk<16, 16>(logits, T, E, k, renorm, tb, nchunks, idx, w, hist, score, s);
   if (rc != MOE_OK) return rc;
+  const uint8_t* keep = nullptr;
+  if (n_groups > 0) {
+    char* base = static_cast<char*>(ws) + route_ws_bytes(T, E);
+    SelectState* st = reinterpret_cast<SelectState*>(base);
+    uint8_t* keep_w = reinterpret_cast<uint8_t*>(base + align_up(sizeof(SelectState), 256));
+    const long M = (long)T * k;
+    const int per_group = E / n_groups;
+    long blocks = (M + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    select_init_kernel<<<1, 256, 0, s>>>(st, n_groups, capacity);
+    MOE_LAUNCH_CHECK();
+    for (int pass = 0; pass < 8; ++pass) {
+      select_count_kernel<<<(int)blocks, 256, 0, s>>>(idx, score, M, per_group, pass, st);
+      MOE_LAUNCH_CHECK();
+      select_pick_kernel<<<1, 256, 0, s>>>(st, n_groups, pass);
+      MOE_LAUNCH_CHECK();
+    }
+    keep_hist_kernel<<<nchunks, 256, 0, s>>>(idx, score, T, E, k, per_group, tb, nchunks, st, keep_w, hist);
+    MOE_LAUNCH_CHECK();
+    keep = keep_w;
+  }
   route_scan_kernel<<<E, 64, 0, s>>>(hist, nchunks, counts);
   MOE_LAUNCH_CHECK();
-  route_rank_kernel<<<nchunks, 64, 0, s>>>(idx, T, E, k, e_lo, e_hi, tb, nchunks, hist, counts, offsets, perm, inv_perm);
+  route_rank_kernel<<<nchunks, 64, 0, s>>>(idx, T, E, k, e_lo, e_hi, tb, nchunks, hist, counts, offsets, perm, inv_perm,
+                                           keep);
   MOE_LAUNCH_CHECK();
   return MOE_OK;
 }

@@ -13,13 +13,18 @@ from . import binding as B
 
 class MoELayer:
     def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype=torch.bfloat16, renorm: int = 1,
-                 fp8: bool = False, grad_dtype=torch.float32, device="cuda:0", expert_range=None):
+                 fp8: bool = False, grad_dtype=torch.float32, device="cuda:0", expert_range=None, capacity=None,
+                 balance=None):
         """expert_range = (e_lo, e_hi): this GPU's expert-parallel share (Section 3.2): x holds the all-gathered
         tokens, only rows routed to experts e_lo..e_hi-1 are dispatched, w1/w2 and their gradients hold those
         experts only, and y / dx are the partial sums over them.  Row buffers keep the bound T*k."""
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
         self.M = T * k
         self.expert_range = expert_range
+        # load balance (Section 3.2): capacity = (devices, rows per device) drops the lowest-affinity assignments of
+        # an overloaded device; balance = (devices, alpha) adds the device-level auxiliary loss and its gradient
+        self.capacity, self.balance = capacity, balance
+        assert not (capacity is not None and (fp8 or expert_range is not None))
         self.E_local = E if expert_range is None else expert_range[1] - expert_range[0]
         assert not (fp8 and expert_range is not None), "the fp8 path needs offsets[E] = M"
         self.dtype, self.renorm, self.fp8, self.device = dtype, renorm, fp8, device
@@ -64,6 +69,13 @@ class MoELayer:
         else:
             self.xp = torch.empty((M, d), **act)
             self.yp = torch.empty((M, d), **act)
+        if capacity is not None:
+            self.score = torch.empty((T, k), **f32)
+            self.route_ws = torch.empty((B.moe_route_capacity_workspace_bytes(T, E, k),), dtype=torch.uint8, **dev)
+        if balance is not None:
+            self.aux_loss = torch.zeros((1,), **f32)
+            self.group_f = torch.empty((balance[0],), **f32)
+            self.group_p = torch.empty((balance[0],), **f32)
         self.timers = None      # set to a dict to collect (start, end) event pairs per call name
         code = B.F8E4M3 if fp8 else B.dtype_code(dtype)
         nbytes = B.moe_workspace_bytes(T, d, E, k, f, code)
@@ -197,7 +209,18 @@ class MoELayer:
             c("router_fwd", B.moe_router_fwd, x, w_r, bias, self.logits)
         else:
             self.logits.copy_(logits)
-        if self.expert_range is None:
+        if self.balance is not None:
+            # the loss counts every assignment, dropped or not: take the counts of the plain row map first
+            c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
+              self.offsets, self.perm, self.inv_perm, self.workspace)
+            c("balance_loss", B.moe_balance_loss, self.logits, self.counts, self.k, self.balance[0], self.balance[1],
+              self.aux_loss, self.group_f, self.group_p, self.workspace)
+        if self.capacity is not None:
+            c("route", B.moe_route_capacity, self.logits, self.k, self.renorm, self.capacity[0], self.capacity[1],
+              self.topk_idx, self.topk_w, self.score, self.counts, self.offsets, self.perm, self.inv_perm, self.route_ws)
+        elif self.balance is not None:
+            pass
+        elif self.expert_range is None:
             c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
               self.offsets, self.perm, self.inv_perm, self.workspace)
         else:
@@ -220,6 +243,9 @@ class MoELayer:
         c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, None, self.k, self.dx)
         c("route_bwd", B.moe_route_bwd, self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E,
           self.renorm, self.d_logits)
+        if self.balance is not None:
+            c("balance_loss_bwd", B.moe_balance_loss_bwd, self.logits, self.group_f, self.balance[0], self.balance[1],
+              self.d_logits)
         if with_router:
             c("router_bwd", B.moe_router_bwd, x, w_r, self.d_logits, self.d_w_r, self.dx, self.workspace)
         return self.dx

@@ -118,3 +118,30 @@ def test_fp8_backward_argument_errors_without_gpu(lib):
     assert lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), null) == -1
     a.dh_t = 4100                                     # misaligned
     assert lib.moe_expert_ffn_bwd_fp8(ctypes.byref(a), null) == -2
+
+
+def test_route_range_capacity_balance_argument_errors_without_gpu(lib):
+    P, Z, F = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+    null, fake = P(0), P(4096)
+    big = Z(1 << 24)
+    # expert range outside [0, E] or reversed
+    assert lib.moe_route_range(fake, 4, 8, 2, 1, 3, 9, fake, fake, fake, fake, fake, fake, fake, big, null) == -1
+    assert lib.moe_route_range(fake, 4, 8, 2, 1, 5, 4, fake, fake, fake, fake, fake, fake, fake, big, null) == -1
+    assert lib.moe_route_range(fake, 4, 8, 2, 1, 2, 6, fake, fake, fake, fake, fake, fake, null, Z(0), null) == -3
+    # devices must divide the experts; capacity >= 0; score is required; workspace size
+    lib.moe_route_capacity_workspace_bytes.restype = Z
+    need = lib.moe_route_capacity_workspace_bytes(64, 8, 2)
+    assert need > 64 * 2 and lib.moe_route_capacity_workspace_bytes(64, 8, 9) == 0
+    args = lambda g, cap, score, ws, n: (fake, 64, 8, 2, 1, g, cap, fake, fake, score, fake, fake, fake, fake, ws, Z(n), null)
+    assert lib.moe_route_capacity(*args(3, 10, fake, fake, need)) == -1
+    assert lib.moe_route_capacity(*args(4, -1, fake, fake, need)) == -1
+    assert lib.moe_route_capacity(*args(4, 10, null, fake, need)) == -1
+    assert lib.moe_route_capacity(*args(4, 10, fake, fake, need - 1)) == -3
+    lib.moe_balance_loss.argtypes = [P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, F, P, P, P, P, Z, P]
+    assert lib.moe_balance_loss(fake, fake, 64, 8, 2, 3, F(0.1), fake, fake, fake, fake, big, null) == -1
+    assert lib.moe_balance_loss(fake, fake, 64, 8, 2, 4, F(0.1), null, fake, fake, fake, big, null) == -1
+    assert lib.moe_balance_loss(fake, fake, 64, 8, 2, 4, F(0.1), fake, fake, fake, null, Z(0), null) == -3
+    lib.moe_balance_loss_bwd.argtypes = [P, P, ctypes.c_int, ctypes.c_int, ctypes.c_int, F, P, P]
+    assert lib.moe_balance_loss_bwd(fake, fake, 64, 8, 5, F(0.1), fake, null) == -1
+    assert lib.moe_balance_loss_bwd(fake, null, 64, 8, 4, F(0.1), fake, null) == -1
+    assert lib.moe_balance_loss_bwd(null, null, 0, 8, 4, F(0.1), null, null) == 0

@@ -567,3 +567,102 @@ def test_layer_expert_parallel_share(B, dtype):
         assert not bad, ((lo, hi), bad)
         y_sum += to_np(layer.y)
     assert max_norm_err(y_sum, full["y"]) < 2 * tol
+
+
+# ---- load balance: device-level capacity with token dropping, and the auxiliary balance loss ----------------------
+@pytest.mark.parametrize("T,E,k,G,cap,skew", [(300, 8, 2, 4, 100, 2.0), (1000, 32, 3, 8, 300, 1.0), (513, 64, 8, 8, 400, 0.0),
+                                             (257, 6, 2, 3, 10 ** 6, 1.0), (64, 4, 2, 1, 0, 0.0), (4000, 16, 4, 16, 900, 1.5)])
+def test_route_capacity(B, T, E, k, G, cap, skew):
+    """The drop decision depends on fp32 affinities, so both sides take it from the same numbers: the kernel's
+    scores are compared with the oracle's by tolerance, then the oracle decides on the kernel's scores and the
+    whole row map must agree bit for bit."""
+    z = random_logits(T, E, seed=T + E + k, quantum=0.25 if T % 2 else None)
+    z[:, 0] += skew
+    M = T * k
+    i32 = dict(dtype=torch.int32, device=DEV)
+    out = dict(idx=torch.full((T, k), -7, **i32), w=torch.full((T, k), -7.0, device=DEV), score=torch.full((T, k), -7.0, device=DEV),
+               counts=torch.full((E,), -7, **i32), offsets=torch.full((E + 1,), -7, **i32),
+               perm=torch.full((M,), -7, **i32), inv_perm=torch.full((M,), -7, **i32))
+    ws = torch.empty(B.moe_route_capacity_workspace_bytes(T, E, k), dtype=torch.uint8, device=DEV)
+    B.moe_route_capacity(to_dev(z), k, 1, G, cap, out["idx"], out["w"], out["score"], out["counts"], out["offsets"],
+                         out["perm"], out["inv_perm"], ws)
+    torch.cuda.synchronize()
+    idx = to_np(out["idx"])
+    assert np.array_equal(idx, O.topk_select(z, k))
+    score = to_np(out["score"]).astype(np.float32)
+    assert np.allclose(score, O.affinity_scores(z, idx), rtol=3e-6, atol=1e-12)
+    ref = O.route_capacity(z, k, G, cap, score=score)
+    for name in ("counts", "offsets", "inv_perm"):
+        assert np.array_equal(to_np(out[name]), ref[name]), name
+    n = int(ref["offsets"][-1])
+    assert np.array_equal(to_np(out["perm"])[:n], ref["perm"])
+    assert np.allclose(to_np(out["w"]), ref["w"], rtol=2e-6, atol=1e-7)
+    per_dev = ref["counts"].reshape(G, E // G).sum(axis=1)
+    assert per_dev.max() <= cap
+    print(f"T={T} E={E} k={k} devices={G} capacity={cap}: kept {n} of {M}, per device {per_dev.tolist()[:8]}")
+
+
+@pytest.mark.parametrize("T,E,k,G", [(300, 8, 2, 4), (1000, 64, 6, 8), (257, 256, 8, 32), (64, 5, 2, 5), (2048, 32, 3, 8)])
+def test_balance_loss_and_gradient(B, T, E, k, G):
+    z = random_logits(T, E, seed=T + E)
+    z[:, :2] += 1.0
+    alpha = 0.01
+    r = O.route(z, k)
+    zt = to_dev(z)
+    counts = to_dev(r["counts"].astype(np.int32))
+    loss = torch.full((1,), -1.0, device=DEV)
+    gf, gp = torch.full((G,), -1.0, device=DEV), torch.full((G,), -1.0, device=DEV)
+    ws = torch.empty(max(B.moe_workspace_bytes(T, 16, E, k, 16, B.F32), 256), dtype=torch.uint8, device=DEV)
+    B.moe_balance_loss(zt, counts, k, G, alpha, loss, gf, gp, ws)
+    dz = torch.zeros((T, E), device=DEV)
+    B.moe_balance_loss_bwd(zt, gf, G, alpha, dz)
+    dz2 = dz.clone()
+    B.moe_balance_loss_bwd(zt, gf, G, alpha, dz2)                 # the call adds into d_logits
+    torch.cuda.synchronize()
+    l_ref, f_ref, p_ref = O.balance_loss(z, r["idx"], G, alpha)
+    assert np.allclose(to_np(gf), f_ref, rtol=1e-6) and np.allclose(to_np(gp), p_ref, rtol=1e-5)
+    assert abs(float(loss[0]) - l_ref) <= 1e-5 * abs(l_ref)
+    g_ref = O.balance_loss_bwd(z, r["idx"], G, alpha)
+    assert max_norm_err(to_np(dz), g_ref) < 1e-4
+    assert torch.equal(dz2, dz + dz)
+    loss2 = torch.empty_like(loss)
+    B.moe_balance_loss(zt, counts, k, G, alpha, loss2, gf, gp, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(loss, loss2)                               # fixed summation order: bit-reproducible
+
+
+def test_layer_with_capacity_and_balance_loss(B):
+    """Whole layer with device-level dropping and the auxiliary loss: the oracle decides the drops on the kernel's
+    affinities, then every tensor is compared; d_logits carries the gate gradient plus the balance-loss gradient."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = MoEConfig("cap", T=600, d=128, E=8, k=2, f=160, dtype="bf16", w_std=0.09, wr_std=0.6)
+    inp = make_inputs(cfg, seed=8)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    z[:, 0] += 1.0
+    G, cap, alpha = 4, 260, 0.02
+    td = torch.bfloat16
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, capacity=(G, cap), balance=(G, alpha))
+    x, dy, wr = to_dev(inp["x"], td), to_dev(inp["dy"], td), to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"], td), to_dev(inp["W2"], td)
+    for t in (layer.xp, layer.yp, layer.d_yp, layer.d_xp, layer.h_save):
+        t.fill_(float("nan"))
+    layer.forward(x, wr, None, w1, w2, logits=to_dev(z))
+    layer.backward(x, wr, w1, w2, dy, with_router=False)
+    torch.cuda.synchronize()
+    r = O.route_capacity(z, cfg.k, G, cap, score=to_np(layer.score).astype(np.float32))
+    assert 0 < (~r["keep"]).sum() < cfg.T * cfg.k
+    assert np.array_equal(to_np(layer.inv_perm), r["inv_perm"]) and np.array_equal(to_np(layer.offsets), r["offsets"])
+    fwd = O.layer_fwd_routed(inp["x"], r, inp["W1"], inp["W2"], cfg.k)
+    bwd = O.layer_bwd_routed(inp["x"], inp["W1"], inp["W2"], cfg.k, inp["dy"], fwd)
+    n = int(r["offsets"][-1])
+    tol = TOL["bf16"]
+    full = O.route(z, cfg.k)
+    l_ref, _, _ = O.balance_loss(z, full["idx"], G, alpha)
+    assert abs(float(layer.aux_loss[0]) - l_ref) <= 1e-5 * abs(l_ref)
+    dz_ref = O.route_bwd(z, r["idx"], r["w"], bwd["dw"]) + O.balance_loss_bwd(z, full["idx"], G, alpha)
+    errs = {"H": max_norm_err(to_np(layer.h_save)[:n], fwd["H"]), "y": max_norm_err(to_np(layer.y), fwd["y"]),
+            "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]), "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
+            "dz": max_norm_err(to_np(layer.d_logits), dz_ref),
+            "dW1": max_norm_err(to_np(layer.d_w1), bwd["dW1"]), "dW2": max_norm_err(to_np(layer.d_w2), bwd["dW2"])}
+    bad = {k_: v for k_, v in errs.items() if not v < tol}
+    assert not bad, bad

@@ -274,9 +274,9 @@ def test_capacity_keep_drops_the_lowest_affinities_per_device():
     z = rng.standard_normal((T, E)).astype(np.float32)
     z[:, 0] += 1.5                                          # device 0 is overloaded
     idx = O.topk_select(z, k)
-    keep = O.capacity_keep(z, idx, G, cap)
-    s = O.softmax_all(z).astype(np.float32)
-    score = np.take_along_axis(s, idx.astype(np.int64), axis=1)
+    score = O.affinity_scores(z, idx)
+    assert np.allclose(score, np.take_along_axis(scipy_softmax(z.astype(np.float64), axis=1), idx.astype(np.int64), axis=1), rtol=1e-6)
+    keep = O.capacity_keep(score, idx, E, G, cap)
     grp = idx // (E // G)
     for g in range(G):
         m = grp == g
@@ -285,9 +285,10 @@ def test_capacity_keep_drops_the_lowest_affinities_per_device():
             assert score[m & keep].min() >= score[m & ~keep].max()
     # brute force on a tiny case with ties: equal affinities -> the lower assignment id stays
     z2 = np.zeros((4, 2), dtype=np.float32)
-    keep2 = O.capacity_keep(z2, O.topk_select(z2, 1), 1, 2)
+    i2 = O.topk_select(z2, 1)
+    keep2 = O.capacity_keep(O.affinity_scores(z2, i2), i2, 2, 1, 2)
     assert keep2.reshape(-1).tolist() == [True, True, False, False]
-    assert O.capacity_keep(z, idx, G, T * k).all()          # capacity never reached: nothing dropped
+    assert O.capacity_keep(score, idx, E, G, T * k).all()   # capacity never reached: nothing dropped
 
 
 def test_route_capacity_row_map():
