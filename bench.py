@@ -10,6 +10,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -36,6 +37,10 @@ def parse():
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = T/8)")
     ap.add_argument("--fp8-backward", action="store_true",
                     help="fp8 configurations only: run the four backward GEMMs on e4m3 operands as well")
+    ap.add_argument("--capacity-factor", type=float, default=0.0,
+                    help="bf16 configurations: device-level token dropping with capacity = factor * T*k / devices (0 = dropless)")
+    ap.add_argument("--balance-alpha", type=float, default=0.0, help="add the device-level auxiliary balance loss (0 = off)")
+    ap.add_argument("--devices", type=int, default=8, help="expert groups (GPUs of the node) for the two switches above")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size reference for HBM byte counters")
     return ap.parse_args()
@@ -120,8 +125,11 @@ def main():
     w_r = to_dev_bf16(np.ascontiguousarray(inp["W_r"].T), torch)
     bias = torch.from_numpy(inp["bias"]).to("cuda:0") if cfg.bias != "none" else None
     w1, w2 = to_dev_bf16(inp["W1"], torch), to_dev_bf16(inp["W2"], torch)
+    devices = min(args.devices, cfg.E)
+    capacity = (devices, int(math.ceil(args.capacity_factor * cfg.T * cfg.k / devices))) if args.capacity_factor > 0 else None
+    balance = (devices, args.balance_alpha) if args.balance_alpha > 0 else None
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=fp8,
-                     expert_range=cfg.expert_range)
+                     expert_range=cfg.expert_range, capacity=capacity, balance=balance)
     if fp8:
         layer.set_fp8_weights(w1, w2)       # parameters are kept in E4M3 across steps (Section 7): outside the timed loop
         if args.fp8_backward:
@@ -168,6 +176,8 @@ def main():
     counts = layer.counts.cpu().tolist()
     # dispatched rows: all T*k, or the rows of the local experts for an expert-parallel share
     M = cfg.M if cfg.expert_range is None else int(sum(counts[e] for e in cfg.local_experts))
+    if capacity is not None:
+        M = int(sum(counts))                                   # rows kept after dropping
     gemm_flops = 18.0 * M * cfg.d * cfg.f                      # three matmuls per routed token, fwd + 2x bwd
     # bf16 path: these two calls are exactly the six GEMM launches (fp8 path: plus the two row casts in the forward)
     gemm_ms = per_call["expert_ffn_fwd"] + per_call["expert_ffn_bwd"]
@@ -189,7 +199,9 @@ def main():
                                  "e4m3 dispatched activations / expert GEMMs / returned outputs forward, bf16 backward, ")
                                 if fp8 else "bf16 weights/activations, ") + "fp32 accumulate, fp32 weight gradients" +
                                (f"; expert-parallel share: experts {cfg.expert_range[0]}..{cfg.expert_range[1] - 1} local, "
-                                f"{M} of {cfg.M} dispatched rows, tokens = the all-gathered tokens" if cfg.expert_range else ""),
+                                f"{M} of {cfg.M} dispatched rows, tokens = the all-gathered tokens" if cfg.expert_range else "") +
+                               (f"; capacity {capacity[1]} rows per device over {capacity[0]} devices, {M} of {cfg.M} rows kept"
+                                if capacity else "") + (f"; balance loss alpha={args.balance_alpha}" if balance else ""),
                    "tokens": cfg.T, "expert_rows": counts},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",

@@ -262,37 +262,77 @@ __global__ void __launch_bounds__(256) select_init_kernel(SelectState* st, int n
   }
 }
 
+// LDS_GROUPS > 0: the block counts into LDS first (up to 16 devices) and adds its totals once; otherwise straight
+// into the global histogram.
+template <int LDS_GROUPS>
 __global__ void __launch_bounds__(256) select_count_kernel(const int32_t* __restrict__ topk_idx,
                                                            const float* __restrict__ score, long M, int per_group,
-                                                           int pass, SelectState* st) {
+                                                           int n_groups, int pass, SelectState* st) {
+  __shared__ int h[LDS_GROUPS > 0 ? LDS_GROUPS : 1][256];
+  if constexpr (LDS_GROUPS > 0) {
+    for (int i = threadIdx.x; i < LDS_GROUPS * 256; i += blockDim.x) (&h[0][0])[i] = 0;
+    __syncthreads();
+  }
   const int shift = 56 - 8 * pass;
   for (long a = blockIdx.x * (long)blockDim.x + threadIdx.x; a < M; a += (long)gridDim.x * blockDim.x) {
     const int g = topk_idx[a] / per_group;
     if (st->all_kept[g]) continue;
     const unsigned long long key = drop_key(score[a], a);
     const bool match = pass == 0 || (key >> (shift + 8)) == st->prefix[g];
-    if (match) atomicAdd(&st->hist[g][(int)((key >> shift) & 0xffull)], 1);
+    if (match) {
+      const int digit = (int)((key >> shift) & 0xffull);
+      if constexpr (LDS_GROUPS > 0) atomicAdd(&h[g][digit], 1);
+      else atomicAdd(&st->hist[g][digit], 1);
+    }
+  }
+  if constexpr (LDS_GROUPS > 0) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < n_groups * 256; i += blockDim.x) {
+      const int v = (&h[0][0])[i];
+      if (v) atomicAdd(&st->hist[i / 256][i % 256], v);
+    }
   }
 }
 
+// One wave per device: lane l holds the counts of digits 4l .. 4l+3; the digit that contains the threshold is the
+// highest d with (keys in digits above d) + hist[d] >= remaining.
 __global__ void __launch_bounds__(256) select_pick_kernel(SelectState* st, int n_groups, int pass) {
-  for (int g = threadIdx.x; g < n_groups; g += blockDim.x) {
-    if (st->all_kept[g]) continue;
-    int total = 0;
-    for (int d = 0; d < 256; ++d) total += st->hist[g][d];
-    if (pass == 0 && total <= st->remaining[g]) {
-      st->all_kept[g] = 1;                         // threshold 0: every key passes
-      st->prefix[g] = 0ull;
-    } else {
-      int cum = 0, d = 255;
-      for (; d > 0; --d) {
-        if (cum + st->hist[g][d] >= st->remaining[g]) break;
-        cum += st->hist[g][d];
-      }
-      st->prefix[g] = (st->prefix[g] << 8) | (unsigned long long)d;
-      st->remaining[g] -= cum;
-    }
-    for (int d = 0; d < 256; ++d) st->hist[g][d] = 0;
+  const int lane = threadIdx.x % 64;
+  const int g = blockIdx.x * 4 + threadIdx.x / 64;
+  if (g >= n_groups || st->all_kept[g]) return;            // wave-uniform
+  int c[4];
+  int mine = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    c[i] = st->hist[g][4 * lane + i];
+    st->hist[g][4 * lane + i] = 0;
+    mine += c[i];
+  }
+  int incl = mine;                                          // inclusive suffix sum over lanes (lane 63 first)
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_down(incl, off);
+    if (lane + off < 64) incl += o;
+  }
+  const int total = __shfl(incl, 0);
+  const int remaining = st->remaining[g];
+  if (pass == 0 && total <= remaining) {
+    if (lane == 0) { st->all_kept[g] = 1; st->prefix[g] = 0ull; }   // threshold 0: every key passes
+    return;
+  }
+  int cum = incl - mine;                                    // keys in digits above this lane's four
+  int hit = -1, cum_at_hit = 0;
+#pragma unroll
+  for (int i = 3; i >= 0; --i) {
+    if (hit < 0 && cum + c[i] >= remaining) { hit = 4 * lane + i; cum_at_hit = cum; }
+    cum += c[i];
+  }
+  const unsigned long long hits = __ballot(hit >= 0);
+  // remaining <= total here, so some lane hits; remaining = 0 (capacity 0) hits in lane 63 at digit 255
+  const int winner = 63 - __builtin_clzll(hits);
+  if (lane == winner) {
+    st->prefix[g] = (st->prefix[g] << 8) | (unsigned long long)hit;
+    st->remaining[g] = remaining - cum_at_hit;
   }
 }
 
@@ -363,14 +403,15 @@ int launch_route(const float* logits, int T, int E, int k, int renorm, int e_lo,
     uint8_t* keep_w = reinterpret_cast<uint8_t*>(base + align_up(sizeof(SelectState), 256));
     const long M = (long)T * k;
     const int per_group = E / n_groups;
-    long blocks = (M + 255) / 256;
-    if (blocks > 1024) blocks = 1024;
+    long blocks = (M + 1023) / 1024;
+    if (blocks > 512) blocks = 512;
     select_init_kernel<<<1, 256, 0, s>>>(st, n_groups, capacity);
     MOE_LAUNCH_CHECK();
     for (int pass = 0; pass < 8; ++pass) {
-      select_count_kernel<<<(int)blocks, 256, 0, s>>>(idx, score, M, per_group, pass, st);
+      if (n_groups <= 16) select_count_kernel<16><<<(int)blocks, 256, 0, s>>>(idx, score, M, per_group, n_groups, pass, st);
+      else select_count_kernel<0><<<(int)blocks, 256, 0, s>>>(idx, score, M, per_group, n_groups, pass, st);
       MOE_LAUNCH_CHECK();
-      select_pick_kernel<<<1, 256, 0, s>>>(st, n_groups, pass);
+      select_pick_kernel<<<cdiv(n_groups, 4), 256, 0, s>>>(st, n_groups, pass);
       MOE_LAUNCH_CHECK();
     }
     keep_hist_kernel<<<nchunks, 256, 0, s>>>(idx, score, T, E, k, per_group, tb, nchunks, st, keep_w, hist);
