@@ -261,7 +261,11 @@ typedef struct moe_ffn_bwd_fp8_args {
   uint8_t* dh_t; uint8_t* dh_e8m0;        /* [2f,ldt], [ldt/128,2f] */
   uint8_t* a_t;  uint8_t* a_e8m0;         /* [f,ldt],  [ldt/128,f]  */
   uint8_t* x_t;  uint8_t* x_e8m0;         /* [d,ldt],  [ldt/128,d]  */
+  void* splitk_ws;                        /* MOE_SPLITK_WS_BYTES of scratch, or NULL: lets the d_xp GEMM split the
+                                             tiles of a partly filled last round along K (faster, same result up
+                                             to fp32 summation order) */
 } moe_ffn_bwd_fp8_args;
+#define MOE_SPLITK_WS_BYTES ((size_t)256 * 256 * 256 * 4)
 int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* args, void* stream);
 
 /* Backward-orientation cast for the weight-gradient GEMMs (Section 7: per-channel quantisation

@@ -38,8 +38,11 @@ class FfnBwdFp8Args(ctypes.Structure):
         + [("grad_dt", c_int), ("accumulate", c_int)]
         + [(n, c_void_p) for n in ("dy_codes", "dy_scale", "dh", "dh_codes", "dh_scale", "pad_offsets")]
         + [("ldt", ctypes.c_long)]
-        + [(n, c_void_p) for n in ("dy_t", "dy_e8m0", "dh_t", "dh_e8m0", "a_t", "a_e8m0", "x_t", "x_e8m0")]
+        + [(n, c_void_p) for n in ("dy_t", "dy_e8m0", "dh_t", "dh_e8m0", "a_t", "a_e8m0", "x_t", "x_e8m0", "splitk_ws")]
     )
+
+
+SPLITK_WS_BYTES = 256 * 256 * 256 * 4
 
 
 class MoEError(RuntimeError):
@@ -230,6 +233,7 @@ def moe_expert_ffn_bwd_fp8(d_yp, h_save, xp_deq, a_deq, offsets, w1t, w1t_scale,
     for name in ("dy_codes", "dy_scale", "dh", "dh_codes", "dh_scale", "pad_offsets", "dy_t", "dy_e8m0", "dh_t",
                  "dh_e8m0", "a_t", "a_e8m0", "x_t", "x_e8m0"):
         setattr(a, name, _p(inter[name]))
+    a.splitk_ws = _p(inter.get("splitk_ws"))
     a.M, a.d, a.E, a.f = M, d, offsets.numel() - 1, f
     a.grad_dt = dtype_code(d_w1.dtype)
     a.accumulate = int(accumulate)

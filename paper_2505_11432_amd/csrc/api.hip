@@ -16,16 +16,17 @@ size_t ffn_fwd_ws_bytes(int M, int d, int f, moe_dtype act, moe_dtype out) {
   if (act == MOE_F8E4M3) {
     // A in bf16, A codes, A scales, Y in bf16 (only when yp is written as codes)
     size_t b = align_up(m * f * 2, 256) + align_up(m * f, 256) + align_up(m * 4, 256);
-    if (out == MOE_F8E4M3) b += align_up(m * d * 2, 256);
-    return b;
+    b += align_up(m * d * 2, 256);          // Y in bf16 (used only when yp is written as codes)
+    (void)out;
+    return b + MOE_SPLITK_WS_BYTES;
   }
-  return align_up(m * f * dtype_size(act), 256);
+  return align_up(m * f * dtype_size(act), 256) + (act == MOE_BF16 ? MOE_SPLITK_WS_BYTES : 0);
 }
 
 size_t ffn_bwd_ws_bytes(int M, int d, int f, moe_dtype dt) {
   (void)d;
   const size_t m = (size_t)M, es = dtype_size(dt);
-  return align_up(m * f * es, 256) * 2 + align_up(m * 2 * f * es, 256);
+  return align_up(m * f * es, 256) * 2 + align_up(m * 2 * f * es, 256) + (dt == MOE_BF16 ? MOE_SPLITK_WS_BYTES : 0);
 }
 
 static bool sizes_ok(int T, int d, int E, int k, int f) {
@@ -59,7 +60,8 @@ static int ffn_fwd_bf16(const void* xp, const int32_t* offsets, const void* w1, 
   void* A = ws;
   int rc = mfma_fc1_swiglu(xp, w1, offsets, M, d, E, f, h_save, A, s);
   if (rc != MOE_OK) return rc;
-  return mfma_rowseg_nt(A, w2, (long)d * f, offsets, M, d, f, E, yp, s);
+  void* splitk = static_cast<char*>(ws) + align_up((size_t)M * f * 2, 256);
+  return mfma_rowseg_nt(A, w2, (long)d * f, offsets, M, d, f, E, yp, splitk, s);
 }
 
 // fp8 (Section 5 / Section 7 "FP8 training"): e4m3 operands with per-token and per-output-channel scales on
@@ -79,7 +81,8 @@ static int ffn_fwd_fp8(const void* xp, const float* xp_scale, const int32_t* off
   rc = launch_quant_fp8(A_bf16, MOE_BF16, M, f, MOE_Q_ROW, a_codes, a_scale, s);
   if (rc != MOE_OK) return rc;
   void* y_dst = out_dt == MOE_F8E4M3 ? y_bf16 : yp;
-  rc = mfma_rowseg_nt_fp8(a_codes, a_scale, w2, w2_scale, (long)d * f, offsets, M, d, f, E, y_dst, s);
+  void* splitk = static_cast<char*>(y_bf16) + align_up((size_t)M * d * 2, 256);
+  rc = mfma_rowseg_nt_fp8(a_codes, a_scale, w2, w2_scale, (long)d * f, offsets, M, d, f, E, y_dst, splitk, s);
   if (rc != MOE_OK) return rc;
   if (out_dt == MOE_F8E4M3) rc = launch_quant_fp8(y_bf16, MOE_BF16, M, d, MOE_Q_ROW, static_cast<uint8_t*>(yp), yp_scale, s);
   return rc;
@@ -96,7 +99,8 @@ static int ffn_bwd_bf16(const void* xp, const void* h_save, const void* d_yp, co
   if (rc != MOE_OK) return rc;
   rc = mfma_wgrad(d_yp, a_override ? a_override : A, offsets, d, f, E, d_w2, grad_dt, accumulate, s);
   if (rc != MOE_OK) return rc;
-  rc = mfma_rowseg_nn(dH, w1, 2L * f * d, offsets, M, d, 2 * f, E, d_xp, s);
+  void* splitk = base + 2 * align_up((size_t)M * f * 2, 256) + align_up((size_t)M * 2 * f * 2, 256);
+  rc = mfma_rowseg_nn(dH, w1, 2L * f * d, offsets, M, d, 2 * f, E, d_xp, splitk, s);
   if (rc != MOE_OK) return rc;
   return mfma_wgrad(dH, xp, offsets, 2 * f, d, E, d_w1, grad_dt, accumulate, s);
 }
@@ -438,7 +442,7 @@ int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* a, void* stream) {
   for (const void* q : ptrs)
     if (!q) return MOE_ERR_INVALID;
   const void* vec[] = {a->d_yp, a->h_save, a->xp_deq, a->a_deq, a->w1t, a->w2t, a->d_xp, a->d_w1, a->d_w2, a->dy_codes,
-                       a->dh, a->dh_codes, a->dy_t, a->dh_t, a->a_t, a->x_t};
+                       a->dh, a->dh_codes, a->dy_t, a->dh_t, a->a_t, a->x_t, a->splitk_ws};
   for (const void* q : vec)
     if (!aligned16(q)) return MOE_ERR_UNSUPPORTED;
   hipStream_t s = as_stream(stream);
@@ -451,7 +455,7 @@ int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* a, void* stream) {
   rc = launch_quant_fp8(a->dh, MOE_BF16, M, 2 * f, MOE_Q_ROW, a->dh_codes, a->dh_scale, s);
   if (rc != MOE_OK) return rc;
   rc = mfma_rowseg_nt_fp8(a->dh_codes, a->dh_scale, a->w1t, a->w1t_scale, (long)d * 2 * f, a->offsets, M, d, 2 * f, E,
-                          a->d_xp, s);
+                          a->d_xp, a->splitk_ws, s);
   if (rc != MOE_OK) return rc;
   rc = launch_tgroup_offsets(a->offsets, E, a->pad_offsets, s);
   if (rc != MOE_OK) return rc;

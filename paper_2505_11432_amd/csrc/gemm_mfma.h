@@ -42,6 +42,11 @@ struct Args {
   // operand, applied by the block-scaled MFMA; [groups, rows] with the given row counts as leading dimensions
   const uint8_t* a_e8m0; long a_e8_ld;
   const uint8_t* b_e8m0; long b_e8_ld;
+  // Split-K for the last, partly filled round of tiles (ROWSEG, bf16 store epilogue only): when the tiles left
+  // after the complete rounds fill at most half of the workgroups, each of them is cut into 2..4 parts along K
+  // that run on different workgroups and write fp32 partial tiles here ([part][BM][BN]); splitk_fixup_kernel
+  // adds the parts and writes C.  NULL: no splitting.
+  float* splitk_ws;
   unsigned long long* clk_out;       // tuning aid (NULL in the library): per-block {core clocks, 100 MHz ticks}
 };
 

@@ -46,8 +46,19 @@ int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
     MOE_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
     configured = true;
   }
-  kern<<<dim3((unsigned)blocks), dim3(WM * WN * 64), smem, s>>>(a);
+  Args args = a;
+  constexpr bool kSplitK = MODE == ROWSEG && EPI == EPI_STORE && sizeof(TC) == 2;
+  if (!kSplitK || args.accumulate || blocks > MOE_SPLITK_MAX_PARTS) args.splitk_ws = nullptr;
+  kern<<<dim3((unsigned)blocks), dim3(WM * WN * 64), smem, s>>>(args);
   MOE_LAUNCH_CHECK();
+  if constexpr (kSplitK) {
+    if (args.splitk_ws != nullptr) {
+      // one workgroup per tile of the partly filled last round (fewer than `blocks`); the others return at once
+      splitk_fixup_kernel<BM, BN><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(args.splitk_ws, args.offsets, args.E, args.N, blocks,
+                                                                              static_cast<bf16*>(args.C), args.ldc);
+      MOE_LAUNCH_CHECK();
+    }
+  }
   return MOE_OK;
 }
 
@@ -70,8 +81,9 @@ int mfma_fc1_swiglu(const void* xp, const void* w1, const int32_t* offsets, int 
 
 // C[M,N] = A[M,K] * W[e]^T with W[e] = [N,K]
 int mfma_rowseg_nt(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
-                   void* C, hipStream_t s) {
+                   void* C, void* splitk_ws, hipStream_t s) {
   Args a{};
+  a.splitk_ws = static_cast<float*>(splitk_ws);
   a.A = (const bf16*)A; a.lda = K;
   a.B = (const bf16*)W; a.ldb = K; a.b_es = w_es;
   a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
@@ -80,8 +92,9 @@ int mfma_rowseg_nt(const void* A, const void* W, long w_es, const int32_t* offse
 
 // C[M,N] = A[M,K] * W[e] with W[e] = [K,N]
 int mfma_rowseg_nn(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
-                   void* C, hipStream_t s) {
+                   void* C, void* splitk_ws, hipStream_t s) {
   Args a{};
+  a.splitk_ws = static_cast<float*>(splitk_ws);
   a.A = (const bf16*)A; a.lda = K;
   a.B = (const bf16*)W; a.ldb = N; a.b_es = w_es;
   a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;
@@ -127,8 +140,9 @@ int mfma_fc1_swiglu_fp8(const void* xp, const float* xp_scale, const void* w1, c
 
 // C[M,N] = (A*sa) * (W[e]*sw)^T, bf16 out
 int mfma_rowseg_nt_fp8(const void* A, const float* a_scale, const void* W, const float* w_scale, long w_es,
-                       const int32_t* offsets, int M, int N, int K, int E, void* C, hipStream_t s) {
+                       const int32_t* offsets, int M, int N, int K, int E, void* C, void* splitk_ws, hipStream_t s) {
   Args a{};
+  a.splitk_ws = static_cast<float*>(splitk_ws);
   a.A = A; a.lda = K;
   a.B = W; a.ldb = K; a.b_es = w_es;
   a.C = C; a.ldc = N; a.offsets = offsets; a.E = E; a.M = M; a.N = N; a.K = K;

@@ -194,6 +194,74 @@ __device__ __forceinline__ i32x8 read_frag_fp8(const char* tile, int base, int k
   return r;
 }
 
+// Work list with the last round split along K: tiles [0, full_tiles) are whole; each of the remaining
+// total_tiles - full_tiles tiles becomes `split` items.  No split unless it at least halves the last round.
+__host__ __device__ __forceinline__ void splitk_plan(int total_tiles, int workgroups, int& full_tiles, int& split, int& total_items) {
+  full_tiles = total_tiles / workgroups * workgroups;
+  const int rem = total_tiles - full_tiles;
+  split = 1;
+  if (rem > 0 && workgroups / rem >= 2) split = workgroups / rem >= 4 ? 4 : workgroups / rem;
+  if (split == 1) full_tiles = total_tiles;
+  total_items = full_tiles + (total_tiles - full_tiles) * split;
+}
+
+// Adds the K parts of every split tile and writes the bf16 result with the tile's row / column masks.  One
+// workgroup per split tile; the tile list is rebuilt exactly as in the GEMM kernel (same grouping constants).
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) splitk_fixup_kernel(const float* __restrict__ parts, const int32_t* __restrict__ offsets,
+                                                           int E, int N, int gemm_workgroups, bf16* __restrict__ C, long ldc) {
+  constexpr int GN = 4;
+  __shared__ int cum_tiles[MOE_MAX_EXPERTS + 1];
+  if (threadIdx.x == 0) {
+    int run = 0;
+    cum_tiles[0] = 0;
+    for (int i = 0; i < E; ++i) {
+      run += (offsets[i + 1] - offsets[i] + BM - 1) / BM;
+      cum_tiles[i + 1] = run;
+    }
+  }
+  __syncthreads();
+  const int tiles_n = (N + BN - 1) / BN;
+  const int total_tiles = cum_tiles[E] * tiles_n;
+  int full_tiles, split, total_items;
+  splitk_plan(total_tiles, gemm_workgroups, full_tiles, split, total_items);
+  const int r_tile = blockIdx.x;
+  if (split == 1 || r_tile >= total_tiles - full_tiles) return;
+  int l = full_tiles + r_tile;
+  int lo = 0, hi = E;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cum_tiles[mid] * tiles_n <= l) lo = mid; else hi = mid;
+  }
+  const int e = lo;
+  const int mt_e = cum_tiles[e + 1] - cum_tiles[e];
+  l -= cum_tiles[e] * tiles_n;
+  const int ng = l / (mt_e * GN);
+  const int r = l - ng * mt_e * GN;
+  const int gw = min(GN, tiles_n - ng * GN);
+  const int mt = r / gw;
+  const int nt = ng * GN + (r - mt * gw);
+  const int m0 = offsets[e] + mt * BM, m_end = offsets[e + 1], n0 = nt * BN;
+  const float* base = parts + (long)r_tile * split * (BM * BN);
+  for (int i = threadIdx.x; i < BM * BN / 8; i += blockDim.x) {
+    const int row = i / (BN / 8), col = (i % (BN / 8)) * 8;
+    if (m0 + row >= m_end || n0 + col >= N) continue;          // N is a multiple of 8
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = 0.f;
+    for (int s = 0; s < split; ++s) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(base + (long)s * (BM * BN) + row * BN + col);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(base + (long)s * (BM * BN) + row * BN + col + 4);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { v[q] += a[q]; v[4 + q] += b[q]; }
+    }
+    bf16x8 o;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) o[q] = static_cast<bf16>(v[q]);
+    *reinterpret_cast<bf16x8*>(C + (long)(m0 + row) * ldc + n0 + col) = o;
+  }
+}
+
 template <int BM, int BN, int BKT, int NSTAGE, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC,
           int PROBE = 0, typename TIN = bf16>   // TIN = uint8_t: e4m3 codes, K-major operands only   // PROBE (tuning only): 1 = no global loads, 2 = no LDS reads / MFMAs, 3 = all tiles load tile 0
 __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) {
@@ -261,6 +329,12 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   } else {
     total_tiles = tiles_m_fixed * tiles_n;
   }
+  // split-K plan for the partly filled last round (see Args::splitk_ws); identical arithmetic in splitk_fixup_kernel
+  constexpr bool SPLITK = MODE == ROWSEG && EPI == EPI_STORE && sizeof(TC) == 2;
+  int full_tiles = total_tiles, split = 1, total_items = total_tiles;
+  if constexpr (SPLITK) {
+    if (p.splitk_ws != nullptr) splitk_plan(total_tiles, (int)gridDim.x, full_tiles, split, total_items);
+  }
   const int xcd = blockIdx.x % XCDS;
   const int window = gridDim.x / XCDS;           // tiles per window = CUs per XCD
   const int in_window = blockIdx.x / XCDS;
@@ -268,6 +342,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
   // tile state
   int e = 0, m0 = 0, m_end = 0, n0 = 0, klen = 0, nk = 0;
+  int part_slot = -1;               // >= 0: this work item is one K part of a split tile; index of its partial tile
   const bool is_loader = !SPLIT || wave < NL;            // wave-uniform; the lower waves win issue arbitration
   const int lw = wave & (NL - 1);                        // loader index
   const char* a_base = zero;        // wave-uniform: operand origin of the open tile at its first k
@@ -288,7 +363,14 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   // Decode slot -> tile and set up this lane's source pointers.  Returns false when the list is exhausted.
   auto open_tile = [&](int sl) __attribute__((always_inline)) -> bool {
     int l = (sl * XCDS + xcd) * window + in_window;
-    if (l >= total_tiles) return false;
+    if (l >= total_items) return false;
+    int part = 0;
+    part_slot = -1;
+    if (l >= full_tiles) {           // only with SPLITK: parts of one tile are neighbours in the list
+      part_slot = l - full_tiles;
+      part = part_slot % split;
+      l = full_tiles + part_slot / split;
+    }
     int mt_e, m_lo, m_hi;
     if constexpr (MODE == ROWSEG) {
       // binary search: largest ex with cum_tiles[ex] * tiles_n <= l
@@ -319,6 +401,12 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     else { k_begin = 0; k_end = p.K; }
     klen = k_end - k_begin;
     nk = (klen + BKT - 1) / BKT;
+    if (part_slot >= 0) {            // this item covers k-steps [s0, s1) of the tile
+      const int s0 = part * nk / split, s1 = (part + 1) * nk / split;
+      k_begin += s0 * BKT;
+      klen = min(klen, s1 * BKT) - s0 * BKT;
+      nk = s1 - s0;
+    }
     const char* Ag = static_cast<const char*>(p.A);
     const char* Bg = static_cast<const char*>(p.B) + (long)e * p.b_es * ESZ;
     const int real_m0 = m0, real_n0 = n0;
@@ -494,7 +582,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     }
 
     // ---- hand the ring to the next tile, then write this one out -------------------------------------
-    const int ep_e = e, ep_m0 = m0, ep_m_end = m_end, ep_n0 = n0;
+    const int ep_e = e, ep_m0 = m0, ep_m_end = m_end, ep_n0 = n0, ep_part_slot = part_slot;
     slot += 1;
     __syncthreads();                      // every wave has read its last fragments: the ring is free
     const bool has_next = open_tile(slot);
@@ -532,7 +620,15 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         }
       }
       // every 32x32 MFMA tile goes through the wave's LDS patch (see stage_store_* above)
-      if constexpr (EPI == EPI_STORE) {
+      if (SPLITK && ep_part_slot >= 0) {
+        // one K part of a split tile: the whole fp32 tile goes to the partial buffer, no masks
+        float* part_tile = p.splitk_ws + (long)ep_part_slot * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            stage_store_f32(stg, acc[i][j], part_tile + (long)(wm * WTM + i * 32) * BN + wn * WTN + j * 32, BN, 32, 32, false, lane);
+      } else if constexpr (EPI == EPI_STORE) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
           const int mb = m0 + wm * WTM + i * 32;

@@ -99,10 +99,13 @@ int launch_quant_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, c
 // bf16 grouped GEMMs on the matrix cores (gemm_mfma.hip)
 int mfma_fc1_swiglu(const void* xp, const void* w1, const int32_t* offsets, int M, int d, int E, int f, void* H,
                     void* A_out, hipStream_t s);
+// splitk_ws: MOE_SPLITK_WS_BYTES of scratch for the partial tiles of a split last round, or NULL (no splitting)
+constexpr int MOE_SPLITK_MAX_PARTS = 256;                               // at most one part per workgroup
+static_assert(MOE_SPLITK_WS_BYTES == (size_t)MOE_SPLITK_MAX_PARTS * 256 * 256 * 4, "one 256x256 fp32 tile per part");
 int mfma_rowseg_nt(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
-                   void* C, hipStream_t s);
+                   void* C, void* splitk_ws, hipStream_t s);
 int mfma_rowseg_nn(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
-                   void* C, hipStream_t s);
+                   void* C, void* splitk_ws, hipStream_t s);
 int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offsets, int M, int d, int E, int f,
                            const void* H, void* dH, void* A_out, hipStream_t s);
 int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int N, int E, void* C, moe_dtype c_dt,
@@ -111,7 +114,7 @@ int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int
 int mfma_fc1_swiglu_fp8(const void* xp, const float* xp_scale, const void* w1, const float* w1_scale,
                         const int32_t* offsets, int M, int d, int E, int f, void* H, void* A_out, hipStream_t s);
 int mfma_rowseg_nt_fp8(const void* A, const float* a_scale, const void* W, const float* w_scale, long w_es,
-                       const int32_t* offsets, int M, int N, int K, int E, void* C, hipStream_t s);
+                       const int32_t* offsets, int M, int N, int K, int E, void* C, void* splitk_ws, hipStream_t s);
 int mfma_dgrad2_swiglu_bwd_fp8(const void* dyq, const float* dyq_scale, const void* w2t, const float* w2t_scale,
                                const int32_t* offsets, int M, int d, int E, int f, const void* H, void* dH, void* A_out,
                                hipStream_t s);

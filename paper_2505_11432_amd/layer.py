@@ -140,7 +140,8 @@ class MoELayer:
             dy_t=torch.zeros((d, ldt), **u8), dy_e8m0=torch.zeros((G, d), **u8),
             dh_t=torch.zeros((two_f, ldt), **u8), dh_e8m0=torch.zeros((G, two_f), **u8),
             a_t=torch.zeros((f, ldt), **u8), a_e8m0=torch.zeros((G, f), **u8),
-            x_t=torch.zeros((d, ldt), **u8), x_e8m0=torch.zeros((G, d), **u8))
+            x_t=torch.zeros((d, ldt), **u8), x_e8m0=torch.zeros((G, d), **u8),
+            splitk_ws=torch.empty((B.SPLITK_WS_BYTES,), **u8))
 
     def backward_fp8_gemm(self, x, w_r, dy, with_router: bool = True):
         """Backward of forward_fp8 with the four expert GEMMs on E4M3 operands (Section 7: per-channel
