@@ -24,7 +24,7 @@ PEAK_HBM_GBPS = 8000.0
 # L2-fill + write-back bytes per grouped-GEMM launch (average of the six launches of one step) on the default
 # workload, from rocprofv3 --pmc FETCH_SIZE (x2.000, the factor a 1 GiB copy gives) and WRITE_SIZE (x1.000);
 # the counter runs are summarised in profiles/grouped_gemm_mixtral_hbm_counters.txt.
-MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"mixtral": 8.20e9}
+MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"mixtral": 8.09e9}
 
 
 def parse():
@@ -95,7 +95,8 @@ def cpu_baseline(cfg, inp, tokens):
     dt = time.perf_counter() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {tokens} of {cfg.T} tokens, all {len(cfg.local_experts)} local experts and full d, d_ff; "
+            "sample": f"first {tokens} of {cfg.T} tokens, all {len(cfg.local_experts)} " +
+                      ("local " if cfg.expert_range else "") + "experts and full d, d_ff; "
                       f"numpy float64 forward+backward, {dt:.1f} s"}
 
 
