@@ -312,6 +312,109 @@ def expert_ffn_bwd(xp, H, dY, offsets, W1, W2, A=None):
 
 
 # --------------------------------------------------------------------------
+# Section 4.1 / 4.2 operator order: rows selected by the index map inside FC1 (no
+# dispatched copy of the input), the gate weight multiplied right after SwiGLU so
+# that the FC2 output need not be kept, the gate-weight gradient taken where the
+# recomputed FC2 input is at hand.  Same layer, other association: pinned equal to
+# layer_fwd / layer_bwd.
+# --------------------------------------------------------------------------
+
+def row_tokens(perm, k: int) -> np.ndarray:
+    """Token whose copy dispatched row r is: perm[r] div k."""
+    return np.asarray(perm, np.int64) // k
+
+
+def row_gate_weights(w, perm) -> np.ndarray:
+    """Gate weight of the assignment behind dispatched row r: w.flat[perm[r]]."""
+    return np.asarray(w, F64).reshape(-1)[np.asarray(perm, np.int64)]
+
+
+def expert_ffn_fwd_folded(x, tok, row_w, offsets, W1, W2):
+    """[G|U] = x[tok[r]] W1^T,  A' = w_r * silu(G) * U,  Y' = A' W2^T  (Y' = w_r * Y).  Returns H, A', Y'."""
+    x = np.asarray(x, F64)
+    row_w = np.asarray(row_w, F64)
+    E, two_f, d = W1.shape
+    f = two_f // 2
+    M = len(tok)
+    H = np.zeros((M, two_f), dtype=F64)
+    Aw = np.zeros((M, f), dtype=F64)
+    Yw = np.zeros((M, d), dtype=F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo:
+            continue
+        X = x[tok[lo:hi], :]
+        G = X @ np.asarray(W1[e, :f, :], F64).T
+        U = X @ np.asarray(W1[e, f:, :], F64).T
+        H[lo:hi, :f] = G
+        H[lo:hi, f:] = U
+        Aw[lo:hi] = row_w[lo:hi, None] * silu(G) * U
+        Yw[lo:hi] = Aw[lo:hi] @ np.asarray(W2[e], F64).T
+    return H, Aw, Yw
+
+
+def expert_ffn_bwd_folded(x, dy, tok, row_w, H, offsets, W1, W2):
+    """Backward of expert_ffn_fwd_folded followed by an unweighted combine.
+
+    dY'[r] = dy[tok[r]];  dA' = dY' W2 (gradient w.r.t. A' = w_r A);  d_row_w[r] = <dA'[r], A[r]> with A
+    recomputed from H;  dA = w_r dA';  dW2 = dY'^T A';  then SwiGLU', dgrad1 and wgrad1 as usual, with the
+    FC1 input rows again selected from x.  Returns dxp, dW1, dW2, dH, d_row_w.
+    """
+    x = np.asarray(x, F64)
+    dy = np.asarray(dy, F64)
+    H = np.asarray(H, F64)
+    row_w = np.asarray(row_w, F64)
+    E, two_f, d = W1.shape
+    f = two_f // 2
+    M = H.shape[0]
+    dxp = np.zeros((M, d), dtype=F64)
+    dH = np.zeros((M, two_f), dtype=F64)
+    dW1 = np.zeros((E, two_f, d), dtype=F64)
+    dW2 = np.zeros((E, d, f), dtype=F64)
+    d_row_w = np.zeros(M, dtype=F64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if hi == lo:
+            continue
+        G, U = H[lo:hi, :f], H[lo:hi, f:]
+        A = silu(G) * U
+        dYw = dy[tok[lo:hi], :]
+        dAw = dYw @ np.asarray(W2[e], F64)
+        d_row_w[lo:hi] = np.einsum("rf,rf->r", dAw, A)
+        dW2[e] = dYw.T @ (A * row_w[lo:hi, None])
+        dG, dU = swiglu_bwd(G, U, dAw * row_w[lo:hi, None])
+        dH[lo:hi, :f] = dG
+        dH[lo:hi, f:] = dU
+        dW1[e] = dH[lo:hi].T @ x[tok[lo:hi], :]
+        dxp[lo:hi] = dH[lo:hi] @ np.asarray(W1[e], F64)
+    return dxp, dW1, dW2, dH, d_row_w
+
+
+def layer_fwd_folded(x, r: dict, W1, W2, k: int) -> dict:
+    """Forward from a routing result r in the Section 4.1 order.  Rows at or past offsets[E] do not exist."""
+    T = x.shape[0]
+    r = dict(r)
+    M = int(r["offsets"][-1])
+    tok = row_tokens(r["perm"][:M], k)
+    rw = row_gate_weights(r["w"], r["perm"][:M])
+    H, Aw, Yw = expert_ffn_fwd_folded(x, tok, rw, r["offsets"], W1, W2)
+    y = combine(Yw, r["inv_perm"], None, T, k)
+    r.update(tok=tok, row_w=rw, H=H, Aw=Aw, Yw=Yw, y=y)
+    return r
+
+
+def layer_bwd_folded(x, W1, W2, k: int, dy, fwd: dict) -> dict:
+    """Backward of layer_fwd_folded up to the gate-weight gradient dw [T,k] (zero where an assignment has no row)."""
+    T = x.shape[0]
+    M = int(fwd["offsets"][-1])
+    dxp, dW1, dW2, dH, d_row_w = expert_ffn_bwd_folded(x, dy, fwd["tok"], fwd["row_w"], fwd["H"], fwd["offsets"], W1, W2)
+    dw = np.zeros(T * k, dtype=F64)
+    dw[np.asarray(fwd["perm"][:M], np.int64)] = d_row_w
+    dx = combine(dxp, fwd["inv_perm"], None, T, k)
+    return dict(dw=dw.reshape(T, k), dxp=dxp, dW1=dW1, dW2=dW2, dH=dH, dx=dx, d_row_w=d_row_w)
+
+
+# --------------------------------------------------------------------------
 # Whole layer
 # --------------------------------------------------------------------------
 

@@ -228,3 +228,63 @@ def test_synthetic_shapes_follow_table2():
     assert (fg.d, fg.f, fg.E) == (rows["DeepSeekMoE"]["h"], rows["DeepSeekMoE"]["hffn"], rows["DeepSeekMoE"]["E"])
     sk = CONFIGS["skewed"]
     assert sk.d == rows["Internal-352B"]["h"] and sk.E == rows["Internal-352B"]["E"]
+
+
+# ---- Section 4.1 operator order (row select inside FC1, gate weight after SwiGLU) -------------------------
+
+@pytest.mark.parametrize("variant", ["full", "range", "capacity"])
+def test_folded_order_equals_the_plain_layer(variant):
+    # The reordered layer is the same function: pinned against layer_fwd / layer_bwd (themselves pinned by
+    # finite differences and autograd above), on a full route, an expert-parallel share and a route with drops.
+    rng = np.random.default_rng(31)
+    T, d, E, k, f = 37, 16, 6, 3, 8
+    x = rng.standard_normal((T, d))
+    dy = rng.standard_normal((T, d))
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    W1 = rng.standard_normal((E, 2 * f, d)) * 0.3
+    W2 = rng.standard_normal((E, d, f)) * 0.3
+    if variant == "full":
+        r = O.route(logits, k)
+        W1l, W2l = W1, W2
+    elif variant == "range":
+        r = O.route_range(logits, k, 2, 5)
+        W1l, W2l = W1[2:5], W2[2:5]
+    else:
+        r = O.route_capacity(logits, k, 3, 25)
+        W1l, W2l = W1, W2
+        assert (r["inv_perm"] < 0).any()
+    plain = O.layer_fwd_routed(x, r, W1l, W2l, k)
+    fold = O.layer_fwd_folded(x, r, W1l, W2l, k)
+    M = int(r["offsets"][-1])
+    np.testing.assert_allclose(fold["y"], plain["y"], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(fold["H"][:M], plain["H"][:M], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(fold["Yw"][:M], plain["Y"][:M] * fold["row_w"][:, None], rtol=0, atol=1e-12)
+    pb = O.layer_bwd_routed(x, W1l, W2l, k, dy, plain)
+    fb = O.layer_bwd_folded(x, W1l, W2l, k, dy, fold)
+    for key in ("dw", "dx", "dW1", "dW2"):
+        np.testing.assert_allclose(fb[key], pb[key], rtol=0, atol=1e-11, err_msg=key)
+    np.testing.assert_allclose(fb["dxp"][:M], pb["dxp"][:M], rtol=0, atol=1e-11)
+    np.testing.assert_allclose(fb["dH"][:M], pb["dH"][:M], rtol=0, atol=1e-11)
+
+
+def test_folded_gate_gradient_by_finite_differences():
+    # d_row_w is the derivative of <dy, y> w.r.t. each row's gate weight with the rest held fixed
+    rng = np.random.default_rng(32)
+    T, d, E, k, f = 9, 8, 3, 2, 4
+    x = rng.standard_normal((T, d))
+    dy = rng.standard_normal((T, d))
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    W1 = rng.standard_normal((E, 2 * f, d)) * 0.4
+    W2 = rng.standard_normal((E, d, f)) * 0.4
+    r = O.route(logits, k)
+    fwd = O.layer_fwd_folded(x, r, W1, W2, k)
+    g = O.layer_bwd_folded(x, W1, W2, k, dy, fwd)["d_row_w"]
+    eps = 1e-6
+    for row in range(0, T * k, 5):
+        vals = []
+        for sgn in (+1, -1):
+            rw = fwd["row_w"].copy()
+            rw[row] += sgn * eps
+            _, _, Yw = O.expert_ffn_fwd_folded(x, fwd["tok"], rw, r["offsets"], W1, W2)
+            vals.append(float((dy * O.combine(Yw, r["inv_perm"], None, T, k)).sum()))
+        assert abs((vals[0] - vals[1]) / (2 * eps) - g[row]) < 1e-6
