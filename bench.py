@@ -41,6 +41,10 @@ def parse():
                     help="bf16 configurations: device-level token dropping with capacity = factor * T*k / devices (0 = dropless)")
     ap.add_argument("--balance-alpha", type=float, default=0.0, help="add the device-level auxiliary balance loss (0 = off)")
     ap.add_argument("--devices", type=int, default=8, help="expert groups (GPUs of the node) for the two switches above")
+    ap.add_argument("--fused", action="store_true",
+                    help="bf16 only: the paper's Section 4.1 / 4.2 operator order (FC1 selects its rows from x inside the "
+                         "kernel, gate weight after SwiGLU, gate gradient from the dgrad2 epilogue, no dispatched input "
+                         "or FC2 output kept for the backward)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size reference for HBM byte counters")
     return ap.parse_args()
@@ -130,7 +134,10 @@ def main():
     capacity = (devices, int(math.ceil(args.capacity_factor * cfg.T * cfg.k / devices))) if args.capacity_factor > 0 else None
     balance = (devices, args.balance_alpha) if args.balance_alpha > 0 else None
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=fp8,
-                     expert_range=cfg.expert_range, capacity=capacity, balance=balance)
+                     expert_range=cfg.expert_range, capacity=capacity, balance=balance, fused=args.fused)
+    if args.fused and fp8:
+        print("bench.py: --fused is a bf16 path", file=sys.stderr)
+        sys.exit(2)
     if fp8:
         layer.set_fp8_weights(w1, w2)       # parameters are kept in E4M3 across steps (Section 7): outside the timed loop
         if args.fp8_backward:
@@ -202,7 +209,9 @@ def main():
                                (f"; expert-parallel share: experts {cfg.expert_range[0]}..{cfg.expert_range[1] - 1} local, "
                                 f"{M} of {cfg.M} dispatched rows, tokens = the all-gathered tokens" if cfg.expert_range else "") +
                                (f"; capacity {capacity[1]} rows per device over {capacity[0]} devices, {M} of {cfg.M} rows kept"
-                                if capacity else "") + (f"; balance loss alpha={args.balance_alpha}" if balance else ""),
+                                if capacity else "") + (f"; balance loss alpha={args.balance_alpha}" if balance else "") +
+                               ("; fused operator order (row select inside FC1, gate weight after SwiGLU, FC1 input rows "
+                                "produced again in the backward)" if args.fused else ""),
                    "tokens": cfg.T, "expert_rows": counts},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",
@@ -212,7 +221,9 @@ def main():
                      "flops_per_launch_avg": gemm_flops / 6, "launch_ms_avg": gemm_ms / 6},
         "gemm_tflops": {"fwd": 6.0 * M * cfg.d * cfg.f / per_call["expert_ffn_fwd"] / 1e9,
                         "bwd": 12.0 * M * cfg.d * cfg.f / per_call["expert_ffn_bwd"] / 1e9},
-        "hbm_gbps": {"dispatch": row_bytes / per_call["dispatch"] / 1e6,
+        # activations held from the forward to the backward, beyond x itself and the routing tables
+        "kept_activation_bytes": (M * 2 * cfg.f * 2 + M * 8) if args.fused else (M * 2 * cfg.f * 2 + 2 * M * cfg.d * (1 if fp8 else 2)),
+        "hbm_gbps": {"dispatch": row_bytes / per_call["dispatch"] / 1e6 if "dispatch" in per_call else None,
                      "combine": row_bytes / per_call["combine"] / 1e6,
                      "peak": PEAK_HBM_GBPS},
         "ms_per_call": per_call,

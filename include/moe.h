@@ -206,6 +206,54 @@ int moe_expert_ffn_bwd(const void* xp, const void* h_save, const void* d_yp,
                        void* d_xp /*[M,d]*/, void* d_w1, void* d_w2, moe_dtype grad_dt,
                        int accumulate, void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- expert FFN in the Section 4.1 / 4.2 operator order (bf16 only) --------------------
+ * The same layer with three changes of association, each the paper's: FC1 selects its input
+ * rows from the token-order x through an index map inside the kernel's loads instead of
+ * reading a dispatched copy (Section 4.2, "select rows of input data by the index mapping");
+ * the gate weight is multiplied right after SwiGLU, so FC2 returns already weighted rows,
+ * the combine is an unweighted sum (moe_combine with topk_w = NULL) and the FC2 output need
+ * not be kept for the backward; the FC1 input rows are produced again in the backward
+ * instead of being kept (Section 4.1, selective rematerialisation).  What stays resident
+ * between forward and backward: x, h_save, the routing tables, row_token and row_w.
+ *
+ * moe_row_map: row_token[r] = perm[r] / k and row_w[r] = topk_w[perm[r]] for r < offsets[E];
+ * token 0 and weight 0 for the remaining rows up to T*k. */
+int moe_row_map(const int32_t* perm /*[T*k]*/, const float* topk_w /*[T,k]*/,
+                const int32_t* offsets /*[E+1]*/, int E, int T, int k,
+                int32_t* row_token /*[T*k]*/, float* row_w /*[T*k]*/, void* stream);
+
+/* Bytes of workspace for the two calls below (0 on invalid sizes). */
+size_t moe_expert_ffn_fused_workspace_bytes(int T, int k, int d, int f);
+
+/* For row r of expert e: [G|U] = x[row_token[r],:] * w1[e]^T (written to h_save [T*k,2f]),
+ * A' = row_w[r] * SwiGLU(G,U), ypw[r,:] = A' * w2[e]^T = row_w[r] * (the plain yp[r,:]).
+ * x [T,d], w1, w2, h_save, ypw are bf16; T*d*2 bytes must stay below 4 GiB
+ * (MOE_ERR_UNSUPPORTED otherwise).  Rows at or past offsets[E] are not written. */
+int moe_expert_ffn_fused_fwd(const void* x, const int32_t* row_token, const float* row_w,
+                             const int32_t* offsets, const void* w1, const void* w2,
+                             int T, int k, int d, int E, int f, void* h_save, void* ypw /*[T*k,d]*/,
+                             void* workspace, size_t ws_bytes, void* stream);
+
+/* Backward of moe_expert_ffn_fused_fwd followed by the unweighted combine, from the
+ * token-order output gradient dy [T,d]:  dY'[r] = dy[token of r];  dA' = dY' * w2[e];
+ * d_topk_w[t,j] = <dA'[r,:], A[r,:]> for the row r of assignment (t,j), A recomputed from
+ * h_save, 0 where the assignment has no row (summed in a fixed order: bit-reproducible);
+ * d_w2[e] = dY'_e^T * A'_e.  The gate weight is linear in everything downstream of dA', so
+ * it is applied once per row instead of once per element:
+ *   (dG,dU) = SwiGLU'(G,U, dA');  d_xp[r,:] = [dG|dU] * w1[e]  -- WITHOUT the weight: the
+ *   input gradient is dx[t,:] = sum_j topk_w[t,j] * d_xp[row(t,j),:], i.e. moe_combine WITH
+ *   topk_w;  d_w1[e] = [dG|dU]_e^T * (row_w[r] * x[token of r]).
+ * topk_w [T,k] and row_w [T*k] are the same weights by assignment and by row (moe_row_map).
+ * grad_dt, accumulate: as in moe_expert_ffn_bwd. */
+int moe_expert_ffn_fused_bwd(const void* x, const void* dy, const void* h_save,
+                             const int32_t* inv_perm /*[T*k]*/, const float* topk_w,
+                             const float* row_w, const int32_t* offsets,
+                             const void* w1, const void* w2,
+                             int T, int k, int d, int E, int f,
+                             void* d_xp /*[T*k,d]*/, void* d_w1, void* d_w2, moe_dtype grad_dt,
+                             int accumulate, float* d_topk_w /*[T,k]*/,
+                             void* workspace, size_t ws_bytes, void* stream);
+
 /* ---- E4M3 cast (Section 5 "Communication compression for FP8 training"; Section 7 "FP8
  * training": per-token 1 x h scales forward, per-channel scales in 128-token groups
  * backward) ---------------------------------------------------------------------------

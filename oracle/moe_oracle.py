@@ -357,8 +357,9 @@ def expert_ffn_bwd_folded(x, dy, tok, row_w, H, offsets, W1, W2):
     """Backward of expert_ffn_fwd_folded followed by an unweighted combine.
 
     dY'[r] = dy[tok[r]];  dA' = dY' W2 (gradient w.r.t. A' = w_r A);  d_row_w[r] = <dA'[r], A[r]> with A
-    recomputed from H;  dA = w_r dA';  dW2 = dY'^T A';  then SwiGLU', dgrad1 and wgrad1 as usual, with the
-    FC1 input rows again selected from x.  Returns dxp, dW1, dW2, dH, d_row_w.
+    recomputed from H;  dW2 = dY'^T A'.  Everything downstream of dA' is linear in it, so the weight is applied
+    once per row: dH0 = SwiGLU'(G, U, dA'), dxp0 = dH0 W1 (both WITHOUT the weight), the true input-row gradient
+    is dxp = w_r dxp0, and dW1 = dH0^T (w_r x[tok[r]]).  Returns dxp, dW1, dW2, dH0, d_row_w, dxp0.
     """
     x = np.asarray(x, F64)
     dy = np.asarray(dy, F64)
@@ -367,8 +368,8 @@ def expert_ffn_bwd_folded(x, dy, tok, row_w, H, offsets, W1, W2):
     E, two_f, d = W1.shape
     f = two_f // 2
     M = H.shape[0]
-    dxp = np.zeros((M, d), dtype=F64)
-    dH = np.zeros((M, two_f), dtype=F64)
+    dxp0 = np.zeros((M, d), dtype=F64)
+    dH0 = np.zeros((M, two_f), dtype=F64)
     dW1 = np.zeros((E, two_f, d), dtype=F64)
     dW2 = np.zeros((E, d, f), dtype=F64)
     d_row_w = np.zeros(M, dtype=F64)
@@ -382,12 +383,12 @@ def expert_ffn_bwd_folded(x, dy, tok, row_w, H, offsets, W1, W2):
         dAw = dYw @ np.asarray(W2[e], F64)
         d_row_w[lo:hi] = np.einsum("rf,rf->r", dAw, A)
         dW2[e] = dYw.T @ (A * row_w[lo:hi, None])
-        dG, dU = swiglu_bwd(G, U, dAw * row_w[lo:hi, None])
-        dH[lo:hi, :f] = dG
-        dH[lo:hi, f:] = dU
-        dW1[e] = dH[lo:hi].T @ x[tok[lo:hi], :]
-        dxp[lo:hi] = dH[lo:hi] @ np.asarray(W1[e], F64)
-    return dxp, dW1, dW2, dH, d_row_w
+        dG, dU = swiglu_bwd(G, U, dAw)
+        dH0[lo:hi, :f] = dG
+        dH0[lo:hi, f:] = dU
+        dW1[e] = dH0[lo:hi].T @ (row_w[lo:hi, None] * x[tok[lo:hi], :])
+        dxp0[lo:hi] = dH0[lo:hi] @ np.asarray(W1[e], F64)
+    return dxp0 * row_w[:, None], dW1, dW2, dH0, d_row_w, dxp0
 
 
 def layer_fwd_folded(x, r: dict, W1, W2, k: int) -> dict:
@@ -407,11 +408,11 @@ def layer_bwd_folded(x, W1, W2, k: int, dy, fwd: dict) -> dict:
     """Backward of layer_fwd_folded up to the gate-weight gradient dw [T,k] (zero where an assignment has no row)."""
     T = x.shape[0]
     M = int(fwd["offsets"][-1])
-    dxp, dW1, dW2, dH, d_row_w = expert_ffn_bwd_folded(x, dy, fwd["tok"], fwd["row_w"], fwd["H"], fwd["offsets"], W1, W2)
+    dxp, dW1, dW2, dH0, d_row_w, dxp0 = expert_ffn_bwd_folded(x, dy, fwd["tok"], fwd["row_w"], fwd["H"], fwd["offsets"], W1, W2)
     dw = np.zeros(T * k, dtype=F64)
     dw[np.asarray(fwd["perm"][:M], np.int64)] = d_row_w
-    dx = combine(dxp, fwd["inv_perm"], None, T, k)
-    return dict(dw=dw.reshape(T, k), dxp=dxp, dW1=dW1, dW2=dW2, dH=dH, dx=dx, d_row_w=d_row_w)
+    dx = combine(dxp0, fwd["inv_perm"], fwd["w"], T, k)          # the weight, once per row
+    return dict(dw=dw.reshape(T, k), dxp=dxp, dxp0=dxp0, dW1=dW1, dW2=dW2, dH0=dH0, dx=dx, d_row_w=d_row_w)
 
 
 # --------------------------------------------------------------------------

@@ -26,6 +26,7 @@ EXPORTS = (
     "moe_gate_grad", "moe_expert_ffn_fwd", "moe_expert_ffn_bwd", "moe_quant_fp8", "moe_dequant_fp8",
     "moe_expert_ffn_bwd_fp8", "moe_tgroup_tokens", "moe_quant_fp8_tgroup", "moe_route_range",
     "moe_route_capacity_workspace_bytes", "moe_route_capacity", "moe_balance_loss", "moe_balance_loss_bwd",
+    "moe_row_map", "moe_expert_ffn_fused_workspace_bytes", "moe_expert_ffn_fused_fwd", "moe_expert_ffn_fused_bwd",
 )
 
 
@@ -82,6 +83,10 @@ def _load() -> ctypes.CDLL:
         "moe_dequant_fp8": (I, [P, P, I, I, I, P, I, P]),
         "moe_expert_ffn_bwd_fp8": (I, [ctypes.POINTER(FfnBwdFp8Args), P]),
         "moe_tgroup_tokens": (Z, [I, I]),
+        "moe_row_map": (I, [P, P, P, I, I, I, P, P, P]),
+        "moe_expert_ffn_fused_workspace_bytes": (Z, [I, I, I, I]),
+        "moe_expert_ffn_fused_fwd": (I, [P, P, P, P, P, P, I, I, I, I, I, P, P, P, Z, P]),
+        "moe_expert_ffn_fused_bwd": (I, [P, P, P, P, P, P, P, P, P, I, I, I, I, I, P, P, P, I, I, P, P, Z, P]),
         "moe_quant_fp8_tgroup": (I, [P, I, I, I, P, I, P, P, ctypes.c_long, P, P]),
     }
     for name, (res, args) in sig.items():
@@ -271,3 +276,31 @@ def moe_balance_loss_bwd(logits, group_f, n_groups, alpha, d_logits):
     T, E = logits.shape
     _check("moe_balance_loss_bwd", _lib.moe_balance_loss_bwd(_p(logits), _p(group_f), T, E, n_groups, alpha, _p(d_logits),
                                                              _stream()))
+
+
+def moe_row_map(perm, topk_w, offsets, row_token, row_w):
+    T, k = topk_w.shape
+    E = offsets.numel() - 1
+    _check("moe_row_map", _lib.moe_row_map(_p(perm), _p(topk_w), _p(offsets), E, T, k, _p(row_token), _p(row_w), _stream()))
+
+
+def moe_expert_ffn_fused_workspace_bytes(T, k, d, f) -> int:
+    return _lib.moe_expert_ffn_fused_workspace_bytes(T, k, d, f)
+
+
+def moe_expert_ffn_fused_fwd(x, row_token, row_w, offsets, w1, w2, k, h_save, ypw, workspace):
+    T, d = x.shape
+    E, two_f, _ = w1.shape
+    _check("moe_expert_ffn_fused_fwd", _lib.moe_expert_ffn_fused_fwd(
+        _p(x), _p(row_token), _p(row_w), _p(offsets), _p(w1), _p(w2), T, k, d, E, two_f // 2, _p(h_save), _p(ypw),
+        _p(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_expert_ffn_fused_bwd(x, dy, h_save, inv_perm, topk_w, row_w, offsets, w1, w2, k, d_xp, d_w1, d_w2, accumulate,
+                             d_topk_w, workspace):
+    T, d = x.shape
+    E, two_f, _ = w1.shape
+    _check("moe_expert_ffn_fused_bwd", _lib.moe_expert_ffn_fused_bwd(
+        _p(x), _p(dy), _p(h_save), _p(inv_perm), _p(topk_w), _p(row_w), _p(offsets), _p(w1), _p(w2), T, k, d, E, two_f // 2,
+        _p(d_xp), _p(d_w1), _p(d_w2), dtype_code(d_w1.dtype), int(accumulate), _p(d_topk_w), _p(workspace),
+        workspace.numel() * workspace.element_size(), _stream()))

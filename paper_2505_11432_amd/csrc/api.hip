@@ -386,6 +386,97 @@ int moe_expert_ffn_bwd(const void* xp, const void* h_save, const void* d_yp, con
                        accumulate != 0, workspace, as_stream(stream));
 }
 
+// ---- Section 4.1 / 4.2 operator order (bf16) ---------------------------------------------------------------
+// workspace: A' [M,f] | dH [M,2f] | one [M,d] buffer (dY', later the re-dispatched FC1 input) | gate-gradient partials | split-K
+static size_t fused_a_bytes(size_t m, int f) { return align_up(m * f * 2, 256); }
+static size_t fused_dh_bytes(size_t m, int f) { return align_up(m * 2 * f * 2, 256); }
+static size_t fused_rows_bytes(size_t m, int d) { return align_up(m * d * 2, 256); }
+static size_t fused_part_bytes(size_t m, int f) { return align_up((size_t)mfma_dgrad2_fold_parts(f) * m * 4, 256); }
+
+size_t moe_expert_ffn_fused_workspace_bytes(int T, int k, int d, int f) {
+  if (T < 0 || k < 1 || d <= 0 || f <= 0) return 0;
+  const size_t m = (size_t)T * k;
+  return fused_a_bytes(m, f) + fused_dh_bytes(m, f) + fused_rows_bytes(m, d) + fused_part_bytes(m, f) + MOE_SPLITK_WS_BYTES + 256;
+}
+
+int moe_row_map(const int32_t* perm, const float* topk_w, const int32_t* offsets, int E, int T, int k,
+                int32_t* row_token, float* row_w, void* stream) {
+  if (T < 0 || k < 1 || k > MOE_MAX_TOPK || E < 1 || E > MOE_MAX_EXPERTS || (long)T * k > 0x7fffffffL) return MOE_ERR_INVALID;
+  if (T == 0) return MOE_OK;
+  if (!perm || !topk_w || !offsets || !row_token || !row_w) return MOE_ERR_INVALID;
+  return launch_row_map(perm, topk_w, offsets, E, T * k, k, row_token, row_w, as_stream(stream));
+}
+
+static int fused_args_ok(int T, int k, int d, int E, int f) {
+  if (T < 0 || k < 1 || k > MOE_MAX_TOPK || d <= 0 || f <= 0 || E < 1 || E > MOE_MAX_EXPERTS || (long)T * k > 0x7fffffffL)
+    return MOE_ERR_INVALID;
+  if (d % 16 != 0 || f % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  return MOE_OK;
+}
+
+int moe_expert_ffn_fused_fwd(const void* x, const int32_t* row_token, const float* row_w, const int32_t* offsets,
+                             const void* w1, const void* w2, int T, int k, int d, int E, int f, void* h_save, void* ypw,
+                             void* workspace, size_t ws_bytes, void* stream) {
+  int rc = fused_args_ok(T, k, d, E, f);
+  if (rc != MOE_OK) return rc;
+  if (T == 0) return MOE_OK;
+  if (!x || !row_token || !row_w || !offsets || !w1 || !w2 || !h_save || !ypw) return MOE_ERR_INVALID;
+  if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(h_save) || !aligned16(ypw) || !aligned16(workspace))
+    return MOE_ERR_UNSUPPORTED;
+  if (!workspace || ws_bytes < moe_expert_ffn_fused_workspace_bytes(T, k, d, f)) return MOE_ERR_WORKSPACE;
+  const int M = T * k;
+  hipStream_t s = as_stream(stream);
+  char* base = static_cast<char*>(workspace);
+  void* Aw = base;
+  void* splitk = base + fused_a_bytes(M, f) + fused_dh_bytes(M, f) + fused_rows_bytes(M, d) + fused_part_bytes(M, f);
+  rc = mfma_fc1_swiglu_gather(x, T, row_token, row_w, w1, offsets, M, d, E, f, h_save, Aw, s);
+  if (rc != MOE_OK) return rc;
+  return mfma_rowseg_nt(Aw, w2, (long)d * f, offsets, M, d, f, E, ypw, splitk, s);
+}
+
+int moe_expert_ffn_fused_bwd(const void* x, const void* dy, const void* h_save, const int32_t* inv_perm,
+                             const float* topk_w, const float* row_w, const int32_t* offsets, const void* w1, const void* w2, int T, int k,
+                             int d, int E, int f, void* d_xp, void* d_w1, void* d_w2, moe_dtype grad_dt, int accumulate,
+                             float* d_topk_w, void* workspace, size_t ws_bytes, void* stream) {
+  int rc = fused_args_ok(T, k, d, E, f);
+  if (rc != MOE_OK) return rc;
+  if (grad_dt != MOE_F32 && grad_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (!offsets || !d_w1 || !d_w2) return MOE_ERR_INVALID;
+  if (T > 0 && (!x || !dy || !h_save || !inv_perm || !topk_w || !row_w || !w1 || !w2 || !d_xp || !d_topk_w)) return MOE_ERR_INVALID;
+  if (!aligned16(x) || !aligned16(dy) || !aligned16(h_save) || !aligned16(w1) || !aligned16(w2) || !aligned16(d_xp) ||
+      !aligned16(d_w1) || !aligned16(d_w2) || !aligned16(workspace))
+    return MOE_ERR_UNSUPPORTED;
+  if (T > 0 && (!workspace || ws_bytes < moe_expert_ffn_fused_workspace_bytes(T, k, d, f))) return MOE_ERR_WORKSPACE;
+  const int M = T * k;
+  hipStream_t s = as_stream(stream);
+  char* base = static_cast<char*>(workspace);
+  void* Aw = base;
+  void* dH = base + fused_a_bytes(M, f);
+  void* rows = static_cast<char*>(dH) + fused_dh_bytes(M, f);
+  float* part = reinterpret_cast<float*>(static_cast<char*>(rows) + fused_rows_bytes(M, d));
+  void* splitk = reinterpret_cast<char*>(part) + fused_part_bytes(M, f);
+  if (T > 0) {
+    // dY'[r] = dy[token of r], unweighted: the weight now sits between SwiGLU and FC2
+    rc = launch_dispatch(dy, nullptr, MOE_BF16, inv_perm, nullptr, T, k, d, rows, nullptr, s);
+    if (rc != MOE_OK) return rc;
+    rc = mfma_dgrad2_swiglu_bwd_fold(rows, w2, offsets, M, d, E, f, h_save, dH, Aw, row_w, part, s);
+    if (rc != MOE_OK) return rc;
+    rc = launch_gate_grad_reduce(part, mfma_dgrad2_fold_parts(f), M, inv_perm, M, d_topk_w, s);
+    if (rc != MOE_OK) return rc;
+  }
+  rc = mfma_wgrad(rows, Aw, offsets, d, f, E, d_w2, grad_dt, accumulate != 0, s);
+  if (rc != MOE_OK) return rc;
+  if (T > 0) {
+    rc = mfma_rowseg_nn(dH, w1, 2L * f * d, offsets, M, d, 2 * f, E, d_xp, splitk, s);
+    if (rc != MOE_OK) return rc;
+    // the FC1 input rows are produced again here instead of being kept since the forward (Section 4.1); they carry
+    // the gate weight that dH was computed without
+    rc = launch_dispatch(x, nullptr, MOE_BF16, inv_perm, topk_w, T, k, d, rows, nullptr, s);
+    if (rc != MOE_OK) return rc;
+  }
+  return mfma_wgrad(dH, rows, offsets, 2 * f, d, E, d_w1, grad_dt, accumulate != 0, s);
+}
+
 int moe_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmode mode, uint8_t* codes,
                   float* scales, void* stream) {
   if (rows < 0 || cols < 0) return MOE_ERR_INVALID;

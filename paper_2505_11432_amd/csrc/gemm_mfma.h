@@ -18,7 +18,9 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 enum Layout { KMAJOR = 0, MNMAJOR = 1 };
 enum Mode { ROWSEG = 0, KSEG = 1, PLAIN = 2 };   // PLAIN: one dense GEMM, no expert segments
-enum Epi { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SWIGLU_BWD = 2, EPI_BIAS_F32 = 3 };
+// EPI_SWIGLU_W / EPI_SWIGLU_BWD_W: the Section 4.1 operator order (gate weight multiplied right after SwiGLU; the
+// forward one also selects its A rows through an index map, Section 4.2)
+enum Epi { EPI_STORE = 0, EPI_SWIGLU = 1, EPI_SWIGLU_BWD = 2, EPI_BIAS_F32 = 3, EPI_SWIGLU_W = 4, EPI_SWIGLU_BWD_W = 5 };
 
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
@@ -47,6 +49,11 @@ struct Args {
   // that run on different workgroups and write fp32 partial tiles here ([part][BM][BN]); splitk_fixup_kernel
   // adds the parts and writes C.  NULL: no splitting.
   float* splitk_ws;
+  // Section 4.1 / 4.2 order (EPI_SWIGLU_W, EPI_SWIGLU_BWD_W)
+  const int32_t* a_rowmap;           // EPI_SWIGLU_W: logical row r of A is row a_rowmap[r] of the buffer ([M] entries)
+  int a_phys_rows;                   //   rows of that buffer (for the 32-bit offset check)
+  const float* row_w;                // [M] gate weight of each row: A_out = w * SwiGLU(G, U) in both epilogues
+  float* dw_part;                    // EPI_SWIGLU_BWD_W: [n-tiles * waves along n][M] partial sums of <dA'[r,:], A[r,:]>
   unsigned long long* clk_out;       // tuning aid (NULL in the library): per-block {core clocks, 100 MHz ticks}
 };
 

@@ -30,9 +30,10 @@ int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
   {
     // the kernel addresses each operand as a 64-bit tile base plus a 32-bit per-lane byte offset
     const unsigned long long esz = sizeof(TIN), lim = 1ull << 32;
-    const unsigned long long a_span = (LA == KMAJOR) ? (unsigned long long)BM * a.lda * esz
-                                                     : ((unsigned long long)BKT * a.lda + a.M) * esz;
-    const unsigned long long b_rows = (EPI == EPI_SWIGLU) ? 2ull * a.f : (unsigned long long)a.N;
+    const unsigned long long a_span = (EPI == EPI_SWIGLU_W) ? (unsigned long long)a.a_phys_rows * a.lda * esz   // absolute row offsets
+                                      : (LA == KMAJOR)      ? (unsigned long long)BM * a.lda * esz
+                                                            : ((unsigned long long)BKT * a.lda + a.M) * esz;
+    const unsigned long long b_rows = (EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_W) ? 2ull * a.f : (unsigned long long)a.N;
     const unsigned long long b_span = (LB == KMAJOR) ? b_rows * a.ldb * esz : ((unsigned long long)BKT * a.ldb + a.N) * esz;
     if (a_span >= lim || b_span >= lim) return MOE_ERR_UNSUPPORTED;
   }
@@ -79,6 +80,18 @@ int mfma_fc1_swiglu(const void* xp, const void* w1, const int32_t* offsets, int 
   return launch<256, 256, 64, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_SWIGLU, bf16>(a, rowseg_blocks(M, E, f, 256, 128), s);
 }
 
+// The same with the Section 4.1 / 4.2 operator order: row r of the A operand is row row_token[r] of x [T,d] (selected
+// inside the kernel's loads, no dispatched copy), and A_out = row_w[r] * SwiGLU(H)
+int mfma_fc1_swiglu_gather(const void* x, int T, const int32_t* row_token, const float* row_w, const void* w1,
+                           const int32_t* offsets, int M, int d, int E, int f, void* H, void* A_out, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)x; a.lda = d; a.a_rowmap = row_token; a.a_phys_rows = T; a.row_w = row_w;
+  a.B = (const bf16*)w1; a.ldb = d; a.b_es = 2L * f * d;
+  a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d; a.f = f;
+  a.H = (bf16*)H; a.A_out = (bf16*)A_out;
+  return launch<256, 256, 64, 2, 4, 2, KMAJOR, KMAJOR, ROWSEG, EPI_SWIGLU_W, bf16>(a, rowseg_blocks(M, E, f, 256, 128), s);
+}
+
 // C[M,N] = A[M,K] * W[e]^T with W[e] = [N,K]
 int mfma_rowseg_nt(const void* A, const void* W, long w_es, const int32_t* offsets, int M, int N, int K, int E,
                    void* C, void* splitk_ws, hipStream_t s) {
@@ -110,6 +123,20 @@ int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offs
   a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d;
   a.H = (bf16*)const_cast<void*>(H); a.dH = (bf16*)dH; a.A_out = (bf16*)A_out;
   return launch<256, 256, 64, 2, 2, 4, KMAJOR, MNMAJOR, ROWSEG, EPI_SWIGLU_BWD, bf16>(a, rowseg_blocks(M, E, f, 256, 256), s);
+}
+
+// dgrad2 in the Section 4.1 order: d_yp holds the unweighted output gradient of each row; dH gets SwiGLU'(dA') (the
+// row's weight is applied downstream), A_out = w_r * A, and dw_part [mfma_dgrad2_fold_parts(f)][M] the partial sums of <dA'[r,:], A[r,:]>
+int mfma_dgrad2_fold_parts(int f) { return cdiv(f, 256) * 4; }
+int mfma_dgrad2_swiglu_bwd_fold(const void* d_yp, const void* w2, const int32_t* offsets, int M, int d, int E, int f,
+                                const void* H, void* dH, void* A_out, const float* row_w, float* dw_part, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)d_yp; a.lda = d;
+  a.B = (const bf16*)w2; a.ldb = f; a.b_es = (long)d * f;
+  a.offsets = offsets; a.E = E; a.M = M; a.N = f; a.K = d;
+  a.H = (bf16*)const_cast<void*>(H); a.dH = (bf16*)dH; a.A_out = (bf16*)A_out;
+  a.row_w = row_w; a.dw_part = dw_part;
+  return launch<256, 256, 64, 2, 2, 4, KMAJOR, MNMAJOR, ROWSEG, EPI_SWIGLU_BWD_W, bf16>(a, rowseg_blocks(M, E, f, 256, 256), s);
 }
 
 // C[e][Mo,N] (+)= P[rows_e, Mo]^T * Q[rows_e, N]

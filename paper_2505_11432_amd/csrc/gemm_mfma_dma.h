@@ -285,11 +285,15 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr int A_DMA = A_BYTES / 1024 / NL, B_DMA = B_BYTES / 1024 / NL;     // loads per loader wave per stage
   constexpr int LOADS = A_DMA + B_DMA;
   constexpr int KK = FP8 ? BKT / 64 : BKT / 16;    // MFMA sub-steps per k-step
-  constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+  constexpr bool SWI = EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_W;              // FC1 + SwiGLU epilogue
+  constexpr bool FOLD = EPI == EPI_SWIGLU_W || EPI == EPI_SWIGLU_BWD_W;       // gate weight folded in (Section 4.1)
+  constexpr bool GATHER_A = EPI == EPI_SWIGLU_W;                              // A rows selected by index map (Section 4.2)
+  static_assert(!FOLD || (!FP8 && MODE == ROWSEG && LA == KMAJOR), "the folded order exists for the bf16 row-segmented kernels");
+  constexpr int BN_OUT = SWI ? BN / 2 : BN;
   constexpr int GN = 4, XCDS = 8;
   static_assert(A_BYTES % (1024 * NL) == 0 && B_BYTES % (1024 * NL) == 0, "tile does not split over the loader waves");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * LOADS < 64, "pipeline depth exceeds the vmcnt range");
-  static_assert(EPI != EPI_SWIGLU || TN % 2 == 0, "SwiGLU pairs gate/up MFMA tiles inside a wave");
+  static_assert(!SWI || TN % 2 == 0, "SwiGLU pairs gate/up MFMA tiles inside a wave");
   static_assert(NW <= 8, "LDS is budgeted for at most 8 epilogue patches");
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -413,7 +417,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     if constexpr (PROBE == 3) { m0 = 0; n0 = 0; Bg = static_cast<const char*>(p.B); }      // every tile loads the same panels (all L2 hits)
     // Base of each operand at the tile's first k (wave-uniform) and this lane's fixed byte offset from it.
     // Load j of loader wave lw fills DMA slot q = lw + j*NL of the tile (1 KiB of LDS each).
-    if constexpr (LA == KMAJOR) a_base = uniform_ptr(Ag + ((long)m0 * p.lda + k_begin) * ESZ);
+    if constexpr (GATHER_A) a_base = uniform_ptr(Ag + (long)k_begin * ESZ);          // row offsets are absolute
+    else if constexpr (LA == KMAJOR) a_base = uniform_ptr(Ag + ((long)m0 * p.lda + k_begin) * ESZ);
     else a_base = uniform_ptr(Ag + (long)k_begin * p.lda * ESZ);
     if constexpr (LB == KMAJOR) b_base = uniform_ptr(Bg + (long)k_begin * ESZ);
     else b_base = uniform_ptr(Bg + (long)k_begin * p.ldb * ESZ);
@@ -424,7 +429,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         using TL = KTile<BM, BKT, ESZ>;
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
         const int lc = (lane % TL::CPR) ^ TL::swz(row);
-        const int rel = min(row, p.M - 1 - m0);                       // rows past the end of A repeat its last row
+        int rel = min(row, p.M - 1 - m0);                             // rows past the end of A repeat its last row
+        if constexpr (GATHER_A) rel = p.a_rowmap[m0 + rel];           // < a_phys_rows: the launcher's contract
         a_off[j] = (unsigned)rel * (unsigned)(p.lda * ESZ) + (unsigned)(lc * 16);
         a_k[j] = lc * CHUNK;
       } else {
@@ -444,7 +450,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
         const int lc = (lane % TL::CPR) ^ TL::swz(row);
         int gr;
-        if constexpr (EPI == EPI_SWIGLU) {
+        if constexpr (SWI) {
           const int qq = row >> 5;
           const int n = min(n0 + (qq >> 1) * 32 + (row & 31), p.f - 1);
           gr = (qq & 1) ? p.f + n : n;
@@ -498,11 +504,21 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 #pragma unroll
       for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + j * NL) * 1024u);
     } else {
-      // ragged last step: chunks past the end of the contraction come from the zero block
+      // ragged last step: chunks past the end of the contraction come from the zero block.  The offsets pass
+      // through an empty asm so that their 64-bit extensions are made here, in the cold path, instead of being
+      // kept in register pairs across the whole k loop.
 #pragma unroll
-      for (int j = 0; j < A_DMA; ++j) dma16(a_k[j] >= k_left ? zero : ab + a_off[j], stage + (unsigned)(lw + j * NL) * 1024u);
+      for (int j = 0; j < A_DMA; ++j) {
+        unsigned off = a_off[j];
+        asm volatile("" : "+v"(off));
+        dma16(a_k[j] >= k_left ? zero : ab + off, stage + (unsigned)(lw + j * NL) * 1024u);
+      }
 #pragma unroll
-      for (int j = 0; j < B_DMA; ++j) dma16(b_k[j] >= k_left ? zero : bb + b_off[j], stage + A_BYTES + (unsigned)(lw + j * NL) * 1024u);
+      for (int j = 0; j < B_DMA; ++j) {
+        unsigned off = b_off[j];
+        asm volatile("" : "+v"(off));
+        dma16(b_k[j] >= k_left ? zero : bb + off, stage + A_BYTES + (unsigned)(lw + j * NL) * 1024u);
+      }
     }
   };
   auto issue_prologue = [&]() __attribute__((always_inline)) {
@@ -605,7 +621,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               int n;
-              if constexpr (EPI == EPI_SWIGLU) {
+              if constexpr (SWI) {
                 const int nn = min(n0 + ((wn * WTN + (j & ~1) * 32) >> 1) + q * 8 + lcol, p.f - 4);
                 n = (j & 1) ? p.f + nn : nn;
               } else {
@@ -678,13 +694,15 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
               if (n < p.N) Cg[(long)m * p.ldc + n] = acc[i][j][r] + (p.bias ? p.bias[n] : 0.f);
             }
         }
-      } else if constexpr (EPI == EPI_SWIGLU) {
+      } else if constexpr (SWI) {
         // MFMA tile 2j holds G and tile 2j+1 holds U for the same 32 output columns
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
           const int mb = m0 + wm * WTM + i * 32;
           const int rows_valid = m_end - mb;
           if (rows_valid <= 0) continue;
+          float w_row = 1.0f;                                   // this lane's row is lane % 32 of the block
+          if constexpr (FOLD) w_row = p.row_w[min(mb + (lane & 31), p.M - 1)];
 #pragma unroll
           for (int j = 0; j < TN; j += 2) {
             const int nb = n0 + ((wn * WTN + j * 32) >> 1);
@@ -698,7 +716,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
                 g[q][t] = static_cast<bf16>(acc[i][j][4 * q + t]);
                 u[q][t] = static_cast<bf16>(acc[i][j + 1][4 * q + t]);
                 const float gf = static_cast<float>(g[q][t]);
-                a[q][t] = static_cast<bf16>(gf * sigmoid_f32(gf) * static_cast<float>(u[q][t]));
+                a[q][t] = static_cast<bf16>(w_row * (gf * sigmoid_f32(gf) * static_cast<float>(u[q][t])));
               }
             bf16* hrow = p.H + (long)mb * 2 * p.f + nb;
             stage_store_bf16(stg, g, hrow, 2L * p.f, rows_valid, cols_valid, lane);
@@ -707,25 +725,44 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
           }
         }
       } else {
-        // acc = dA; read G|U, write dG|dU and the recomputed SwiGLU output
+        // acc = dA; read G|U, write dG|dU and the recomputed SwiGLU output.  Folded order (Section 4.1): acc is dA', the
+        // gradient w.r.t. A' = w_r * A.  dG|dU are written for dA' as it is (the row's weight is applied downstream:
+        // once per row in the combine of d_xp and in the rows handed to wgrad1, not per element here), the stored
+        // FC2 input is A', and <dA'[r,:], A[r,:]> over this wave's columns goes to dw_part as one partial sum of the
+        // gate-weight gradient of row r.
         auto swiglu_bwd_block = [&](const f32x16& dacc, const bf16x4 (&g)[4], const bf16x4 (&u)[4], int mb, int nb,
-                                    int rows_valid, int cols_valid) __attribute__((always_inline)) {
+                                    int rows_valid, int cols_valid, float w_row, float& dw_sum) __attribute__((always_inline)) {
           bf16x4 dg[4], du[4], a[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
               const float gf = static_cast<float>(g[q][t]), uf = static_cast<float>(u[q][t]);
-              const float d = static_cast<float>(static_cast<bf16>(dacc[4 * q + t]));
+              float d = static_cast<float>(static_cast<bf16>(dacc[4 * q + t]));
               const float sg = sigmoid_f32(gf);
+              const float av = gf * sg * uf;
+              if constexpr (FOLD) dw_sum += d * av;      // masked G, U are zero: columns past N and rows past the segment add 0
               dg[q][t] = static_cast<bf16>(d * uf * sg * (1.0f + gf * (1.0f - sg)));
               du[q][t] = static_cast<bf16>(d * gf * sg);
-              a[q][t] = static_cast<bf16>(gf * sg * uf);
+              a[q][t] = static_cast<bf16>(FOLD ? w_row * av : av);
             }
           bf16* drow = p.dH + (long)mb * 2 * p.N + nb;
           stage_store_bf16(stg, dg, drow, 2L * p.N, rows_valid, cols_valid, lane);
           stage_store_bf16(stg, du, drow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
           if (p.A_out) stage_store_bf16(stg, a, p.A_out + (long)mb * p.N + nb, p.N, rows_valid, cols_valid, lane);
+        };
+        // lanes l and l + 32 hold the two column halves of row l.  Every row of the expert's segment gets exactly one
+        // partial per (n-tile, wave along n); blocks past N contribute zero.
+        auto row_weight = [&](int i) __attribute__((always_inline)) -> float {
+          if constexpr (FOLD) return p.row_w[min(m0 + wm * WTM + i * 32 + (lane & 31), p.M - 1)];
+          return 1.0f;
+        };
+        auto write_dw = [&](int i, float dw_sum) __attribute__((always_inline)) {
+          if constexpr (FOLD) {
+            const float tot = dw_sum + __shfl_xor(dw_sum, 32);
+            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
+            if (lane < 32 && m < m_end) p.dw_part[(long)((n0 / BN) * WN + wn) * p.M + m] = tot;
+          }
         };
         if constexpr (FP8) {
           // (the e4m3 instantiation has no registers to spare for reading ahead)
@@ -734,6 +771,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             const int mb = m0 + wm * WTM + i * 32;
             const int rows_valid = m_end - mb;
             if (rows_valid <= 0) continue;
+            float dw_sum = 0.f;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
               const int nb = n0 + wn * WTN + j * 32;
@@ -743,11 +781,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
               const bf16* hrow = p.H + (long)mb * 2 * p.N + nb;
               stage_load_bf16(stg, g, hrow, 2L * p.N, rows_valid, cols_valid, lane);
               stage_load_bf16(stg, u, hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
-              swiglu_bwd_block(acc[i][j], g, u, mb, nb, rows_valid, cols_valid);
+              swiglu_bwd_block(acc[i][j], g, u, mb, nb, rows_valid, cols_valid, 1.0f, dw_sum);
             }
           }
         } else {
-          // the G and U reads of block b+1 are issued before block b is processed
+          // The G and U reads of block b+1 are issued as soon as block b has been unpacked from the fetch registers,
+          // so they are in flight while block b is computed and stored (one set of fetch registers: a second set
+          // makes the compiler spill the loaders' tile offsets and reload them inside the k loop).
           constexpr int NB = TM * TN;
           auto block_geom = [&](int b, int& mb, int& nb, int& rows_valid, int& cols_valid) __attribute__((always_inline)) {
             const int i = b / TN, j = b % TN;
@@ -763,18 +803,21 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             fg = stage_fetch_bf16(hrow, 2L * p.N, rows_valid, cols_valid, lane);
             fu = stage_fetch_bf16(hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
           };
-          StageFetch fg[2], fu[2];
-          fetch_block(0, fg[0], fu[0]);
+          StageFetch fg, fu;
+          fetch_block(0, fg, fu);
+          float w_row = 1.0f, dw_sum = 0.f;
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
-            if (b + 1 < NB) fetch_block(b + 1, fg[(b + 1) & 1], fu[(b + 1) & 1]);
+            if (b % TN == 0) { w_row = row_weight(b / TN); dw_sum = 0.f; }
             int mb, nb, rows_valid, cols_valid;
             block_geom(b, mb, nb, rows_valid, cols_valid);
-            if (rows_valid <= 0 || cols_valid <= 0) continue;
             bf16x4 g[4], u[4];
-            stage_unpack_bf16(stg, fg[b & 1], g, lane);
-            stage_unpack_bf16(stg, fu[b & 1], u, lane);
-            swiglu_bwd_block(acc[b / TN][b % TN], g, u, mb, nb, rows_valid, cols_valid);
+            stage_unpack_bf16(stg, fg, g, lane);
+            stage_unpack_bf16(stg, fu, u, lane);
+            if (b + 1 < NB) fetch_block(b + 1, fg, fu);
+            if (rows_valid > 0 && cols_valid > 0)
+              swiglu_bwd_block(acc[b / TN][b % TN], g, u, mb, nb, rows_valid, cols_valid, w_row, dw_sum);
+            if (b % TN == TN - 1) write_dw(b / TN, dw_sum);
           }
         }
       }

@@ -88,6 +88,10 @@ int launch_combine(const void* yp, const float* yp_scale, moe_dtype dt, const in
                    int T, int k, int d, void* y, moe_dtype y_dt, hipStream_t s);
 int launch_gate_grad(const void* dy, moe_dtype dy_dt, const void* yp, const float* yp_scale, moe_dtype dt,
                      const int32_t* inv_perm, int T, int k, int d, float* d_topk_w, hipStream_t s);
+int launch_row_map(const int32_t* perm, const float* topk_w, const int32_t* offsets, int E, int rows, int k,
+                   int32_t* row_token, float* row_w, hipStream_t s);
+int launch_gate_grad_reduce(const float* part, int parts, long ld, const int32_t* inv_perm, int n, float* d_topk_w,
+                            hipStream_t s);
 int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmode mode, uint8_t* codes,
                      float* scales, hipStream_t s);
 int launch_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols, moe_qmode mode, void* dst,
@@ -110,6 +114,12 @@ int mfma_dgrad2_swiglu_bwd(const void* d_yp, const void* w2, const int32_t* offs
                            const void* H, void* dH, void* A_out, hipStream_t s);
 int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int N, int E, void* C, moe_dtype c_dt,
                int accumulate, hipStream_t s);
+// Section 4.1 / 4.2 operator order
+int mfma_fc1_swiglu_gather(const void* x, int T, const int32_t* row_token, const float* row_w, const void* w1,
+                           const int32_t* offsets, int M, int d, int E, int f, void* H, void* A_out, hipStream_t s);
+int mfma_dgrad2_fold_parts(int f);
+int mfma_dgrad2_swiglu_bwd_fold(const void* d_yp, const void* w2, const int32_t* offsets, int M, int d, int E, int f,
+                                const void* H, void* dH, void* A_out, const float* row_w, float* dw_part, hipStream_t s);
 
 int mfma_fc1_swiglu_fp8(const void* xp, const float* xp_scale, const void* w1, const float* w1_scale,
                         const int32_t* offsets, int M, int d, int E, int f, void* H, void* A_out, hipStream_t s);

@@ -211,6 +211,69 @@ int launch_dispatch(const void* x, const float* x_scale, moe_dtype dt, const int
   return MOE_OK;
 }
 
+// ---- Section 4.1 / 4.2 operator order: per-row index map and gate weight; reduction of the gate-gradient partials ----
+
+__global__ void __launch_bounds__(256) row_map_kernel(const int32_t* __restrict__ perm, const float* __restrict__ topk_w,
+                                                      const int32_t* __restrict__ offsets, int E, int rows, int k,
+                                                      int32_t* __restrict__ row_token, float* __restrict__ row_w) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows) return;
+  int tok = 0;
+  float w = 0.f;
+  if (r < offsets[E]) {              // rows past the last segment exist only as padding: token 0, weight 0
+    const int a = perm[r];
+    tok = a / k;
+    w = topk_w[a];
+  }
+  row_token[r] = tok;
+  row_w[r] = w;
+}
+
+// d_topk_w[a] = sum over the parts, in a fixed order, of part[p][inv_perm[a]]; 0 for an assignment without a row.
+// A workgroup handles 64 assignments; its four waves each add a quarter of the parts (unrolled, so the loads of one
+// wave are in flight together), then wave 0 adds the four quarters in ascending order.
+__global__ void __launch_bounds__(256) gate_grad_reduce_kernel(const float* __restrict__ part, int parts, long ld,
+                                                               const int32_t* __restrict__ inv_perm, int n,
+                                                               float* __restrict__ d_topk_w) {
+  __shared__ float quarter[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int a = blockIdx.x * 64 + lane;
+  const int r = a < n ? inv_perm[a] : -1;
+  const int per = (parts + 3) / 4;
+  const int p0 = q * per, p1 = min(parts, p0 + per);
+  float acc = 0.f;
+  if (r >= 0) {
+    int p = p0;
+    for (; p + 8 <= p1; p += 8) {
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = part[(long)(p + i) * ld + r];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc += v[i];
+    }
+    for (; p < p1; ++p) acc += part[(long)p * ld + r];
+  }
+  quarter[q][lane] = acc;
+  __syncthreads();
+  if (q == 0 && a < n) d_topk_w[a] = ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
+}
+
+int launch_row_map(const int32_t* perm, const float* topk_w, const int32_t* offsets, int E, int rows, int k,
+                   int32_t* row_token, float* row_w, hipStream_t s) {
+  if (rows == 0) return MOE_OK;
+  row_map_kernel<<<dim3((unsigned)cdiv(rows, 256)), dim3(256), 0, s>>>(perm, topk_w, offsets, E, rows, k, row_token, row_w);
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
+int launch_gate_grad_reduce(const float* part, int parts, long ld, const int32_t* inv_perm, int n, float* d_topk_w,
+                            hipStream_t s) {
+  if (n == 0) return MOE_OK;
+  gate_grad_reduce_kernel<<<dim3((unsigned)cdiv(n, 64)), dim3(256), 0, s>>>(part, parts, ld, inv_perm, n, d_topk_w);
+  MOE_LAUNCH_CHECK();
+  return MOE_OK;
+}
+
 int launch_combine(const void* yp, const float* yp_scale, moe_dtype dt, const int32_t* inv_perm, const float* topk_w,
                    int T, int k, int d, void* y, moe_dtype y_dt, hipStream_t s) {
   const dim3 grid(row_grid(T)), block(64 * kWavesPerBlock);

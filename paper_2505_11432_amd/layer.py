@@ -14,8 +14,12 @@ from . import binding as B
 class MoELayer:
     def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype=torch.bfloat16, renorm: int = 1,
                  fp8: bool = False, grad_dtype=torch.float32, device="cuda:0", expert_range=None, capacity=None,
-                 balance=None):
-        """expert_range = (e_lo, e_hi): this GPU's expert-parallel share (Section 3.2): x holds the all-gathered
+                 balance=None, fused: bool = False):
+        """fused = True: the Section 4.1 / 4.2 operator order (bf16): FC1 selects its rows from x through the index
+        map, the gate weight is applied right after SwiGLU, the combine is unweighted, the gate gradient comes out
+        of the dgrad2 epilogue; neither the dispatched input nor the FC2 output is kept for the backward.
+
+        expert_range = (e_lo, e_hi): this GPU's expert-parallel share (Section 3.2): x holds the all-gathered
         tokens, only rows routed to experts e_lo..e_hi-1 are dispatched, w1/w2 and their gradients hold those
         experts only, and y / dx are the partial sums over them.  Row buffers keep the bound T*k."""
         self.T, self.d, self.E, self.k, self.f = T, d, E, k, f
@@ -42,7 +46,6 @@ class MoELayer:
         self.inv_perm = torch.empty((M,), **i32)
         self.h_save = torch.empty((M, 2 * f), **act)
         self.y = torch.empty((T, d), **act)
-        self.d_yp = torch.empty((M, d), **act)
         self.d_topk_w = torch.empty((T, k), **f32)
         self.d_xp = torch.empty((M, d), **act)
         self.dx = torch.empty((T, d), **act)
@@ -66,9 +69,13 @@ class MoELayer:
             self.dy_codes = torch.empty((T, d), **u8)
             self.dy_scale = torch.empty(((T + 127) // 128, d), **f32)
             self.dy_deq = torch.empty((T, d), **act)
+        elif fused:
+            self.yp = torch.empty((M, d), **act)        # transient: FC2 output -> combine; not needed by the backward
         else:
             self.xp = torch.empty((M, d), **act)
             self.yp = torch.empty((M, d), **act)
+        if not fused:
+            self.d_yp = torch.empty((M, d), **act)
         if capacity is not None:
             self.score = torch.empty((T, k), **f32)
             self.route_ws = torch.empty((B.moe_route_capacity_workspace_bytes(T, E, k),), dtype=torch.uint8, **dev)
@@ -76,6 +83,12 @@ class MoELayer:
             self.aux_loss = torch.zeros((1,), **f32)
             self.group_f = torch.empty((balance[0],), **f32)
             self.group_p = torch.empty((balance[0],), **f32)
+        self.fused = fused
+        if fused:
+            assert not fp8 and dtype == torch.bfloat16, "the fused operator order exists for bf16"
+            self.row_token = torch.empty((M,), **i32)
+            self.row_w = torch.empty((M,), **f32)
+            self.fused_ws = torch.empty((B.moe_expert_ffn_fused_workspace_bytes(T, k, d, f),), dtype=torch.uint8, **dev)
         self.timers = None      # set to a dict to collect (start, end) event pairs per call name
         code = B.F8E4M3 if fp8 else B.dtype_code(dtype)
         nbytes = B.moe_workspace_bytes(T, d, E, k, f, code)
@@ -227,6 +240,12 @@ class MoELayer:
         else:
             c("route", B.moe_route_range, self.logits, self.k, self.renorm, self.expert_range[0], self.expert_range[1],
               self.topk_idx, self.topk_w, self.counts, self.offsets, self.perm, self.inv_perm, self.workspace)
+        if self.fused:
+            c("row_map", B.moe_row_map, self.perm, self.topk_w, self.offsets, self.row_token, self.row_w)
+            c("expert_ffn_fwd", B.moe_expert_ffn_fused_fwd, x, self.row_token, self.row_w, self.offsets, w1, w2, self.k,
+              self.h_save, self.yp, self.fused_ws)
+            c("combine", B.moe_combine, self.yp, None, self.inv_perm, None, self.k, self.y)
+            return self.y
         c("dispatch", B.moe_dispatch, x, None, self.inv_perm, None, self.k, self.xp, None)
         c("expert_ffn_fwd", B.moe_expert_ffn_fwd, self.xp, None, self.offsets, w1, None, w2, None, self.h_save,
           self.yp, None, self.workspace)
@@ -236,12 +255,18 @@ class MoELayer:
     # ---- backward: Fig. 8b -----------------------------------------------------------------
     def backward(self, x, w_r, w1, w2, dy, with_router: bool = True):
         c = self._call
-        c("gate_grad", B.moe_gate_grad, dy, self.yp, None, self.inv_perm, self.k, self.d_topk_w)
-        c("dispatch_bwd_of_combine", B.moe_dispatch, dy, None, self.inv_perm, self.topk_w.view(-1), self.k,
-          self.d_yp, None)
-        c("expert_ffn_bwd", B.moe_expert_ffn_bwd, self.xp, self.h_save, self.d_yp, None, self.offsets, w1, w2,
-          self.d_xp, self.d_w1, self.d_w2, 0, self.workspace)
-        c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, None, self.k, self.dx)
+        if self.fused:
+            c("expert_ffn_bwd", B.moe_expert_ffn_fused_bwd, x, dy, self.h_save, self.inv_perm, self.topk_w, self.row_w,
+              self.offsets, w1, w2, self.k, self.d_xp, self.d_w1, self.d_w2, 0, self.d_topk_w, self.fused_ws)
+        else:
+            c("gate_grad", B.moe_gate_grad, dy, self.yp, None, self.inv_perm, self.k, self.d_topk_w)
+            c("dispatch_bwd_of_combine", B.moe_dispatch, dy, None, self.inv_perm, self.topk_w.view(-1), self.k,
+              self.d_yp, None)
+            c("expert_ffn_bwd", B.moe_expert_ffn_bwd, self.xp, self.h_save, self.d_yp, None, self.offsets, w1, w2,
+              self.d_xp, self.d_w1, self.d_w2, 0, self.workspace)
+        # fused order: d_xp comes without the gate weight, which this combine applies once per row
+        c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, self.topk_w if self.fused else None,
+          self.k, self.dx)
         c("route_bwd", B.moe_route_bwd, self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E,
           self.renorm, self.d_logits)
         if self.balance is not None:

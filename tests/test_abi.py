@@ -145,3 +145,30 @@ def test_route_range_capacity_balance_argument_errors_without_gpu(lib):
     assert lib.moe_balance_loss_bwd(fake, fake, 64, 8, 5, F(0.1), fake, null) == -1
     assert lib.moe_balance_loss_bwd(fake, null, 64, 8, 4, F(0.1), fake, null) == -1
     assert lib.moe_balance_loss_bwd(null, null, 0, 8, 4, F(0.1), null, null) == 0
+
+
+def test_fused_order_argument_errors_without_gpu(lib):
+    P, Z, I = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+    null, fake = P(0), P(4096)
+    lib.moe_expert_ffn_fused_workspace_bytes.restype = Z
+    need = lib.moe_expert_ffn_fused_workspace_bytes(64, 2, 128, 256)
+    # A' + dH + one [M,d] buffer + gate-gradient partials + split-K scratch
+    assert need >= 128 * 256 * 2 + 128 * 512 * 2 + 128 * 128 * 2 + 4 * 128 * 4 + 256 * 256 * 256 * 4
+    assert lib.moe_expert_ffn_fused_workspace_bytes(64, 0, 128, 256) == 0
+    lib.moe_row_map.argtypes = [P, P, P, I, I, I, P, P, P]
+    assert lib.moe_row_map(fake, fake, fake, 8, 64, 2, fake, null, null) == -1
+    assert lib.moe_row_map(fake, fake, fake, 300, 64, 2, fake, fake, null) == -1
+    assert lib.moe_row_map(null, null, null, 8, 0, 2, null, null, null) == 0
+    lib.moe_expert_ffn_fused_fwd.argtypes = [P, P, P, P, P, P, I, I, I, I, I, P, P, P, Z, P]
+    fwd = lambda x, d, ws, n: lib.moe_expert_ffn_fused_fwd(x, fake, fake, fake, fake, fake, 64, 2, d, 8, 256, fake, fake, ws, Z(n), null)
+    assert fwd(null, 128, fake, need) == -1
+    assert fwd(fake, 120, fake, need) == -2          # d must be a multiple of 16
+    assert fwd(fake, 128, fake, need - 1) == -3
+    assert fwd(P(4100), 128, fake, need) == -2       # 16-byte alignment
+    lib.moe_expert_ffn_fused_bwd.argtypes = [P, P, P, P, P, P, P, P, P, I, I, I, I, I, P, P, P, I, I, P, P, Z, P]
+    bwd = lambda dy, gdt, dw, n: lib.moe_expert_ffn_fused_bwd(fake, dy, fake, fake, fake, fake, fake, fake, fake, 64, 2, 128, 8, 256,
+                                                              fake, fake, fake, gdt, 0, dw, fake, Z(n), null)
+    assert bwd(null, 0, fake, need) == -1
+    assert bwd(fake, 2, fake, need) == -2            # weight gradients are fp32 or bf16
+    assert bwd(fake, 0, null, need) == -1
+    assert bwd(fake, 0, fake, need - 1) == -3

@@ -666,3 +666,90 @@ def test_layer_with_capacity_and_balance_loss(B):
             "dW1": max_norm_err(to_np(layer.d_w1), bwd["dW1"]), "dW2": max_norm_err(to_np(layer.d_w2), bwd["dW2"])}
     bad = {k_: v for k_, v in errs.items() if not v < tol}
     assert not bad, bad
+
+
+# ---- Section 4.1 / 4.2 operator order: row select inside FC1, gate weight after SwiGLU, gate gradient from dgrad2 ----
+def _fused_layer(cfg, inp, z, td, expert_range=None, with_router=True):
+    from paper_2505_11432_amd.layer import MoELayer
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, renorm=cfg.renorm, expert_range=expert_range, fused=True)
+    lo, hi = expert_range if expert_range else (0, cfg.E)
+    x, dy, wr = to_dev(inp["x"], td), to_dev(inp["dy"], td), to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"][lo:hi], td), to_dev(inp["W2"][lo:hi], td)
+    for t in (layer.yp, layer.d_xp, layer.h_save):
+        t.fill_(float("nan"))                                    # rows past the last segment must never be read
+    layer.fused_ws.view(torch.int16).fill_(0x7fc0)               # bf16 NaN in every intermediate as well
+    layer.d_w1.fill_(7.0)
+    layer.d_w2.fill_(7.0)
+    layer.forward(x, wr, None, w1, w2, logits=to_dev(z))
+    layer.backward(x, wr, w1, w2, dy, with_router=with_router)
+    torch.cuda.synchronize()
+    return layer
+
+
+@pytest.mark.parametrize("cfg", SMALL_BF16, ids=lambda c: c.name)
+def test_layer_fused_order(B, cfg):
+    """Every result against the plain layer of the oracle (the reordering changes no value, only rounding), the
+    kept and returned intermediates against the oracle's statement of the reordered operators."""
+    inp = make_inputs(cfg, seed=1)
+    z = O.router_logits(inp["x"], inp["W_r"], inp["bias"]).astype(np.float32)
+    if cfg.name == "ragged":
+        z[:, 4] = -1e4
+        z[:, 2] -= 4.0
+    layer = _fused_layer(cfg, inp, z, torch.bfloat16)
+    fwd = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k, cfg.renorm)
+    bwd = O.layer_bwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k, inp["dy"], fwd, cfg.renorm, W_r=inp["W_r"])
+    for name, got in (("idx", layer.topk_idx), ("offsets", layer.offsets), ("perm", layer.perm), ("inv_perm", layer.inv_perm)):
+        assert np.array_equal(to_np(got), fwd[name]), name
+    # the index map and the per-row weights are copies: bit-exact
+    assert np.array_equal(to_np(layer.row_token), O.row_tokens(fwd["perm"], cfg.k))
+    assert np.array_equal(to_np(layer.row_w), to_np(layer.topk_w).reshape(-1)[fwd["perm"]])
+    fold = O.layer_fwd_folded(inp["x"], fwd, inp["W1"], inp["W2"], cfg.k)
+    fb = O.layer_bwd_folded(inp["x"], inp["W1"], inp["W2"], cfg.k, inp["dy"], fold)
+    tol = TOL["bf16"]
+    errs = {"H": max_norm_err(to_np(layer.h_save), fwd["H"]), "Yw": max_norm_err(to_np(layer.yp), fold["Yw"]),
+            "y": max_norm_err(to_np(layer.y), fwd["y"]), "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]),
+            "dxp0": max_norm_err(to_np(layer.d_xp), fb["dxp0"]), "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
+            "dz": max_norm_err(to_np(layer.d_logits), bwd["dz"]), "dW_r": max_norm_err(to_np(layer.d_w_r), bwd["dW_r"].T)}
+    dW1, dW2 = to_np(layer.d_w1), to_np(layer.d_w2)
+    for e in range(cfg.E):
+        if fwd["counts"][e] == 0:
+            assert np.all(dW1[e] == 0) and np.all(dW2[e] == 0)
+        else:
+            errs[f"dW1[{e}]"] = max_norm_err(dW1[e], bwd["dW1"][e])
+            errs[f"dW2[{e}]"] = max_norm_err(dW2[e], bwd["dW2"][e])
+    bad = {k_: v for k_, v in errs.items() if not v < tol}
+    assert not bad, bad
+    # the gate gradient is a fixed-order sum: a second backward reproduces it bit for bit
+    first = layer.d_topk_w.clone()
+    td = torch.bfloat16
+    layer.backward(to_dev(inp["x"], td), to_dev(inp["W_r"].T, td), to_dev(inp["W1"], td), to_dev(inp["W2"], td),
+                   to_dev(inp["dy"], td), with_router=False)
+    torch.cuda.synchronize()
+    assert torch.equal(first, layer.d_topk_w)
+
+
+def test_layer_fused_order_expert_parallel_share(B):
+    cfg = MoEConfig("ep_fused", T=520, d=128, E=12, k=3, f=160, dtype="bf16", w_std=0.09, wr_std=0.6)
+    inp = make_inputs(cfg, seed=6)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    z[:, 7] = -1e4
+    lo, hi = 5, 9
+    layer = _fused_layer(cfg, inp, z, torch.bfloat16, expert_range=(lo, hi), with_router=False)
+    fwd = O.layer_fwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, lo, hi)
+    bwd = O.layer_bwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, inp["dy"], fwd)
+    n = int(fwd["offsets"][-1])
+    assert np.array_equal(to_np(layer.inv_perm), fwd["inv_perm"])
+    assert np.array_equal(to_np(layer.row_token)[:n], O.row_tokens(fwd["perm"][:n], cfg.k))
+    assert np.all(to_np(layer.row_token)[n:] == 0) and np.all(to_np(layer.row_w)[n:] == 0)
+    errs = {"H": max_norm_err(to_np(layer.h_save)[:n], fwd["H"][:n]), "y": max_norm_err(to_np(layer.y), fwd["y"]),
+            "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]), "dx": max_norm_err(to_np(layer.dx), bwd["dx"])}
+    dW1, dW2 = to_np(layer.d_w1), to_np(layer.d_w2)
+    for e in range(hi - lo):
+        if fwd["counts"][lo + e] == 0:
+            assert np.all(dW1[e] == 0) and np.all(dW2[e] == 0)
+        else:
+            errs[f"dW1[{lo + e}]"] = max_norm_err(dW1[e], bwd["dW1"][e])
+            errs[f"dW2[{lo + e}]"] = max_norm_err(dW2[e], bwd["dW2"][e])
+    assert np.all(to_np(layer.d_topk_w)[(fwd["idx"] < lo) | (fwd["idx"] >= hi)] == 0)
+    bad = {k_: v for k_, v in errs.items() if not v < TOL["bf16"]}
+    assert not bad, bad

@@ -264,7 +264,8 @@ def test_folded_order_equals_the_plain_layer(variant):
     for key in ("dw", "dx", "dW1", "dW2"):
         np.testing.assert_allclose(fb[key], pb[key], rtol=0, atol=1e-11, err_msg=key)
     np.testing.assert_allclose(fb["dxp"][:M], pb["dxp"][:M], rtol=0, atol=1e-11)
-    np.testing.assert_allclose(fb["dH"][:M], pb["dH"][:M], rtol=0, atol=1e-11)
+    np.testing.assert_allclose(fb["dH0"][:M] * fold["row_w"][:, None], pb["dH"][:M], rtol=0, atol=1e-11)
+    np.testing.assert_allclose(fb["dxp0"][:M] * fold["row_w"][:, None], pb["dxp"][:M], rtol=0, atol=1e-11)
 
 
 def test_folded_gate_gradient_by_finite_differences():
