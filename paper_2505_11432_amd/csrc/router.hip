@@ -11,62 +11,82 @@ namespace moe {
 namespace {
 
 constexpr int kETile = 64;        // experts per register tile
-constexpr int kSlabCols = 512;    // 256 threads x 2 columns
 
-template <typename T> struct Pair;
-template <> struct Pair<float> { __device__ static float2 load(const float* p) { return *reinterpret_cast<const float2*>(p); } };
-template <> struct Pair<bf16> {
-  __device__ static float2 load(const bf16* p) {
-    const unsigned u = *reinterpret_cast<const unsigned*>(p);
-    return make_float2(__builtin_bit_cast(float, u << 16), __builtin_bit_cast(float, u & 0xffff0000u));
+// COLS consecutive elements of a row as fp32 (COLS * sizeof(T) bytes in one load)
+template <typename T, int COLS> struct RowChunk {
+  __device__ static void load(const T* p, float (&out)[COLS]) {
+    struct alignas(COLS * sizeof(T)) Raw { T v[COLS]; };
+    const Raw r = *reinterpret_cast<const Raw*>(p);
+#pragma unroll
+    for (int i = 0; i < COLS; ++i) out[i] = to_f32(r.v[i]);
   }
 };
 
 // partial[chunk][e][col] = sum over the chunk's tokens of d_logits[t][e] * x[t][col].
-// The chunk's gate gradients (up to 128 tokens x 64 experts) are staged in LDS once and read back as
-// broadcasts, so the inner loop is one LDS read per four FMAs and the kernel is FMA-bound.
-constexpr int kChunkTokens = 128;
+// A block owns 256 * COLS columns of x and one chunk of tokens; a thread keeps ETILE x COLS fp32 sums.  The
+// chunk's gate gradients (up to 64 tokens x ETILE experts) are staged in LDS and read back as broadcasts.
+// ETILE is the smallest of 8 / 16 / 32 / 64 that holds E (more than 64 experts: passes of 64), so that few
+// experts do not pay for 64: with ETILE = 8 the kernel is bound by reading x, not by FMAs.
+constexpr int kChunkTokens = 64;
+constexpr int kTokUnroll = 8;         // rows of x in flight per thread
 
-template <typename T>
+template <typename T, int ETILE, int COLS>
 __global__ void __launch_bounds__(256) router_dwr_partial_kernel(const T* __restrict__ x,
                                                                  const float* __restrict__ d_logits, int Tn, int d,
                                                                  int E, int tokens_per_chunk,
                                                                  float* __restrict__ partial) {
-  __shared__ __attribute__((aligned(16))) float g_lds[kChunkTokens][kETile];
-  const int slabs = (d + kSlabCols - 1) / kSlabCols;
+  __shared__ __attribute__((aligned(16))) float g_lds[kChunkTokens][ETILE];
+  constexpr int kSlab = 256 * COLS;
+  const int slabs = (d + kSlab - 1) / kSlab;
   const int slab = blockIdx.x % slabs, chunk = blockIdx.x / slabs;
-  const int col = slab * kSlabCols + threadIdx.x * 2;
+  const int col = slab * kSlab + threadIdx.x * COLS;
   const int t0 = chunk * tokens_per_chunk, t1 = min(t0 + tokens_per_chunk, Tn);
-  const bool active = col < d;
-  for (int e0 = 0; e0 < E; e0 += kETile) {
-    float2 acc[kETile];
+  const bool active = col < d;                 // d is a multiple of 16 >= COLS: a chunk is inside the row or outside
+  for (int e0 = 0; e0 < E; e0 += ETILE) {
+    float acc[ETILE][COLS];
 #pragma unroll
-    for (int i = 0; i < kETile; ++i) acc[i] = make_float2(0.f, 0.f);
-    for (int ts = t0; ts < t1; ts += kChunkTokens) {          // 128 tokens at a time through LDS
+    for (int i = 0; i < ETILE; ++i)
+#pragma unroll
+      for (int c = 0; c < COLS; ++c) acc[i][c] = 0.f;
+    for (int ts = t0; ts < t1; ts += kChunkTokens) {
       const int te = min(ts + kChunkTokens, t1);
       __syncthreads();
-      for (int i = threadIdx.x; i < (te - ts) * kETile; i += 256) {
-        const int tt = i / kETile, ee = i % kETile;
-        g_lds[tt][ee] = (e0 + ee < E) ? d_logits[(long)(ts + tt) * E + e0 + ee] : 0.f;
+      for (int i = threadIdx.x; i < kChunkTokens * ETILE; i += 256) {
+        const int tt = i / ETILE, ee = i % ETILE;
+        g_lds[tt][ee] = (ts + tt < te && e0 + ee < E) ? d_logits[(long)(ts + tt) * E + e0 + ee] : 0.f;   // zero rows past the chunk
       }
       __syncthreads();
-      for (int t = ts; t < te; ++t) {
-        const float2 xv = active ? Pair<T>::load(x + (long)t * d + col) : make_float2(0.f, 0.f);
-        const float4* g = reinterpret_cast<const float4*>(g_lds[t - ts]);
+      if (!active) continue;
+      for (int tb = ts; tb < te; tb += kTokUnroll) {
+        float xv[kTokUnroll][COLS];
 #pragma unroll
-        for (int i = 0; i < kETile / 4; ++i) {
-          const float4 gv = g[i];
-          acc[4 * i + 0].x = fmaf(gv.x, xv.x, acc[4 * i + 0].x); acc[4 * i + 0].y = fmaf(gv.x, xv.y, acc[4 * i + 0].y);
-          acc[4 * i + 1].x = fmaf(gv.y, xv.x, acc[4 * i + 1].x); acc[4 * i + 1].y = fmaf(gv.y, xv.y, acc[4 * i + 1].y);
-          acc[4 * i + 2].x = fmaf(gv.z, xv.x, acc[4 * i + 2].x); acc[4 * i + 2].y = fmaf(gv.z, xv.y, acc[4 * i + 2].y);
-          acc[4 * i + 3].x = fmaf(gv.w, xv.x, acc[4 * i + 3].x); acc[4 * i + 3].y = fmaf(gv.w, xv.y, acc[4 * i + 3].y);
+        for (int u = 0; u < kTokUnroll; ++u) RowChunk<T, COLS>::load(x + (long)min(tb + u, Tn - 1) * d + col, xv[u]);
+#pragma unroll
+        for (int u = 0; u < kTokUnroll; ++u) {
+          // rows past the chunk's end multiply zeros (tb + u - ts < kChunkTokens: both are multiples of 8 apart)
+          const float4* g = reinterpret_cast<const float4*>(g_lds[tb + u - ts]);
+#pragma unroll
+          for (int i = 0; i < ETILE / 4; ++i) {
+            const float4 gv = g[i];
+#pragma unroll
+            for (int c = 0; c < COLS; ++c) {
+              acc[4 * i + 0][c] = fmaf(gv.x, xv[u][c], acc[4 * i + 0][c]);
+              acc[4 * i + 1][c] = fmaf(gv.y, xv[u][c], acc[4 * i + 1][c]);
+              acc[4 * i + 2][c] = fmaf(gv.z, xv[u][c], acc[4 * i + 2][c]);
+              acc[4 * i + 3][c] = fmaf(gv.w, xv[u][c], acc[4 * i + 3][c]);
+            }
+          }
         }
       }
     }
     if (active) {
 #pragma unroll
-      for (int i = 0; i < kETile; ++i)
-        if (e0 + i < E) *reinterpret_cast<float2*>(partial + ((long)chunk * E + e0 + i) * d + col) = acc[i];
+      for (int i = 0; i < ETILE; ++i)
+        if (e0 + i < E) {
+          float* dst = partial + ((long)chunk * E + e0 + i) * d + col;
+#pragma unroll
+          for (int c = 0; c < COLS; ++c) dst[c] = acc[i][c];
+        }
     }
   }
 }
@@ -183,12 +203,21 @@ int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe
   if (d_w_r) {
     const int chunks = dwr_chunks(T);
     const int tpc = dwr_tokens_per_chunk(T);
-    const int slabs = cdiv(d, kSlabCols);
     float* partial = static_cast<float*>(ws);
-    if (dt == MOE_F32)
-      router_dwr_partial_kernel<float><<<slabs * chunks, 256, 0, s>>>((const float*)x, d_logits, T, d, E, tpc, partial);
-    else
-      router_dwr_partial_kernel<bf16><<<slabs * chunks, 256, 0, s>>>((const bf16*)x, d_logits, T, d, E, tpc, partial);
+#define MOE_DWR_CASE(TT, ET, CO)                                                                                    \
+  router_dwr_partial_kernel<TT, ET, CO><<<cdiv(d, 256 * CO) * chunks, 256, 0, s>>>((const TT*)x, d_logits, T, d, E, tpc, partial)
+    if (dt == MOE_F32) {
+      if (E <= 8) MOE_DWR_CASE(float, 8, 4);
+      else if (E <= 16) MOE_DWR_CASE(float, 16, 4);
+      else if (E <= 32) MOE_DWR_CASE(float, 32, 2);
+      else MOE_DWR_CASE(float, 64, 2);
+    } else {
+      if (E <= 8) MOE_DWR_CASE(bf16, 8, 4);
+      else if (E <= 16) MOE_DWR_CASE(bf16, 16, 4);
+      else if (E <= 32) MOE_DWR_CASE(bf16, 32, 2);
+      else MOE_DWR_CASE(bf16, 64, 2);
+    }
+#undef MOE_DWR_CASE
     MOE_LAUNCH_CHECK();
     const long n = (long)E * d;
     long blocks = (n + 255) / 256;

@@ -308,3 +308,69 @@ def test_full_size_expert_parallel_share():
     print("ep352b_share", {k_: f"{v:.2e}" for k_, v in errs.items()})
     bad = {k_: v for k_, v in errs.items() if not v < TOL}
     assert not bad, bad
+
+
+@pytest.mark.parametrize("name", ["mixtral", "skewed"])
+def test_full_size_fused_order_sampled(name):
+    """The Section 4.1 / 4.2 operator order at the benchmark sizes (bench.py --fused): routing and the row map in
+    full and bit-exact, every row-local tensor of 192 sampled tokens and weight-gradient slices against the oracle."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = CONFIGS[name]
+    inp = make_inputs(cfg, seed=0)
+    T, k, d, f, E = cfg.T, cfg.k, cfg.d, cfg.f, cfg.E
+    layer = MoELayer(T, d, E, k, f, dtype=torch.bfloat16, renorm=cfg.renorm, fused=True)
+    x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
+    w_r = dev_bf16(np.ascontiguousarray(inp["W_r"].T))
+    bias = torch.from_numpy(inp["bias"]).to(DEV)
+    w1, w2 = dev_bf16(inp["W1"]), dev_bf16(inp["W2"])
+    layer.forward(x, w_r, bias, w1, w2)
+    layer.backward(x, w_r, w1, w2, dy)
+    torch.cuda.synchronize()
+    z = layer.logits.cpu().numpy()
+    r = O.route(z, k, cfg.renorm)
+    for nm, got in (("idx", layer.topk_idx), ("offsets", layer.offsets), ("perm", layer.perm), ("inv_perm", layer.inv_perm)):
+        assert np.array_equal(to_np(got), r[nm]), nm
+    assert np.array_equal(to_np(layer.row_token), O.row_tokens(r["perm"], k))
+    assert np.array_equal(to_np(layer.row_w), to_np(layer.topk_w).reshape(-1)[r["perm"]])
+
+    rng = np.random.default_rng(11)
+    toks = np.sort(rng.choice(T, size=192, replace=False))
+    a_ids = (toks[:, None] * k + np.arange(k)[None, :]).reshape(-1)
+    rows = r["inv_perm"][a_ids].astype(np.int64)
+    e_of = r["idx"].reshape(-1)[a_ids]
+    order = np.argsort(e_of, kind="stable")
+    rows_s, e_s, a_s = rows[order], e_of[order], a_ids[order]
+    offs = np.concatenate([[0], np.cumsum(np.bincount(e_s, minlength=E))]).astype(np.int32)
+    tok_s, w_s = a_s // k, r["w"].reshape(-1)[a_s]
+    H, Aw, Yw = O.expert_ffn_fwd_folded(inp["x"], tok_s, w_s, offs, inp["W1"], inp["W2"])
+    dxp_s, _, _, _, drw_s, dxp0_s = O.expert_ffn_bwd_folded(inp["x"], inp["dy"], tok_s, w_s, H, offs, inp["W1"], inp["W2"])
+    rows_t = torch.from_numpy(rows_s).to(DEV)
+    errs = {"H": max_norm_err(to_np(layer.h_save[rows_t]), H), "Yw": max_norm_err(to_np(layer.yp[rows_t]), Yw),
+            "dxp0": max_norm_err(to_np(layer.d_xp[rows_t]), dxp0_s)}
+    back = np.empty_like(order)
+    back[order] = np.arange(order.size)
+    y_ref = Yw[back].reshape(len(toks), k, d).sum(axis=1)
+    dw_ref = drw_s[back].reshape(len(toks), k)
+    dz_ref = O.route_bwd(z[toks], r["idx"][toks], r["w"][toks], dw_ref, cfg.renorm)
+    dx_ref = dxp_s[back].reshape(len(toks), k, d).sum(axis=1) + dz_ref @ inp["W_r"].astype(np.float64).T
+    tt = torch.from_numpy(toks).to(DEV)
+    errs["y"] = max_norm_err(to_np(layer.y[tt]), y_ref)
+    errs["dw"] = max_norm_err(to_np(layer.d_topk_w[tt]), dw_ref)
+    errs["dx"] = max_norm_err(to_np(layer.dx[tt]), dx_ref)
+
+    nonempty = np.flatnonzero(r["counts"] > 0)
+    pick = {int(nonempty[np.argmax(r["counts"][nonempty])]), int(nonempty[np.argmin(r["counts"][nonempty])])}
+    for e in sorted(pick):
+        lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
+        j0 = int(rng.integers(0, f // 64)) * 64
+        sl = np.r_[j0:j0 + 64, f + j0:f + j0 + 64]
+        W1s, W2s = inp["W1"][e:e + 1, sl, :], inp["W2"][e:e + 1, :, j0:j0 + 64]
+        a_e = r["perm"][lo:hi].astype(np.int64)
+        off_e = np.array([0, hi - lo], dtype=np.int32)
+        H_e, _, _ = O.expert_ffn_fwd_folded(inp["x"], a_e // k, r["w"].reshape(-1)[a_e], off_e, W1s, W2s)
+        _, dW1s, dW2s, _, _, _ = O.expert_ffn_bwd_folded(inp["x"], inp["dy"], a_e // k, r["w"].reshape(-1)[a_e], H_e, off_e, W1s, W2s)
+        errs[f"dW1[{e}] ({hi - lo} rows)"] = max_norm_err(to_np(layer.d_w1[e][torch.from_numpy(sl).to(DEV)]), dW1s[0])
+        errs[f"dW2[{e}] ({hi - lo} rows)"] = max_norm_err(to_np(layer.d_w2[e][:, j0:j0 + 64]), dW2s[0])
+    print(name, "fused", {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < TOL}
+    assert not bad, bad
