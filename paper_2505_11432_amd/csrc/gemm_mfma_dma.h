@@ -609,32 +609,30 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     {
       const int e = ep_e, m0 = ep_m0, m_end = ep_m_end, n0 = ep_n0;
       (void)e;
-      if constexpr (FP8 && !BSCALE) {
-        // dequantise: output = acc * scale of the row (token) * scale of the output channel
-        const int lrow = lane & 31, lcol = (lane >> 5) << 2;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
+      // e4m3 operands with per-row / per-output-channel scales: output = acc * scale of the row (token) * scale of
+      // the output channel, applied block by block right before a block is written, so that only one block's 16
+      // channel scales are live at a time
+      auto dequant_block = [&](int i, int j) __attribute__((always_inline)) {
+        if constexpr (FP8 && !BSCALE) {
+          const int lrow = lane & 31, lcol = (lane >> 5) << 2;
           const int m = min(m0 + wm * WTM + i * 32 + lrow, p.M - 1);
           const float rs = p.row_scale ? p.row_scale[m] : 1.f;
 #pragma unroll
-          for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              int n;
-              if constexpr (SWI) {
-                const int nn = min(n0 + ((wn * WTN + (j & ~1) * 32) >> 1) + q * 8 + lcol, p.f - 4);
-                n = (j & 1) ? p.f + nn : nn;
-              } else {
-                n = min(n0 + wn * WTN + j * 32 + q * 8 + lcol, p.N - 4);
-              }
-              f32x4 cs = {1.f, 1.f, 1.f, 1.f};
-              if (p.col_scale) cs = *reinterpret_cast<const f32x4*>(p.col_scale + (long)e * p.cs_es + n);
-#pragma unroll
-              for (int t = 0; t < 4; ++t) acc[i][j][4 * q + t] *= rs * cs[t];
+          for (int q = 0; q < 4; ++q) {
+            int n;
+            if constexpr (SWI) {
+              const int nn = min(n0 + ((wn * WTN + (j & ~1) * 32) >> 1) + q * 8 + lcol, p.f - 4);
+              n = (j & 1) ? p.f + nn : nn;
+            } else {
+              n = min(n0 + wn * WTN + j * 32 + q * 8 + lcol, p.N - 4);
             }
+            f32x4 cs = {1.f, 1.f, 1.f, 1.f};
+            if (p.col_scale) cs = *reinterpret_cast<const f32x4*>(p.col_scale + (long)e * p.cs_es + n);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[i][j][4 * q + t] *= rs * cs[t];
           }
         }
-      }
+      };
       // every 32x32 MFMA tile goes through the wave's LDS patch (see stage_store_* above)
       if (SPLITK && ep_part_slot >= 0) {
         // one K part of a split tile: the whole fp32 tile goes to the partial buffer, no masks
@@ -642,8 +640,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
+          for (int j = 0; j < TN; ++j) {
+            dequant_block(i, j);
             stage_store_f32(stg, acc[i][j], part_tile + (long)(wm * WTM + i * 32) * BN + wn * WTN + j * 32, BN, 32, 32, false, lane);
+          }
       } else if constexpr (EPI == EPI_STORE) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -655,6 +655,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             const int nb = n0 + wn * WTN + j * 32;
             const int cols_valid = p.N - nb;
             if (cols_valid <= 0) continue;
+            dequant_block(i, j);
             if constexpr (sizeof(TC) == 4) {
               float* g = static_cast<float*>(p.C) + (long)e * p.c_es + (long)mb * p.ldc + nb;
               stage_store_f32(stg, acc[i][j], g, p.ldc, rows_valid, cols_valid, p.accumulate != 0, lane);
@@ -708,6 +709,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             const int nb = n0 + ((wn * WTN + j * 32) >> 1);
             const int cols_valid = p.f - nb;
             if (cols_valid <= 0) continue;
+            dequant_block(i, j);
+            dequant_block(i, j + 1);
             bf16x4 g[4], u[4], a[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q)
@@ -781,6 +784,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
               const bf16* hrow = p.H + (long)mb * 2 * p.N + nb;
               stage_load_bf16(stg, g, hrow, 2L * p.N, rows_valid, cols_valid, lane);
               stage_load_bf16(stg, u, hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
+              dequant_block(i, j);
               swiglu_bwd_block(acc[i][j], g, u, mb, nb, rows_valid, cols_valid, 1.0f, dw_sum);
             }
           }
