@@ -285,8 +285,8 @@ typedef struct moe_ffn_bwd_fp8_args {
   /* inputs */
   const void* d_yp;            /* [M,d]  bf16: gradient of the FC2 output (already gate-weighted) */
   const void* h_save;          /* [M,2f] bf16: [G|U] kept by the forward */
-  const void* xp_deq;          /* [M,d]  bf16: the dispatched activations FC1 consumed, dequantised */
-  const void* a_deq;           /* [M,f]  bf16: the FC2 input the forward consumed, dequantised */
+  const void* xp_deq;          /* [M,d]  bf16: the dispatched activations FC1 consumed, dequantised (or xp_codes below) */
+  const void* a_deq;           /* [M,f]  bf16: the FC2 input the forward consumed, dequantised (or a_codes below) */
   const int32_t* offsets;      /* [E+1] */
   const uint8_t* w1t;          /* [E,d,2f] e4m3 codes of W1[e]^T */
   const float* w1t_scale;      /* [E,d] */
@@ -312,6 +312,11 @@ typedef struct moe_ffn_bwd_fp8_args {
   void* splitk_ws;                        /* MOE_SPLITK_WS_BYTES of scratch, or NULL: lets the d_xp GEMM split the
                                              tiles of a partly filled last round along K (faster, same result up
                                              to fp32 summation order) */
+  /* optional inputs: the e4m3 codes and per-row scales the forward consumed.  When xp_codes
+   * (a_codes) is given, the weight-gradient operand is cast from code * scale (one fp32
+   * rounding) and xp_deq (a_deq) is not read and may be NULL. */
+  const uint8_t* xp_codes; const float* xp_scale;   /* [M,d], [M] */
+  const uint8_t* a_codes;  const float* a_scale;    /* [M,f], [M] */
 } moe_ffn_bwd_fp8_args;
 #define MOE_SPLITK_WS_BYTES ((size_t)256 * 256 * 256 * 4)
 int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* args, void* stream);

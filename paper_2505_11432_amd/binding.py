@@ -40,6 +40,7 @@ class FfnBwdFp8Args(ctypes.Structure):
         + [(n, c_void_p) for n in ("dy_codes", "dy_scale", "dh", "dh_codes", "dh_scale", "pad_offsets")]
         + [("ldt", ctypes.c_long)]
         + [(n, c_void_p) for n in ("dy_t", "dy_e8m0", "dh_t", "dh_e8m0", "a_t", "a_e8m0", "x_t", "x_e8m0", "splitk_ws")]
+        + [(n, c_void_p) for n in ("xp_codes", "xp_scale", "a_codes", "a_scale")]
     )
 
 
@@ -227,9 +228,17 @@ def moe_quant_fp8_tgroup(src, offsets, pad_offsets, codes_t, e8m0):
 
 def moe_expert_ffn_bwd_fp8(d_yp, h_save, xp_deq, a_deq, offsets, w1t, w1t_scale, w2t, w2t_scale, d_xp, d_w1, d_w2,
                            accumulate, inter):
-    """`inter` maps the names of the intermediate buffers of moe_ffn_bwd_fp8_args to tensors."""
+    """`inter` maps the names of the intermediate buffers of moe_ffn_bwd_fp8_args to tensors; xp_deq / a_deq may
+    instead be (codes, scales) pairs of the forward's e4m3 operands."""
     M, d = d_yp.shape
-    f = a_deq.shape[1]
+    codes = {}
+    if isinstance(xp_deq, tuple):
+        codes["xp_codes"], codes["xp_scale"] = xp_deq
+        xp_deq = None
+    if isinstance(a_deq, tuple):
+        codes["a_codes"], codes["a_scale"] = a_deq
+        a_deq = None
+    f = h_save.shape[1] // 2
     a = FfnBwdFp8Args()
     for name, t in (("d_yp", d_yp), ("h_save", h_save), ("xp_deq", xp_deq), ("a_deq", a_deq), ("offsets", offsets),
                     ("w1t", w1t), ("w1t_scale", w1t_scale), ("w2t", w2t), ("w2t_scale", w2t_scale), ("d_xp", d_xp),
@@ -239,6 +248,8 @@ def moe_expert_ffn_bwd_fp8(d_yp, h_save, xp_deq, a_deq, offsets, w1t, w1t_scale,
                  "dh_e8m0", "a_t", "a_e8m0", "x_t", "x_e8m0"):
         setattr(a, name, _p(inter[name]))
     a.splitk_ws = _p(inter.get("splitk_ws"))
+    for name, t in codes.items():
+        setattr(a, name, _p(t))
     a.M, a.d, a.E, a.f = M, d, offsets.numel() - 1, f
     a.grad_dt = dtype_code(d_w1.dtype)
     a.accumulate = int(accumulate)

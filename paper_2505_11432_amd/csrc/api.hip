@@ -517,7 +517,7 @@ int moe_quant_fp8_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, 
   if (!aligned16(src) || !aligned16(codes_t)) return MOE_ERR_UNSUPPORTED;
   int rc = launch_tgroup_offsets(offsets, E, pad_offsets, as_stream(stream));
   if (rc != MOE_OK) return rc;
-  return launch_quant_tgroup(src, src_dt, rows, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, as_stream(stream));
+  return launch_quant_tgroup(src, nullptr, src_dt, rows, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, as_stream(stream));
 }
 
 int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* a, void* stream) {
@@ -527,7 +527,12 @@ int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* a, void* stream) {
   if (d % 16 != 0 || f % 16 != 0) return MOE_ERR_UNSUPPORTED;
   if (a->grad_dt != MOE_F32 && a->grad_dt != MOE_BF16) return MOE_ERR_UNSUPPORTED;
   if (a->ldt % 128 != 0 || a->ldt < (long)moe_tgroup_tokens(M, E)) return MOE_ERR_INVALID;
-  const void* ptrs[] = {a->d_yp, a->h_save, a->xp_deq, a->a_deq, a->offsets, a->w1t, a->w1t_scale, a->w2t, a->w2t_scale,
+  // the two forward operands: dequantised bf16 copies, or the codes and per-row scales themselves
+  const bool x_codes = a->xp_codes != nullptr, a_codes = a->a_codes != nullptr;
+  if (x_codes ? !a->xp_scale : !a->xp_deq) return MOE_ERR_INVALID;
+  if (a_codes ? !a->a_scale : !a->a_deq) return MOE_ERR_INVALID;
+  if (!aligned16(a->xp_codes) || !aligned16(a->a_codes)) return MOE_ERR_UNSUPPORTED;
+  const void* ptrs[] = {a->d_yp, a->h_save, a->offsets, a->w1t, a->w1t_scale, a->w2t, a->w2t_scale,
                         a->d_xp, a->d_w1, a->d_w2, a->dy_codes, a->dy_scale, a->dh, a->dh_codes, a->dh_scale,
                         a->pad_offsets, a->dy_t, a->dy_e8m0, a->dh_t, a->dh_e8m0, a->a_t, a->a_e8m0, a->x_t, a->x_e8m0};
   for (const void* q : ptrs)
@@ -550,15 +555,17 @@ int moe_expert_ffn_bwd_fp8(const moe_ffn_bwd_fp8_args* a, void* stream) {
   if (rc != MOE_OK) return rc;
   rc = launch_tgroup_offsets(a->offsets, E, a->pad_offsets, s);
   if (rc != MOE_OK) return rc;
-  rc = launch_quant_tgroup(a->d_yp, MOE_BF16, M, d, a->offsets, a->pad_offsets, E, a->dy_t, a->ldt, a->dy_e8m0, s);
+  rc = launch_quant_tgroup(a->d_yp, nullptr, MOE_BF16, M, d, a->offsets, a->pad_offsets, E, a->dy_t, a->ldt, a->dy_e8m0, s);
   if (rc != MOE_OK) return rc;
-  rc = launch_quant_tgroup(a->a_deq, MOE_BF16, M, f, a->offsets, a->pad_offsets, E, a->a_t, a->ldt, a->a_e8m0, s);
+  rc = a_codes ? launch_quant_tgroup(a->a_codes, a->a_scale, MOE_F8E4M3, M, f, a->offsets, a->pad_offsets, E, a->a_t, a->ldt, a->a_e8m0, s)
+               : launch_quant_tgroup(a->a_deq, nullptr, MOE_BF16, M, f, a->offsets, a->pad_offsets, E, a->a_t, a->ldt, a->a_e8m0, s);
   if (rc != MOE_OK) return rc;
   rc = mfma_wgrad_fp8(a->dy_t, a->dy_e8m0, a->a_t, a->a_e8m0, a->ldt, a->pad_offsets, d, f, E, a->d_w2, a->grad_dt, acc, s);
   if (rc != MOE_OK) return rc;
-  rc = launch_quant_tgroup(a->dh, MOE_BF16, M, 2 * f, a->offsets, a->pad_offsets, E, a->dh_t, a->ldt, a->dh_e8m0, s);
+  rc = launch_quant_tgroup(a->dh, nullptr, MOE_BF16, M, 2 * f, a->offsets, a->pad_offsets, E, a->dh_t, a->ldt, a->dh_e8m0, s);
   if (rc != MOE_OK) return rc;
-  rc = launch_quant_tgroup(a->xp_deq, MOE_BF16, M, d, a->offsets, a->pad_offsets, E, a->x_t, a->ldt, a->x_e8m0, s);
+  rc = x_codes ? launch_quant_tgroup(a->xp_codes, a->xp_scale, MOE_F8E4M3, M, d, a->offsets, a->pad_offsets, E, a->x_t, a->ldt, a->x_e8m0, s)
+               : launch_quant_tgroup(a->xp_deq, nullptr, MOE_BF16, M, d, a->offsets, a->pad_offsets, E, a->x_t, a->ldt, a->x_e8m0, s);
   if (rc != MOE_OK) return rc;
   return mfma_wgrad_fp8(a->dh_t, a->dh_e8m0, a->x_t, a->x_e8m0, a->ldt, a->pad_offsets, 2 * f, d, E, a->d_w1, a->grad_dt, acc, s);
 }

@@ -97,7 +97,8 @@ int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_
 int launch_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols, moe_qmode mode, void* dst,
                        moe_dtype dst_dt, hipStream_t s);
 int launch_tgroup_offsets(const int32_t* offsets, int E, int32_t* pad_offsets, hipStream_t s);
-int launch_quant_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, const int32_t* offsets,
+// src_dt = MOE_F8E4M3: src holds e4m3 codes with one scale per row (src_row_scale [rows]); NULL otherwise
+int launch_quant_tgroup(const void* src, const float* src_row_scale, moe_dtype src_dt, int rows, int cols, const int32_t* offsets,
                         const int32_t* pad_offsets, int E, uint8_t* codes_t, long ldt, uint8_t* e8m0, hipStream_t s);
 
 // bf16 grouped GEMMs on the matrix cores (gemm_mfma.hip)

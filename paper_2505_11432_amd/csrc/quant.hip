@@ -167,7 +167,8 @@ __global__ void tgroup_offsets_kernel(const int32_t* __restrict__ offsets, int E
 // of four channels; channel maxima go through LDS; the codes are transposed through LDS so that global
 // memory sees 16-byte lanes forming 128-byte rows (one channel x 128 tokens).
 template <typename T>
-__global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__ src, int cols,
+__global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__ src,
+                                                           const float* __restrict__ src_row_scale, int cols,
                                                            const int32_t* __restrict__ offsets,
                                                            const int32_t* __restrict__ pad_offsets, int E,
                                                            uint8_t* __restrict__ codes_t, long ldt,
@@ -198,11 +199,20 @@ __global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__
     for (int j = 0; j < 4; ++j) v[i][j] = 0.f;
     if (col_ok && r < r_end) {
       const T* p = src + (long)r * cols + c;
+      if constexpr (sizeof(T) == 1) {
+        // e4m3 codes with one scale per source row: the value is code * scale, rounded once to fp32
+        const int w = *reinterpret_cast<const int*>(p);
+        const float rs = src_row_scale[r];
+        v[i][0] = __builtin_amdgcn_cvt_f32_fp8(w, 0) * rs;
+        v[i][1] = __builtin_amdgcn_cvt_f32_fp8(w, 1) * rs;
+        v[i][2] = __builtin_amdgcn_cvt_f32_fp8(w, 2) * rs;
+        v[i][3] = __builtin_amdgcn_cvt_f32_fp8(w, 3) * rs;
+      } else {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        v[i][j] = to_f32(p[j]);
-        amax[j] = fmaxf(amax[j], fabsf(v[i][j]));
+        for (int j = 0; j < 4; ++j) v[i][j] = to_f32(p[j]);
       }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) amax[j] = fmaxf(amax[j], fabsf(v[i][j]));
     }
   }
 #pragma unroll
@@ -295,7 +305,7 @@ int launch_tgroup_offsets(const int32_t* offsets, int E, int32_t* pad_offsets, h
   return MOE_OK;
 }
 
-int launch_quant_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, const int32_t* offsets,
+int launch_quant_tgroup(const void* src, const float* src_row_scale, moe_dtype src_dt, int rows, int cols, const int32_t* offsets,
                         const int32_t* pad_offsets, int E, uint8_t* codes_t, long ldt, uint8_t* e8m0, hipStream_t s) {
   if (cols == 0) return MOE_OK;
   const int slabs = cdiv(cols, 64);
@@ -303,9 +313,11 @@ int launch_quant_tgroup(const void* src, moe_dtype src_dt, int rows, int cols, c
   const long grid = (long)groups * slabs;
   if (grid <= 0 || grid > 0x7fffffffL) return MOE_ERR_UNSUPPORTED;
   if (src_dt == MOE_F32)
-    quant_tgroup_kernel<float><<<(int)grid, 256, 0, s>>>((const float*)src, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, slabs);
+    quant_tgroup_kernel<float><<<(int)grid, 256, 0, s>>>((const float*)src, nullptr, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, slabs);
+  else if (src_dt == MOE_BF16)
+    quant_tgroup_kernel<bf16><<<(int)grid, 256, 0, s>>>((const bf16*)src, nullptr, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, slabs);
   else
-    quant_tgroup_kernel<bf16><<<(int)grid, 256, 0, s>>>((const bf16*)src, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, slabs);
+    quant_tgroup_kernel<uint8_t><<<(int)grid, 256, 0, s>>>((const uint8_t*)src, src_row_scale, cols, offsets, pad_offsets, E, codes_t, ldt, e8m0, slabs);
   MOE_LAUNCH_CHECK();
   return MOE_OK;
 }

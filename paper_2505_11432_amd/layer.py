@@ -165,10 +165,9 @@ class MoELayer:
         c("gate_grad", B.moe_gate_grad, self.dy_deq, self.yp, self.yp_scale, self.inv_perm, self.k, self.d_topk_w)
         c("dispatch_bwd_of_combine", B.moe_dispatch, self.dy_deq, None, self.inv_perm, self.topk_w.view(-1), self.k,
           self.d_yp, None)
-        c("dequant_xp", B.moe_dequant_fp8, self.xp, self.xp_scale, B.Q_ROW, self.xp_deq)
-        c("dequant_a", B.moe_dequant_fp8, self.a_codes, self.a_scale, B.Q_ROW, self.a_deq)
-        c("expert_ffn_bwd", B.moe_expert_ffn_bwd_fp8, self.d_yp, self.h_save, self.xp_deq, self.a_deq, self.offsets,
-          self.w1t_codes, self.w1t_scale, self.w2t_codes, self.w2t_scale, self.d_xp, self.d_w1, self.d_w2, 0, self.bwd8)
+        # the weight-gradient casts read the forward's codes and per-row scales directly (no dequantised copies)
+        c("expert_ffn_bwd", B.moe_expert_ffn_bwd_fp8, self.d_yp, self.h_save, (self.xp, self.xp_scale),
+          (self.a_codes, self.a_scale), self.offsets, self.w1t_codes, self.w1t_scale, self.w2t_codes, self.w2t_scale, self.d_xp, self.d_w1, self.d_w2, 0, self.bwd8)
         c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, None, self.k, self.dx)
         c("route_bwd", B.moe_route_bwd, self.logits, self.topk_idx, self.topk_w, self.d_topk_w, self.E,
           self.renorm, self.d_logits)

@@ -215,8 +215,11 @@ def test_full_size_fp8_forward_and_fp8_backward_sampled():
     assert np.array_equal(po, np.concatenate([[0], np.cumsum((np.diff(offsets) + 127) // 128 * 128)]))
     allr = np.arange(layer.M)
 
-    def tg_slice(src_t, name, cols):
-        src = g(src_t, allr, cols).astype(np.float32)
+    def tg_slice(src_t, name, cols, row_scale=None):
+        src = g(src_t, allr, cols)
+        if row_scale is not None:          # e4m3 codes with per-row scales: code * scale, rounded once to fp32
+            src = O.e4m3_decode(src).astype(np.float32) * to_np(row_scale).astype(np.float32)[:, None]
+        src = src.astype(np.float32)
         c_ref, k_ref = O.quant_tokengroup_pow2(src, offsets)
         ct = g(I[name + "_t"], cols)                                   # [len(cols), ldt]
         e8 = to_np(I[name + "_e8m0"][:, torch.as_tensor(cols, device=DEV)]).astype(np.int64)
@@ -231,9 +234,9 @@ def test_full_size_fp8_forward_and_fp8_backward_sampled():
         return O.dequant_tokengroup_pow2(c_ref, k_ref, offsets)
 
     dy_g = tg_slice(layer.d_yp, "dy", cd)
-    a_g = tg_slice(layer.a_deq, "a", cf)
+    a_g = tg_slice(layer.a_codes, "a", cf, layer.a_scale)
     dh_g = tg_slice(I["dh"], "dh", hcols)
-    x_g = tg_slice(layer.xp_deq, "x", cd)
+    x_g = tg_slice(layer.xp, "x", cd, layer.xp_scale)
     for e in (0, 3, E - 1):
         lo, hi = offsets[e], offsets[e + 1]
         errs[f"dW2[{e}]"] = max_norm_err(g(layer.d_w2[e], cd, cf), dy_g[lo:hi].T @ a_g[lo:hi])

@@ -475,7 +475,10 @@ def test_layer_fp8_backward_gemms(B, cfg):
     errs["dxp"] = max_norm_err(to_np(layer.d_xp), dxp)
     # (5) token-group casts of the four wgrad operands: bit-exact, padded and transposed as documented
     deq = {}
-    for name, src in (("dy", dyp), ("dh", I["dh"]), ("a", to_np(layer.a_deq)), ("x", to_np(layer.xp_deq))):
+    # the forward's operands enter as code * per-row scale, rounded once to fp32 (the kernel's arithmetic)
+    a_src = (O.e4m3_decode(to_np(layer.a_codes)).astype(np.float32) * to_np(layer.a_scale).astype(np.float32)[:, None])
+    x_src = (O.e4m3_decode(to_np(layer.xp)).astype(np.float32) * to_np(layer.xp_scale).astype(np.float32)[:, None])
+    for name, src in (("dy", dyp), ("dh", I["dh"]), ("a", a_src), ("x", x_src)):
         c_ref, k_ref = _check_tgroup(I[name + "_t"], I[name + "_e8m0"], I["pad_offsets"], src.astype(np.float32), offsets)
         deq[name] = O.dequant_tokengroup_pow2(c_ref, k_ref, offsets)
     # (6) the weight gradients on those codes
