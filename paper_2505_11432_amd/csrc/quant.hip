@@ -12,6 +12,7 @@ namespace moe {
 namespace {
 
 constexpr float kE4M3Max = 448.0f;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float clamp448(float p) { return fminf(fmaxf(p, -kE4M3Max), kE4M3Max); }
 
@@ -38,12 +39,11 @@ __device__ __forceinline__ float block_max(float v, float* red) {
 // One block per row.  A row of up to THREADS x 8 vectors stays in registers between the amax pass and the
 // convert pass, so HBM sees each element once (256 threads: 16384 bf16 columns; 1024 threads, used for wider
 // rows: 65536); longer rows are read a second time (from L2).
-template <typename T, int THREADS>
+template <typename T, int THREADS, int kHold = 8>
 __global__ void __launch_bounds__(THREADS) quant_rows_kernel(const T* __restrict__ src, int rows, int cols,
                                                              uint8_t* __restrict__ codes, float* __restrict__ scales) {
   __shared__ float red[THREADS / 64];
   constexpr int V = 16 / sizeof(T);
-  constexpr int kHold = 8;                       // vectors held per thread
   const int nvec = cols / V;
   const bool in_regs = nvec <= THREADS * kHold;
   for (int r = blockIdx.x; r < rows; r += gridDim.x) {
@@ -51,15 +51,18 @@ __global__ void __launch_bounds__(THREADS) quant_rows_kernel(const T* __restrict
     Vec16<T> hold[kHold];
     float amax = 0.f;
     if (in_regs) {
+      // every load is issued before the first value is used; vectors past the row's end re-read its last vector
+      // (same maximum, never stored), which keeps the loads unconditional
 #pragma unroll
       for (int h = 0; h < kHold; ++h) {
-        const int c = threadIdx.x + h * THREADS;
-        if (c < nvec) {
-          hold[h] = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
-#pragma unroll
-          for (int i = 0; i < V; ++i) amax = fmaxf(amax, fabsf(to_f32(hold[h].v[i])));
-        }
+        const int c = min((int)threadIdx.x + h * THREADS, nvec - 1);
+        // streamed once: non-temporal
+        hold[h] = __builtin_bit_cast(Vec16<T>, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + (long)c * V)));
       }
+#pragma unroll
+      for (int h = 0; h < kHold; ++h)
+#pragma unroll
+        for (int i = 0; i < V; ++i) amax = fmaxf(amax, fabsf(to_f32(hold[h].v[i])));
     } else {
       for (int c = threadIdx.x; c < nvec; c += THREADS) {
         const Vec16<T> v = *reinterpret_cast<const Vec16<T>*>(row + (long)c * V);
@@ -76,14 +79,22 @@ __global__ void __launch_bounds__(THREADS) quant_rows_kernel(const T* __restrict
       for (int i = 0; i < V / 4; ++i)
         out[i] = pack4_e4m3(to_f32(v.v[4 * i]) * inv, to_f32(v.v[4 * i + 1]) * inv, to_f32(v.v[4 * i + 2]) * inv,
                             to_f32(v.v[4 * i + 3]) * inv);
-      unsigned* dst = reinterpret_cast<unsigned*>(codes + (long)r * cols + (long)c * V);
-#pragma unroll
-      for (int i = 0; i < V / 4; ++i) dst[i] = out[i];
+      uint8_t* dst = codes + (long)r * cols + (long)c * V;           // V bytes, V-byte aligned: one store
+      typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+      if constexpr (V == 8) { const u32x2 o = {out[0], out[1]}; __builtin_nontemporal_store(o, reinterpret_cast<u32x2*>(dst)); }
+      else __builtin_nontemporal_store(out[0], reinterpret_cast<unsigned*>(dst));
     };
     if (in_regs) {
 #pragma unroll
       for (int h = 0; h < kHold; ++h) {
         const int c = threadIdx.x + h * THREADS;
+        {
+          // keep the row as the 16 raw bytes per vector between the two passes: without this the compiler holds
+          // the fp32 values it made for the amax pass (4x the registers)
+          u32x4 raw = __builtin_bit_cast(u32x4, hold[h]);
+          asm volatile("" : "+v"(raw));
+          hold[h] = __builtin_bit_cast(Vec16<T>, raw);
+        }
         if (c < nvec) convert(hold[h], c);
       }
     } else {
@@ -286,7 +297,9 @@ int launch_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_
       if (wide) quant_rows_kernel<float, 1024><<<grid, 1024, 0, s>>>((const float*)src, rows, cols, codes, scales);
       else quant_rows_kernel<float, 256><<<grid, 256, 0, s>>>((const float*)src, rows, cols, codes, scales);
     } else {
-      if (wide) quant_rows_kernel<bf16, 1024><<<grid, 1024, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
+      const int nvec = cols / 8;
+      if (wide && nvec <= 256 * 16) quant_rows_kernel<bf16, 256, 16><<<rows < 256 * 64 ? rows : 256 * 64, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
+      else if (wide) quant_rows_kernel<bf16, 1024><<<grid, 1024, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
       else quant_rows_kernel<bf16, 256><<<grid, 256, 0, s>>>((const bf16*)src, rows, cols, codes, scales);
     }
   } else {
