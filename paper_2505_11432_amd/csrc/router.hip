@@ -91,13 +91,27 @@ __global__ void __launch_bounds__(256) router_dwr_partial_kernel(const T* __rest
   }
 }
 
+// d_w_r[i] = sum over the chunks of partial[c][i] in a fixed order: a block owns 64 outputs, its four waves each add
+// every fourth chunk (ascending), then the four sums are added in wave order.
 __global__ void __launch_bounds__(256) router_dwr_reduce_kernel(const float* __restrict__ partial, int chunks,
                                                                 long n /* = E*d */, float* __restrict__ d_w_r) {
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-    float s = 0.f;
-    for (int c = 0; c < chunks; ++c) s += partial[(long)c * n + i];
-    d_w_r[i] = s;
+  __shared__ float part[4][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const long i = (long)blockIdx.x * 64 + lane;
+  float s = 0.f;
+  if (i < n) {
+    int c = q;
+    for (; c + 12 < chunks; c += 16) {
+      const float v0 = partial[(long)c * n + i], v1 = partial[(long)(c + 4) * n + i];
+      const float v2 = partial[(long)(c + 8) * n + i], v3 = partial[(long)(c + 12) * n + i];
+      s = ((s + v0) + v1) + v2;
+      s += v3;
+    }
+    for (; c < chunks; c += 4) s += partial[(long)c * n + i];
   }
+  part[q][lane] = s;
+  __syncthreads();
+  if (q == 0 && i < n) d_w_r[i] = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
 }
 
 // dx[t, cols] += sum_e d_logits[t][e] * w_r[e][cols].  A block owns a slab of 512 columns (64 lanes x 8) and
@@ -220,8 +234,7 @@ int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe
 #undef MOE_DWR_CASE
     MOE_LAUNCH_CHECK();
     const long n = (long)E * d;
-    long blocks = (n + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
+    const long blocks = (n + 63) / 64;
     router_dwr_reduce_kernel<<<(int)blocks, 256, 0, s>>>(partial, chunks, n, d_w_r);
     MOE_LAUNCH_CHECK();
   }
