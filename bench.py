@@ -45,6 +45,9 @@ def parse():
                     help="bf16 only: the paper's Section 4.1 / 4.2 operator order (FC1 selects its rows from x inside the "
                          "kernel, gate weight after SwiGLU, gate gradient from the dgrad2 epilogue, no dispatched input "
                          "or FC2 output kept for the backward)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time K replays of one HIP graph holding the whole step (forward + backward) instead of K eager "
+                         "steps; the per-call times and the roofline figure then come from an extra eager pass of K steps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size reference for HBM byte counters")
     return ap.parse_args()
@@ -168,15 +171,31 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    layer.timers = {}
     start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    start.record()
-    for _ in range(args.steps):
-        step()
-    end.record()
-    torch.cuda.synchronize()
-    total_ms = start.elapsed_time(end)
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(args.steps):
+            graph.replay()
+        end.record()
+        torch.cuda.synchronize()
+        total_ms = start.elapsed_time(end)
+        layer.timers = {}
+        for _ in range(args.steps):
+            step()
+    else:
+        layer.timers = {}
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(args.steps):
+            step()
+        end.record()
+        torch.cuda.synchronize()
+        total_ms = start.elapsed_time(end)
     per_call = {k: v / args.steps for k, v in layer.timer_ms().items()}
     layer.timers = None
     ms_per_step = total_ms / args.steps
@@ -228,6 +247,7 @@ def main():
                      "peak": PEAK_HBM_GBPS},
         "ms_per_call": per_call,
         "setup_s": setup_s,
+        "launch": "one HIP graph per step" if args.graph else "eager",
     }
     if not args.no_cpu_baseline:
         tokens = args.cpu_tokens or max(cfg.T // 8, 1)

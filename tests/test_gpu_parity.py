@@ -756,3 +756,38 @@ def test_layer_fused_order_expert_parallel_share(B):
     assert np.all(to_np(layer.d_topk_w)[(fwd["idx"] < lo) | (fwd["idx"] >= hi)] == 0)
     bad = {k_: v for k_, v in errs.items() if not v < TOL["bf16"]}
     assert not bad, bad
+
+
+# ---- the whole step under HIP graph capture: every call only enqueues on the stream -------------------------------
+@pytest.mark.parametrize("fused", [False, True])
+def test_layer_step_replays_from_a_hip_graph(B, fused):
+    """Forward + backward captured once into a HIP graph and replayed three times, with eager work and
+    synchronisations between the replays: every replay must reproduce the eager step bit for bit (all kernels are
+    deterministic, nothing in the library allocates, synchronises or reads back)."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = SMALL_BF16[0]
+    inp = make_inputs(cfg, seed=4)
+    td = torch.bfloat16
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, renorm=cfg.renorm, fused=fused)
+    x, dy, wr = to_dev(inp["x"], td), to_dev(inp["dy"], td), to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"], td), to_dev(inp["W2"], td)
+
+    def step():
+        layer.forward(x, wr, None, w1, w2)
+        layer.backward(x, wr, w1, w2, dy)
+
+    outs = ("y", "dx", "d_w1", "d_w2", "d_w_r", "d_logits", "inv_perm")
+    step()                                        # eager: also configures every kernel before the capture
+    torch.cuda.synchronize()
+    ref = {n: getattr(layer, n).clone() for n in outs}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for n in outs:
+            getattr(layer, n).fill_(0)            # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in outs:
+            assert torch.equal(getattr(layer, n), ref[n]), (rep, n)
