@@ -791,3 +791,38 @@ def test_layer_step_replays_from_a_hip_graph(B, fused):
         torch.cuda.synchronize()
         for n in outs:
             assert torch.equal(getattr(layer, n), ref[n]), (rep, n)
+
+
+def test_layer_fused_order_with_capacity_and_balance_loss(B):
+    """The fused operator order on a route with dropped assignments (device-level capacity) and the auxiliary loss."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = MoEConfig("cap_fused", T=600, d=128, E=8, k=2, f=160, dtype="bf16", w_std=0.09, wr_std=0.6)
+    inp = make_inputs(cfg, seed=8)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    z[:, 0] += 1.0
+    G, cap, alpha = 4, 260, 0.02
+    td = torch.bfloat16
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, capacity=(G, cap), balance=(G, alpha), fused=True)
+    x, dy, wr = to_dev(inp["x"], td), to_dev(inp["dy"], td), to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"], td), to_dev(inp["W2"], td)
+    for t in (layer.yp, layer.d_xp, layer.h_save):
+        t.fill_(float("nan"))
+    layer.fused_ws.view(torch.int16).fill_(0x7fc0)
+    layer.forward(x, wr, None, w1, w2, logits=to_dev(z))
+    layer.backward(x, wr, w1, w2, dy, with_router=False)
+    torch.cuda.synchronize()
+    r = O.route_capacity(z, cfg.k, G, cap, score=to_np(layer.score).astype(np.float32))
+    assert 0 < (~r["keep"]).sum() < cfg.T * cfg.k
+    assert np.array_equal(to_np(layer.inv_perm), r["inv_perm"]) and np.array_equal(to_np(layer.offsets), r["offsets"])
+    fwd = O.layer_fwd_routed(inp["x"], r, inp["W1"], inp["W2"], cfg.k)
+    bwd = O.layer_bwd_routed(inp["x"], inp["W1"], inp["W2"], cfg.k, inp["dy"], fwd)
+    n = int(r["offsets"][-1])
+    full = O.route(z, cfg.k)
+    dz_ref = O.route_bwd(z, r["idx"], r["w"], bwd["dw"]) + O.balance_loss_bwd(z, full["idx"], G, alpha)
+    errs = {"H": max_norm_err(to_np(layer.h_save)[:n], fwd["H"]), "y": max_norm_err(to_np(layer.y), fwd["y"]),
+            "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]), "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
+            "dz": max_norm_err(to_np(layer.d_logits), dz_ref),
+            "dW1": max_norm_err(to_np(layer.d_w1), bwd["dW1"]), "dW2": max_norm_err(to_np(layer.d_w2), bwd["dW2"])}
+    assert np.all(to_np(layer.d_topk_w)[~r["keep"]] == 0)
+    bad = {k_: v for k_, v in errs.items() if not v < TOL["bf16"]}
+    assert not bad, bad
