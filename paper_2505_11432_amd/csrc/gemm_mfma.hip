@@ -217,8 +217,11 @@ int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, in
   a.B = (const bf16*)w_r; a.ldb = d; a.b_es = 0;
   a.C = logits; a.ldc = E; a.E = 1; a.M = T; a.N = E; a.K = d; a.bias = bias;
   const long mt = cdiv(T, 256);
-  if (E <= 32) return launch<256, 32, 64, 2, 4, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, mt, s);
-  if (E <= 64) return launch<256, 64, 64, 2, 4, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, mt, s);
+  // Few experts: the GEMM is a stream over x with almost no arithmetic, so what matters is how many workgroups pull
+  // on memory and how deep each one's pipeline is: 64-row tiles (four times the workgroups) with an 8-stage ring
+  // halve the time of 256-row tiles with two stages (cfg 2: 59 -> 30 us).
+  if (E <= 32) return launch<64, 32, 64, 8, 2, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, cdiv(T, 64), s);
+  if (E <= 64) return launch<64, 64, 64, 8, 2, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, cdiv(T, 64), s);
   return launch<256, 128, 64, 2, 4, 2, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, mt * cdiv(E, 128), s);
 }
 
