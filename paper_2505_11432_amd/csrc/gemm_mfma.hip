@@ -54,8 +54,8 @@ int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
   MOE_LAUNCH_CHECK();
   if constexpr (kSplitK) {
     if (args.splitk_ws != nullptr) {
-      // one workgroup per tile of the partly filled last round (fewer than `blocks`); the others return at once
-      splitk_fixup_kernel<BM, BN><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(args.splitk_ws, args.offsets, args.E, args.N, blocks,
+      // four workgroups per tile of the partly filled last round (fewer than `blocks` tiles); the others return at once
+      splitk_fixup_kernel<BM, BN><<<dim3((unsigned)blocks * 4), dim3(256), 0, s>>>(args.splitk_ws, args.offsets, args.E, args.N, blocks,
                                                                               static_cast<bf16*>(args.C), args.ldc);
       MOE_LAUNCH_CHECK();
     }

@@ -205,8 +205,8 @@ __host__ __device__ __forceinline__ void splitk_plan(int total_tiles, int workgr
   total_items = full_tiles + (total_tiles - full_tiles) * split;
 }
 
-// Adds the K parts of every split tile and writes the bf16 result with the tile's row / column masks.  One
-// workgroup per split tile; the tile list is rebuilt exactly as in the GEMM kernel (same grouping constants).
+// Adds the K parts of every split tile and writes the bf16 result with the tile's row / column masks.  Four
+// workgroups per split tile; the tile list is rebuilt exactly as in the GEMM kernel (same grouping constants).
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) splitk_fixup_kernel(const float* __restrict__ parts, const int32_t* __restrict__ offsets,
                                                            int E, int N, int gemm_workgroups, bf16* __restrict__ C, long ldc) {
@@ -225,7 +225,8 @@ __global__ void __launch_bounds__(256) splitk_fixup_kernel(const float* __restri
   const int total_tiles = cum_tiles[E] * tiles_n;
   int full_tiles, split, total_items;
   splitk_plan(total_tiles, gemm_workgroups, full_tiles, split, total_items);
-  const int r_tile = blockIdx.x;
+  constexpr int SLICES = 4;                          // workgroups per split tile (each takes BM / SLICES rows)
+  const int r_tile = blockIdx.x / SLICES, slice = blockIdx.x % SLICES;
   if (split == 1 || r_tile >= total_tiles - full_tiles) return;
   int l = full_tiles + r_tile;
   int lo = 0, hi = E;
@@ -243,8 +244,8 @@ __global__ void __launch_bounds__(256) splitk_fixup_kernel(const float* __restri
   const int nt = ng * GN + (r - mt * gw);
   const int m0 = offsets[e] + mt * BM, m_end = offsets[e + 1], n0 = nt * BN;
   const float* base = parts + (long)r_tile * split * (BM * BN);
-  for (int i = threadIdx.x; i < BM * BN / 8; i += blockDim.x) {
-    const int row = i / (BN / 8), col = (i % (BN / 8)) * 8;
+  for (int i = threadIdx.x; i < (BM / SLICES) * BN / 8; i += blockDim.x) {
+    const int row = slice * (BM / SLICES) + i / (BN / 8), col = (i % (BN / 8)) * 8;
     if (m0 + row >= m_end || n0 + col >= N) continue;          // N is a multiple of 8
     float v[8];
 #pragma unroll
