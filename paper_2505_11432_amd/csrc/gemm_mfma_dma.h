@@ -562,6 +562,12 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       const char* at = smem + (kt % NSTAGE) * STAGE_BYTES;
       const char* bt = at + A_BYTES;
       if constexpr (PROBE == 2) continue;
+      if constexpr (MODE == ROWSEG) {
+        // A wave whose rows all lie past the expert's last row has nothing to multiply (wave-uniform; it still
+        // issued its loads and takes part in the barriers).  In a nearly empty last tile of an expert only one or
+        // two waves per CU then use the matrix cores, and the k-step shrinks to what the loads need.
+        if (m0 + wm * WTM >= m_end) continue;
+      }
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
         if constexpr (FP8) {
