@@ -42,6 +42,12 @@ __device__ __forceinline__ void dma16s(const char* sbase, unsigned voff, unsigne
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "m0");
 }
 
+// One wave-wide 4-byte direct-to-LDS load whose data nobody reads (it lands in a dump area): its only effect is to
+// bring the 64 lines it touches into this XCD's L2 ahead of the tile loads that need them.
+__device__ __forceinline__ void touch4s(const char* sbase, unsigned voff, unsigned lds_dump) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_dump) : "m0");
+}
+
 __device__ __forceinline__ const char* uniform_ptr(const char* p) {
   const unsigned long long v = reinterpret_cast<unsigned long long>(p);
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
@@ -354,6 +360,20 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   const char* b_base = zero;
   unsigned a_off[A_DMA], b_off[B_DMA];   // this lane's byte offset from the base, fixed over the k loop
   int a_k[A_DMA], b_k[B_DMA];       // k coordinate (relative to the k-step start) this lane's chunk begins at
+  // L2 touches (row-segmented two-stage kernels).  The workgroups of a window stream the same A and B panels at the
+  // same k, so every new line is requested by 4 to 8 of them at once and all of them wait for the one fill.  At the
+  // end of k-step kt the first wave that does not load (wave NL) touches this workgroup's share of the lines of
+  // k-step kt + 2 (a quarter of each panel; the other sharers touch the rest), just before the loader waves ask for
+  // them.  Touches at the start of a step queue behind the tile loads in the texture-address unit and make the
+  // kernel 16 % slower; at the end of the step they make it 1.2 to 3 % faster; touching one or two steps further
+  // ahead changes nothing.  Not for e4m3 operands: there a k-step has half the time for the same loads and the
+  // touches cost 2 %.
+  constexpr bool TOUCH = MODE == ROWSEG && NSTAGE == 2 && SPLIT && !FP8;
+  // the same for the bf16 weight-gradient kernel (four stages of 32 k-rows): two k-steps per touch, every other step
+  constexpr bool TOUCH_K = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 4;
+  const bool is_toucher = (TOUCH || TOUCH_K) && wave == NL;
+  const unsigned lds_dump = smem_lds + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES;
+  unsigned ta_off = 0, tb_off = 0;
   // block scales of the current and the next k-step for this lane's fragment rows (byte 0 of each register)
   int sa_cur[TM], sb_cur[TN], sa_nxt[TM], sb_nxt[TN];
   const uint8_t* sa_ptr[TM];
@@ -469,6 +489,38 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         b_k[j] = krow;
       }
     }
+    if constexpr (TOUCH) {
+      // the gw n-tiles of a group share the A panel: quarter (nt in group) of its 256 rows each; the m-tiles of the
+      // window share the B panel: quarter (mt mod 4) each.  One line (k-step x row, or k-row x 128 bytes) per lane.
+      const int qa = (r - mt * gw) & 3, qb = mt & 3;
+      int arow = min(qa * 64 + lane, p.M - 1 - m0);
+      if constexpr (GATHER_A) arow = p.a_rowmap[m0 + arow];
+      ta_off = (unsigned)arow * (unsigned)(p.lda * ESZ);
+      if constexpr (LB == KMAJOR) {
+        const int row = qb * 64 + lane;
+        int gr;
+        if constexpr (SWI) {
+          const int qq = row >> 5;
+          const int n = min(n0 + (qq >> 1) * 32 + (row & 31), p.f - 1);
+          gr = (qq & 1) ? p.f + n : n;
+        } else {
+          gr = min(n0 + row, p.N - 1);
+        }
+        tb_off = (unsigned)gr * (unsigned)(p.ldb * ESZ);
+      } else {
+        const int krow = qb * (BKT / 4) + (lane >> 2);
+        const int col = min(n0 + (lane & 3) * 64, p.N - 8);
+        tb_off = (unsigned)krow * (unsigned)(p.ldb * ESZ) + (unsigned)(col * ESZ);
+      }
+    }
+    if constexpr (TOUCH_K) {
+      // weight gradient: lanes 0..31 take this workgroup's quarter (8 k-rows x 4 lines) of one k-step, lanes 32..63
+      // the same quarter of the following k-step
+      const int qa = (r - mt * gw) & 3, qb = mt & 3;
+      const int kr = (lane >> 5) * BKT + (((lane & 31) >> 2));
+      ta_off = (unsigned)(kr + qa * 8) * (unsigned)(p.lda * ESZ) + (unsigned)(min(m0 + (lane & 3) * 64, p.M - 8) * ESZ);
+      tb_off = (unsigned)(kr + qb * 8) * (unsigned)(p.ldb * ESZ) + (unsigned)(min(n0 + (lane & 3) * 64, p.N - 8) * ESZ);
+    }
     m0 = real_m0; n0 = real_n0;
     if constexpr (BSCALE) {
       const long g0 = k_begin / BKT;
@@ -547,10 +599,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     for (int kt = 0; kt < nk; ++kt) {
       // my loads for step kt have landed once at most the younger steps' loads are outstanding; the first
       // step of a tile also drains the previous tile's epilogue stores, which share the counter
-      if (kt > 0 && kt + NSTAGE - 2 < nk) wait_vmcnt<(NSTAGE - 2) * LOADS>();
-      else wait_vmcnt<0>();
+      if (!is_toucher) {                    // (the touching wave has no tile loads of its own to wait for)
+        if (kt > 0 && kt + NSTAGE - 2 < nk) wait_vmcnt<(NSTAGE - 2) * LOADS>();
+        else wait_vmcnt<0>();
+      }
       __syncthreads();
       if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+
       if constexpr (BSCALE) {
         // the wait above covered the scale loads issued one step ago
 #pragma unroll
@@ -570,6 +625,19 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       }
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
+        if constexpr (TOUCH) {
+          // late in the step, when the tile loads of this step have left the texture-address queue
+          if (kk == KK - 1 && is_toucher && (kt + NSTAGE + 1) * BKT <= klen) {   // whole k-steps only: every touched address exists
+            touch4s(a_base + (long)(kt + NSTAGE) * a_step, ta_off, lds_dump);
+            touch4s(b_base + (long)(kt + NSTAGE) * b_step, tb_off, lds_dump);
+          }
+        }
+        if constexpr (TOUCH_K) {
+          if (kk == KK - 1 && is_toucher && (kt & 1) == 0 && (kt + NSTAGE + 2) * BKT <= klen) {
+            touch4s(a_base + (long)(kt + NSTAGE) * a_step, ta_off, lds_dump);
+            touch4s(b_base + (long)(kt + NSTAGE) * b_step, tb_off, lds_dump);
+          }
+        }
         if constexpr (FP8) {
           // 32x32x64 e4m3 x e4m3 (format selectors 0, 0), both block scales 2^0 (E8M0 code 127)
           i32x8 af[TM], bfr[TN];
@@ -604,6 +672,9 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       p.clk_out[2 * blockIdx.x + 1] += __builtin_amdgcn_s_memrealtime() - rt0;
     }
 
+    if constexpr (TOUCH || TOUCH_K) {
+      if (is_toucher) wait_vmcnt<0>();      // no touch may still be on its way into LDS when the patches are used
+    }
     // ---- hand the ring to the next tile, then write this one out -------------------------------------
     const int ep_e = e, ep_m0 = m0, ep_m_end = m_end, ep_n0 = n0, ep_part_slot = part_slot;
     slot += 1;
@@ -841,7 +912,7 @@ template <int BM, int BN, int BKT, int NSTAGE, Layout LA, Layout LB, int ESZ = 2
 constexpr int dma_smem_bytes() {
   // the ring, the per-expert tile table and one epilogue patch per wave (at most 8 waves)
   return NSTAGE * (DmaTileBytes<LA, BM, BKT, ESZ>::value + DmaTileBytes<LB, BN, BKT, ESZ>::value) + (MOE_MAX_EXPERTS + 8) * 4 +
-         8 * STG_BYTES;
+         8 * STG_BYTES + 256;       // + the dump area of the L2 touches
 }
 
 }  // namespace mfma
