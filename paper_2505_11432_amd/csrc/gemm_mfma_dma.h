@@ -374,6 +374,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   const bool is_toucher = (TOUCH || TOUCH_K) && wave == NL;
   const unsigned lds_dump = smem_lds + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES;
   unsigned ta_off = 0, tb_off = 0;
+  int rot_a = 0, rot_b = 0;         // rotation of this workgroup's load order within the A / B tile (see open_tile)
   // block scales of the current and the next k-step for this lane's fragment rows (byte 0 of each register)
   int sa_cur[TM], sb_cur[TN], sa_nxt[TM], sb_nxt[TN];
   const uint8_t* sa_ptr[TM];
@@ -421,6 +422,11 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     const int mt = r / gw;
     const int nt = ng * GN + (r - mt * gw);
     m0 = m_lo + mt * BM; m_end = m_hi; n0 = nt * BN_OUT;
+    // Sharers of a panel start their loads at different quarters of it (the n-tiles of a group share A, the m-tiles
+    // of a window share B), so that the first request for each new line, the one that starts its L2 fill, is spread
+    // over the sharers and over the step instead of all of them queueing on the same line in the same order.
+    rot_a = __builtin_amdgcn_readfirstlane(((r - mt * gw) & 3) * A_DMA / 4);
+    rot_b = __builtin_amdgcn_readfirstlane((mt & 3) * B_DMA / 4);
     int k_begin, k_end;
     if constexpr (MODE == KSEG) { k_begin = p.offsets[e]; k_end = p.offsets[e + 1]; }
     else { k_begin = 0; k_end = p.K; }
@@ -445,7 +451,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     else b_base = uniform_ptr(Bg + (long)k_begin * p.ldb * ESZ);
 #pragma unroll
     for (int j = 0; j < A_DMA; ++j) {
-      const int q = lw + j * NL;
+      const int q = lw + ((j + rot_a) % A_DMA) * NL;
       if constexpr (LA == KMAJOR) {
         using TL = KTile<BM, BKT, ESZ>;
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
@@ -465,7 +471,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     }
 #pragma unroll
     for (int j = 0; j < B_DMA; ++j) {
-      const int q = lw + j * NL;
+      const int q = lw + ((j + rot_b) % B_DMA) * NL;
       if constexpr (LB == KMAJOR) {
         using TL = KTile<BN, BKT, ESZ>;
         const int row = q * TL::ROWS_PER_DMA + lane / TL::CPR;
@@ -553,9 +559,9 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     const char* bb = b_base + (long)ks * b_step;
     if (k_left >= BKT) {
 #pragma unroll
-      for (int j = 0; j < A_DMA; ++j) dma16s(ab, a_off[j], stage + (unsigned)(lw + j * NL) * 1024u);
+      for (int j = 0; j < A_DMA; ++j) dma16s(ab, a_off[j], stage + (unsigned)(lw + ((j + rot_a) % A_DMA) * NL) * 1024u);
 #pragma unroll
-      for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + j * NL) * 1024u);
+      for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
     } else {
       // ragged last step: chunks past the end of the contraction come from the zero block.  The offsets pass
       // through an empty asm so that their 64-bit extensions are made here, in the cold path, instead of being
@@ -564,13 +570,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       for (int j = 0; j < A_DMA; ++j) {
         unsigned off = a_off[j];
         asm volatile("" : "+v"(off));
-        dma16(a_k[j] >= k_left ? zero : ab + off, stage + (unsigned)(lw + j * NL) * 1024u);
+        dma16(a_k[j] >= k_left ? zero : ab + off, stage + (unsigned)(lw + ((j + rot_a) % A_DMA) * NL) * 1024u);
       }
 #pragma unroll
       for (int j = 0; j < B_DMA; ++j) {
         unsigned off = b_off[j];
         asm volatile("" : "+v"(off));
-        dma16(b_k[j] >= k_left ? zero : bb + off, stage + A_BYTES + (unsigned)(lw + j * NL) * 1024u);
+        dma16(b_k[j] >= k_left ? zero : bb + off, stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
       }
     }
   };
