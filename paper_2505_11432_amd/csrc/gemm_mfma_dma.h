@@ -368,13 +368,16 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   // kernel 16 % slower; at the end of the step they make it 1.2 to 3 % faster; touching one or two steps further
   // ahead changes nothing.  Not for e4m3 operands: there a k-step has half the time for the same loads and the
   // touches cost 2 %.
-  constexpr bool TOUCH = MODE == ROWSEG && NSTAGE == 2 && SPLIT && !FP8;
+  constexpr bool TOUCH = MODE == ROWSEG && NSTAGE == 2 && SPLIT && !FP8 && EPI != EPI_SWIGLU_BWD_W;   // (that epilogue has no register to spare)
   // the same for the bf16 weight-gradient kernel (four stages of 32 k-rows): two k-steps per touch, every other step
   constexpr bool TOUCH_K = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 4;
   const bool is_toucher = (TOUCH || TOUCH_K) && wave == NL;
   const unsigned lds_dump = smem_lds + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES;
   unsigned ta_off = 0, tb_off = 0;
-  int rot_a = 0, rot_b = 0;         // rotation of this workgroup's load order within the A / B tile (see open_tile)
+  // rotation of this workgroup's load order within the A / B tile (see open_tile); only where it pays: the e4m3
+  // row-segmented kernels (in the others the extra scalar state pushes tile offsets out of registers)
+  constexpr bool ROT = FP8 && MODE == ROWSEG;
+  int rot_a = 0, rot_b = 0;
   // block scales of the current and the next k-step for this lane's fragment rows (byte 0 of each register)
   int sa_cur[TM], sb_cur[TN], sa_nxt[TM], sb_nxt[TN];
   const uint8_t* sa_ptr[TM];
@@ -425,8 +428,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     // Sharers of a panel start their loads at different quarters of it (the n-tiles of a group share A, the m-tiles
     // of a window share B), so that the first request for each new line, the one that starts its L2 fill, is spread
     // over the sharers and over the step instead of all of them queueing on the same line in the same order.
-    rot_a = __builtin_amdgcn_readfirstlane(((r - mt * gw) & 3) * A_DMA / 4);
-    rot_b = __builtin_amdgcn_readfirstlane((mt & 3) * B_DMA / 4);
+    if constexpr (ROT) {
+      rot_a = __builtin_amdgcn_readfirstlane(((r - mt * gw) & 3) * A_DMA / 4);
+      rot_b = __builtin_amdgcn_readfirstlane((mt & 3) * B_DMA / 4);
+    }
     int k_begin, k_end;
     if constexpr (MODE == KSEG) { k_begin = p.offsets[e]; k_end = p.offsets[e + 1]; }
     else { k_begin = 0; k_end = p.K; }
