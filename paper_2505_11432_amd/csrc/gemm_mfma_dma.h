@@ -360,20 +360,20 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   const char* b_base = zero;
   unsigned a_off[A_DMA], b_off[B_DMA];   // this lane's byte offset from the base, fixed over the k loop
   int a_k[A_DMA], b_k[B_DMA];       // k coordinate (relative to the k-step start) this lane's chunk begins at
-  // L2 touches (row-segmented two-stage kernels).  The workgroups of a window stream the same A and B panels at the
-  // same k, so every new line is requested by 4 to 8 of them at once and all of them wait for the one fill.  At the
-  // end of k-step kt the first wave that does not load (wave NL) touches this workgroup's share of the lines of
-  // k-step kt + 2 (a quarter of each panel; the other sharers touch the rest), just before the loader waves ask for
-  // them.  Touches at the start of a step queue behind the tile loads in the texture-address unit and make the
-  // kernel 16 % slower; at the end of the step they make it 1.2 to 3 % faster; touching one or two steps further
-  // ahead changes nothing.  Not for e4m3 operands: there a k-step has half the time for the same loads and the
-  // touches cost 2 %.
+  // L2 touches (bf16 kernels).  The workgroups of a window stream the same A and B panels at the same k, so every
+  // new line is requested by several of them at once and all of them wait for the one fill.  At the end of k-step kt
+  // the first wave that does not load (wave NL) touches this workgroup's quarter of the A-panel lines that the
+  // loader waves request next (the n-tiles of a group share the A panel; the other three touch the other quarters).
+  // Measured: touches at the start of a step queue behind the tile loads in the texture-address unit (kernel 16 %
+  // slower); at the end of the step they gain 1.2 to 3 %; one or two steps further ahead: no change; touching the B
+  // panel as well, or half of A, or from two waves: slower again (each touch instruction costs the address unit as
+  // much as a 1 KB tile load).  Not for e4m3 operands: half the time per k-step for the same loads, touches cost 2 %.
   constexpr bool TOUCH = MODE == ROWSEG && NSTAGE == 2 && SPLIT && !FP8 && EPI != EPI_SWIGLU_BWD_W;   // (that epilogue has no register to spare)
   // the same for the bf16 weight-gradient kernel (four stages of 32 k-rows): two k-steps per touch, every other step
   constexpr bool TOUCH_K = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 4;
   const bool is_toucher = (TOUCH || TOUCH_K) && wave == NL;
   const unsigned lds_dump = smem_lds + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES;
-  unsigned ta_off = 0, tb_off = 0;
+  unsigned ta_off = 0;
   // rotation of this workgroup's load order within the A / B tile (see open_tile); only where it pays: the e4m3
   // row-segmented kernels (in the others the extra scalar state pushes tile offsets out of registers)
   constexpr bool ROT = FP8 && MODE == ROWSEG;
@@ -501,36 +501,18 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       }
     }
     if constexpr (TOUCH) {
-      // the gw n-tiles of a group share the A panel: quarter (nt in group) of its 256 rows each; the m-tiles of the
-      // window share the B panel: quarter (mt mod 4) each.  One line (k-step x row, or k-row x 128 bytes) per lane.
-      const int qa = (r - mt * gw) & 3, qb = mt & 3;
+      // the gw n-tiles of a group share the A panel: quarter (nt in group) of its 256 rows each, one line per lane
+      const int qa = (r - mt * gw) & 3;
       int arow = min(qa * 64 + lane, p.M - 1 - m0);
       if constexpr (GATHER_A) arow = p.a_rowmap[m0 + arow];
       ta_off = (unsigned)arow * (unsigned)(p.lda * ESZ);
-      if constexpr (LB == KMAJOR) {
-        const int row = qb * 64 + lane;
-        int gr;
-        if constexpr (SWI) {
-          const int qq = row >> 5;
-          const int n = min(n0 + (qq >> 1) * 32 + (row & 31), p.f - 1);
-          gr = (qq & 1) ? p.f + n : n;
-        } else {
-          gr = min(n0 + row, p.N - 1);
-        }
-        tb_off = (unsigned)gr * (unsigned)(p.ldb * ESZ);
-      } else {
-        const int krow = qb * (BKT / 4) + (lane >> 2);
-        const int col = min(n0 + (lane & 3) * 64, p.N - 8);
-        tb_off = (unsigned)krow * (unsigned)(p.ldb * ESZ) + (unsigned)(col * ESZ);
-      }
     }
     if constexpr (TOUCH_K) {
-      // weight gradient: lanes 0..31 take this workgroup's quarter (8 k-rows x 4 lines) of one k-step, lanes 32..63
-      // the same quarter of the following k-step
-      const int qa = (r - mt * gw) & 3, qb = mt & 3;
+      // weight gradient: lanes 0..31 take this workgroup's quarter (8 k-rows x 4 lines) of the A tile of one k-step,
+      // lanes 32..63 the same quarter of the following k-step
+      const int qa = (r - mt * gw) & 3;
       const int kr = (lane >> 5) * BKT + (((lane & 31) >> 2));
       ta_off = (unsigned)(kr + qa * 8) * (unsigned)(p.lda * ESZ) + (unsigned)(min(m0 + (lane & 3) * 64, p.M - 8) * ESZ);
-      tb_off = (unsigned)(kr + qb * 8) * (unsigned)(p.ldb * ESZ) + (unsigned)(min(n0 + (lane & 3) * 64, p.N - 8) * ESZ);
     }
     m0 = real_m0; n0 = real_n0;
     if constexpr (BSCALE) {
@@ -640,13 +622,11 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
           // late in the step, when the tile loads of this step have left the texture-address queue
           if (kk == KK - 1 && is_toucher && (kt + NSTAGE + 1) * BKT <= klen) {   // whole k-steps only: every touched address exists
             touch4s(a_base + (long)(kt + NSTAGE) * a_step, ta_off, lds_dump);
-            touch4s(b_base + (long)(kt + NSTAGE) * b_step, tb_off, lds_dump);
           }
         }
         if constexpr (TOUCH_K) {
           if (kk == KK - 1 && is_toucher && (kt & 1) == 0 && (kt + NSTAGE + 2) * BKT <= klen) {
             touch4s(a_base + (long)(kt + NSTAGE) * a_step, ta_off, lds_dump);
-            touch4s(b_base + (long)(kt + NSTAGE) * b_step, tb_off, lds_dump);
           }
         }
         if constexpr (FP8) {
