@@ -545,10 +545,18 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     const char* ab = a_base + (long)ks * a_step;     // scalar arithmetic
     const char* bb = b_base + (long)ks * b_step;
     if (k_left >= BKT) {
+      // the e4m3 weight-gradient kernel asks for the B tile first, the others for the A tile: measured
+      constexpr bool B_FIRST = FP8 && MODE == KSEG;
+      if constexpr (B_FIRST) {
+#pragma unroll
+        for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
+      }
 #pragma unroll
       for (int j = 0; j < A_DMA; ++j) dma16s(ab, a_off[j], stage + (unsigned)(lw + ((j + rot_a) % A_DMA) * NL) * 1024u);
+      if constexpr (!B_FIRST) {
 #pragma unroll
-      for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
+        for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
+      }
     } else {
       // ragged last step: chunks past the end of the contraction come from the zero block.  The offsets pass
       // through an empty asm so that their 64-bit extensions are made here, in the cold path, instead of being
