@@ -216,7 +216,7 @@ __host__ __device__ __forceinline__ void splitk_plan(int total_tiles, int workgr
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) splitk_fixup_kernel(const float* __restrict__ parts, const int32_t* __restrict__ offsets,
                                                            int E, int N, int gemm_workgroups, bf16* __restrict__ C, long ldc) {
-  constexpr int GN = 4;
+  constexpr int GN = 8;
   __shared__ int cum_tiles[MOE_MAX_EXPERTS + 1];
   if (threadIdx.x == 0) {
     int run = 0;
@@ -297,7 +297,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr bool GATHER_A = EPI == EPI_SWIGLU_W;                              // A rows selected by index map (Section 4.2)
   static_assert(!FOLD || (!FP8 && MODE == ROWSEG && LA == KMAJOR), "the folded order exists for the bf16 row-segmented kernels");
   constexpr int BN_OUT = SWI ? BN / 2 : BN;
-  constexpr int GN = 4, XCDS = 8;
+  constexpr int GN = 8, XCDS = 8;   // GN n-tiles per group: a window of 32 tiles is 4 m-tiles x 8 n-tiles (measured against 8 x 4, 16 x 2, 2 x 16)
   static_assert(A_BYTES % (1024 * NL) == 0 && B_BYTES % (1024 * NL) == 0, "tile does not split over the loader waves");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * LOADS < 64, "pipeline depth exceeds the vmcnt range");
   static_assert(!SWI || TN % 2 == 0, "SwiGLU pairs gate/up MFMA tiles inside a wave");
@@ -363,7 +363,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   // L2 touches (bf16 kernels).  The workgroups of a window stream the same A and B panels at the same k, so every
   // new line is requested by several of them at once and all of them wait for the one fill.  At the end of k-step kt
   // the first wave that does not load (wave NL) touches this workgroup's quarter of the A-panel lines that the
-  // loader waves request next (the n-tiles of a group share the A panel; the other three touch the other quarters).
+  // loader waves request next (the n-tiles of a group share the A panel; quarter = position in the group mod 4).
   // Measured: touches at the start of a step queue behind the tile loads in the texture-address unit (kernel 16 %
   // slower); at the end of the step they gain 1.2 to 3 %; one or two steps further ahead: no change; touching the B
   // panel as well, or half of A, or from two waves: slower again (each touch instruction costs the address unit as
@@ -501,7 +501,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       }
     }
     if constexpr (TOUCH) {
-      // the gw n-tiles of a group share the A panel: quarter (nt in group) of its 256 rows each, one line per lane
+      // the gw n-tiles of a group share the A panel: quarter (position in the group mod 4) of its 256 rows, one line per lane
       const int qa = (r - mt * gw) & 3;
       int arow = min(qa * 64 + lane, p.M - 1 - m0);
       if constexpr (GATHER_A) arow = p.a_rowmap[m0 + arow];
