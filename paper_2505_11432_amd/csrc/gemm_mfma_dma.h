@@ -319,8 +319,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   // of W = G/8 consecutive tiles (one per CU of an XCD); a window is a compact block of one expert -- GN
   // adjacent n-tiles for a run of m-tiles -- whose tiles stream the same A and B panels at the same k, so
   // most of their loads hit in L2.  Windows are dealt round-robin to the XCDs: at any moment the eight
-  // XCDs work on eight neighbouring windows, i.e. the same A panels (shared through the Infinity Cache)
-  // and disjoint B panels, so every weight byte leaves HBM about once.
+  // XCDs work on eight neighbouring windows, mostly the next m-tiles of the same n-tiles, i.e. the same B
+  // panels (shared through the Infinity Cache) and disjoint A panels.
   const int tiles_n = (p.N + BN_OUT - 1) / BN_OUT;
   const int tiles_m_fixed = (p.M + BM - 1) / BM;              // KSEG / PLAIN
   int total_tiles;
