@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="mixtral", help="synthetic workload name (see synth/moe_inputs.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = T/8)")
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = T/4)")
     ap.add_argument("--fp8-backward", action="store_true",
                     help="fp8 configurations only: run the four backward GEMMs on e4m3 operands as well")
     ap.add_argument("--capacity-factor", type=float, default=0.0,
@@ -261,7 +261,7 @@ def main():
         "launch": "one HIP graph per step" if args.graph else "eager",
     }
     if not args.no_cpu_baseline:
-        tokens = args.cpu_tokens or max(cfg.T // 8, 1)
+        tokens = args.cpu_tokens or max(cfg.T // 4, 1)
         out["cpu_baseline"] = (cpu_baseline_fp8(cfg, inp, tokens, args.fp8_backward) if fp8
                                else cpu_baseline(cfg, inp, tokens))
     print(json.dumps(out))
