@@ -68,7 +68,9 @@ int moe_router_fwd(const void* x, const void* w_r, const float* bias, moe_dtype 
 /* Gradients of moe_router_fwd: d_w_r[e,i] = sum_t d_logits[t,e] * x[t,i] (fp32 [E,d],
  * overwritten; summed in a fixed order, so reproducible) and dx[t,i] += sum_e d_logits[t,e]
  * * w_r[e,i] (dx [T,d] in `dt`, read and written).  d_w_r or dx may be NULL to skip that
- * half.  d_w_r needs workspace. */
+ * half.  d_w_r needs workspace (moe_workspace_bytes); dx alone runs without one.  With a
+ * workspace, bf16 data and 32 experts or more, dx is computed on the matrix cores from the
+ * gate gradient rounded to bf16 (relative 2^-9, below the rounding of the bf16 result). */
 int moe_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt,
                    int T, int d, int E, float* d_w_r, void* dx,
                    void* workspace, size_t ws_bytes, void* stream);

@@ -214,8 +214,9 @@ int moe_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dt
   if ((d_w_r && !x && T > 0) || (dx && !w_r)) return MOE_ERR_INVALID;
   if (!aligned16(x) || !aligned16(w_r) || !aligned16(dx) || !aligned16(d_w_r) || !aligned16(workspace))
     return MOE_ERR_UNSUPPORTED;
-  if (d_w_r && (!workspace || ws_bytes < router_bwd_ws_bytes(T, d, E))) return MOE_ERR_WORKSPACE;
-  return launch_router_bwd(x, w_r, d_logits, dt, T, d, E, d_w_r, dx, workspace, as_stream(stream));
+  const bool ws_ok = workspace && ws_bytes >= router_bwd_ws_bytes(T, d, E);
+  if (d_w_r && !ws_ok) return MOE_ERR_WORKSPACE;
+  return launch_router_bwd(x, w_r, d_logits, dt, T, d, E, d_w_r, dx, ws_ok ? workspace : nullptr, as_stream(stream));
 }
 
 int moe_route(const float* logits, int T, int E, int k, int renorm, int32_t* topk_idx, float* topk_w,

@@ -209,6 +209,28 @@ int mfma_wgrad_fp8(const void* Pt, const uint8_t* p_e8m0, const void* Qt, const 
   return launch<256, 256, 128, 2, 4, 2, KMAJOR, KMAJOR, KSEG, EPI_STORE, bf16, uint8_t>(a, blocks, s);
 }
 
+// Router weight gradient as a weight-gradient GEMM over token chunks: partial[c][E, d] (+)= g_c^T * x_c
+int mfma_router_dwr(const void* g, const void* x, const int32_t* chunk_offsets, int chunks, int E, int d, float* partial,
+                    int accumulate, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)g; a.lda = E;
+  a.B = (const bf16*)x; a.ldb = d; a.b_es = 0;
+  a.C = partial; a.ldc = d; a.c_es = (long)E * d; a.offsets = chunk_offsets; a.E = chunks; a.M = E; a.N = d; a.K = 0;
+  a.accumulate = accumulate;
+  const long blocks = (long)chunks * cdiv(E, 128) * cdiv(d, 256);
+  return launch<128, 256, 32, 4, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, float>(a, blocks, s);
+}
+
+// dx[T,d] += g[T,E] * w_r[E,d]: one dense GEMM with a very short contraction (K = E), bound by reading and writing dx
+int mfma_router_dx(const void* g, const void* w_r, int T, int d, int E, void* dx, hipStream_t s) {
+  Args a{};
+  a.A = (const bf16*)g; a.lda = E;
+  a.B = (const bf16*)w_r; a.ldb = d; a.b_es = 0;
+  a.C = dx; a.ldc = d; a.E = 1; a.M = T; a.N = d; a.K = E;
+  a.accumulate = 1;
+  return launch<256, 256, 64, 2, 2, 4, KMAJOR, MNMAJOR, PLAIN, EPI_STORE, bf16>(a, (long)cdiv(T, 256) * cdiv(d, 256), s);
+}
+
 // logits[T,E] = x[T,d] * w_r[E,d]^T (+ bias), fp32 out
 int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, int d, int E, float* logits,
                     hipStream_t s) {

@@ -134,6 +134,10 @@ int mfma_wgrad_fp8(const void* Pt, const uint8_t* p_e8m0, const void* Qt, const 
                    hipStream_t s);
 int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, int d, int E, float* logits,
                     hipStream_t s);
+// partial[c][E][d] (+)= g[tokens of chunk c, E]^T * x[tokens of chunk c, d], g and x bf16, chunk_offsets [chunks+1]
+int mfma_router_dwr(const void* g, const void* x, const int32_t* chunk_offsets, int chunks, int E, int d, float* partial,
+                    int accumulate, hipStream_t s);
+int mfma_router_dx(const void* g, const void* w_r, int T, int d, int E, void* dx, hipStream_t s);
 size_t router_bwd_ws_bytes(int T, int d, int E);
 int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt, int T, int d, int E,
                       float* d_w_r, void* dx, void* ws, hipStream_t s);

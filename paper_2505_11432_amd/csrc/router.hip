@@ -198,6 +198,33 @@ __global__ void __launch_bounds__(256) router_dx_kernel(const T* __restrict__ w_
   }
 }
 
+// ---- d_w_r on the matrix cores (many experts) -----------------------------------------------------------------
+// d_w_r = d_logits^T x is a weight-gradient GEMM with the tokens as contraction index: E output rows, d columns.
+// With 32 experts or more the vector-ALU kernel above is bound by its FMAs, so the grouped weight-gradient kernel is
+// used instead, with token chunks in the role of the experts (one fp32 partial [E, d] per chunk, then the same
+// fixed-order reduction).  The fp32 gate gradient enters as two bf16 matrices, hi = bf16(v) and lo = bf16(v - hi)
+// (relative error of hi + lo: 2^-17), multiplied in two accumulating launches.
+constexpr int kMfmaChunkTokens = 512;
+
+int dwr_mfma_chunk_tokens(int T) {
+  int tpc = kMfmaChunkTokens;
+  while (cdiv(T, tpc) > MOE_MAX_EXPERTS) tpc *= 2;
+  return tpc;
+}
+bool dwr_use_mfma(moe_dtype dt, int T, int d, int E) { return dt == MOE_BF16 && E >= 32 && E % 8 == 0 && d % 8 == 0 && T > 0; }
+
+__global__ void __launch_bounds__(256) dlogits_split_kernel(const float* __restrict__ d_logits, long n, bf16* __restrict__ hi,
+                                                            bf16* __restrict__ lo, int T, int tokens_per_chunk, int chunks,
+                                                            int32_t* __restrict__ chunk_offsets) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i <= chunks) chunk_offsets[i] = (int32_t)min((long)T, i * tokens_per_chunk);
+  if (i >= n) return;
+  const float v = d_logits[i];
+  const bf16 h = static_cast<bf16>(v);
+  hi[i] = h;
+  lo[i] = static_cast<bf16>(v - static_cast<float>(h));
+}
+
 int dwr_tokens_per_chunk(int T) {                // a multiple of the LDS staging size; at most 256 chunks
   int tpc = kChunkTokens;
   while (cdiv(T, tpc) > 256) tpc *= 2;
@@ -210,11 +237,40 @@ int dwr_chunks(int T) {
 
 }  // namespace
 
-size_t router_bwd_ws_bytes(int T, int d, int E) { return align_up((size_t)dwr_chunks(T) * E * d * sizeof(float), 256); }
+static size_t dwr_mfma_ws_bytes(int T, int d, int E) {
+  const size_t chunks = cdiv(T, dwr_mfma_chunk_tokens(T));
+  return align_up(chunks * E * d * sizeof(float), 256) + 2 * align_up((size_t)T * E * 2, 256) + align_up((chunks + 1) * 4, 256);
+}
+size_t router_bwd_ws_bytes(int T, int d, int E) {
+  const size_t valu = align_up((size_t)dwr_chunks(T) * E * d * sizeof(float), 256);
+  const size_t mfma = T > 0 && E >= 32 && E % 8 == 0 ? dwr_mfma_ws_bytes(T, d, E) : 0;      // (any dtype: an upper bound)
+  return valu > mfma ? valu : mfma;
+}
 
 int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt, int T, int d, int E,
                       float* d_w_r, void* dx, void* ws, hipStream_t s) {
-  if (d_w_r) {
+  const bool mfma_path = ws && dwr_use_mfma(dt, T, d, E) && (d_w_r || dx);     // dx alone may come without a workspace
+  bf16* hi = nullptr;
+  if (mfma_path) {
+    const int tpc = dwr_mfma_chunk_tokens(T), chunks = cdiv(T, tpc);
+    char* base = static_cast<char*>(ws);
+    float* partial = reinterpret_cast<float*>(base);
+    hi = reinterpret_cast<bf16*>(base + align_up((size_t)chunks * E * d * sizeof(float), 256));
+    bf16* lo = reinterpret_cast<bf16*>(reinterpret_cast<char*>(hi) + align_up((size_t)T * E * 2, 256));
+    int32_t* chunk_offsets = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(lo) + align_up((size_t)T * E * 2, 256));
+    const long n = (long)T * E;
+    dlogits_split_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(d_logits, n, hi, lo, T, tpc, chunks, chunk_offsets);
+    MOE_LAUNCH_CHECK();
+    if (d_w_r) {
+      int rc = mfma_router_dwr(hi, x, chunk_offsets, chunks, E, d, partial, 0, s);
+      if (rc != MOE_OK) return rc;
+      rc = mfma_router_dwr(lo, x, chunk_offsets, chunks, E, d, partial, 1, s);
+      if (rc != MOE_OK) return rc;
+      const long nout = (long)E * d;
+      router_dwr_reduce_kernel<<<(int)((nout + 63) / 64), 256, 0, s>>>(partial, chunks, nout, d_w_r);
+      MOE_LAUNCH_CHECK();
+    }
+  } else if (d_w_r) {
     const int chunks = dwr_chunks(T);
     const int tpc = dwr_tokens_per_chunk(T);
     float* partial = static_cast<float*>(ws);
@@ -238,7 +294,11 @@ int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe
     router_dwr_reduce_kernel<<<(int)blocks, 256, 0, s>>>(partial, chunks, n, d_w_r);
     MOE_LAUNCH_CHECK();
   }
-  if (dx && T > 0) {
+  if (dx && mfma_path) {
+    // dx is bf16: the hi part of the gate gradient alone is below its rounding (lo is 2^-9 of hi)
+    const int rc = mfma_router_dx(hi, w_r, T, d, E, dx, s);
+    if (rc != MOE_OK) return rc;
+  } else if (dx && T > 0) {
     const int slabs = cdiv(d, kDxCols);
     int token_groups = cdiv(512, slabs);                 // about two blocks per CU
     if (token_groups > cdiv(T, 16)) token_groups = cdiv(T, 16);

@@ -90,7 +90,8 @@ def test_route_bwd(B, renorm):
     assert max_norm_err(to_np(dz), dz_ref) < 1e-5
 
 
-@pytest.mark.parametrize("dtype,T,d,E", [("f32", 100, 48, 8), ("bf16", 300, 256, 64), ("bf16", 64, 4096, 8)])
+@pytest.mark.parametrize("dtype,T,d,E", [("f32", 100, 48, 8), ("bf16", 300, 256, 64), ("bf16", 64, 4096, 8),
+                                         ("bf16", 1100, 528, 32), ("bf16", 700, 272, 40)])
 def test_router_fwd_bwd(B, dtype, T, d, E):
     cfg = MoEConfig("t", T=T, d=d, E=E, k=1, f=16, dtype=dtype, w_std=0.1, wr_std=0.1, bias="linear", bias_gamma=0.5)
     inp = make_inputs(cfg, with_weights=False)
@@ -112,6 +113,16 @@ def test_router_fwd_bwd(B, dtype, T, d, E):
     dW_ref, dx_ref = O.router_bwd(inp["x"], inp["W_r"], dz)
     assert max_norm_err(to_np(dwr), dW_ref.T) < 1e-5
     assert max_norm_err(to_np(dx), dx0 + dx_ref) < TOL[dtype]
+    # either output alone: the same values
+    dwr2 = torch.empty((E, d), device=DEV)
+    B.moe_router_bwd(x, wr, to_dev(dz), dwr2, None, ws)
+    assert torch.equal(dwr2, dwr)
+    dx2 = to_dev(dx0, td)
+    B.moe_router_bwd(x, wr, to_dev(dz), None, dx2, ws)
+    assert torch.equal(dx2, dx)
+    dx3 = to_dev(dx0, td)                          # dx needs no workspace
+    B.moe_router_bwd(x, wr, to_dev(dz), None, dx3, torch.empty(0, dtype=torch.uint8, device=DEV))
+    assert max_norm_err(to_np(dx3), dx0 + dx_ref) < TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype,T,d,E,k", [("f32", 37, 48, 4, 2), ("bf16", 500, 1040, 8, 3), ("bf16", 129, 4096, 64, 8),
