@@ -91,7 +91,8 @@ def test_route_bwd(B, renorm):
 
 
 @pytest.mark.parametrize("dtype,T,d,E", [("f32", 100, 48, 8), ("bf16", 300, 256, 64), ("bf16", 64, 4096, 8),
-                                         ("bf16", 1100, 528, 32), ("bf16", 700, 272, 40)])
+                                         ("bf16", 1100, 528, 32), ("bf16", 700, 272, 40),      # matrix-core gradients
+                                         ("bf16", 300, 256, 36), ("f32", 200, 64, 40)])        # vector-ALU gradients, wide tile
 def test_router_fwd_bwd(B, dtype, T, d, E):
     cfg = MoEConfig("t", T=T, d=d, E=E, k=1, f=16, dtype=dtype, w_std=0.1, wr_std=0.1, bias="linear", bias_gamma=0.5)
     inp = make_inputs(cfg, with_weights=False)
