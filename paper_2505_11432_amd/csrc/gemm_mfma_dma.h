@@ -600,10 +600,11 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     // bf16 kernels: the fragments of a sub-step are read one sub-step ahead, also across the step barrier.  The
     // barrier that opens step s+1 sits before the last sub-step's MFMAs of step s (whose fragments are in registers
     // by then), so the first fragment reads of a step, which all eight waves issue at once, overlap MFMAs instead of
-    // leaving the matrix cores idle at every step start: -1.6 % on the forward kernels, -0.3 % on the others.  Not
-    // for the fused-order dgrad2 kernel (the second fragment set makes it reload registers inside the loop) and not
-    // for the e4m3 kernels (32-byte fragments: no room for a second set).
-    constexpr bool XPIPE = !FP8 && EPI != EPI_SWIGLU_BWD_W;
+    // leaving the matrix cores idle at every step start: -1.6 to -2.2 % on the forward kernels and dgrad1.  Measured
+    // kernel by kernel (builds side by side): no gain in the dgrad2 kernels, whose epilogues need the registers of
+    // the second fragment set (the fused-order one would reload registers inside the loop), a loss of 1 % in the
+    // weight-gradient kernel, and the e4m3 kernels have no room for a second set of 32-byte fragments.
+    constexpr bool XPIPE = !FP8 && MODE != KSEG && EPI != EPI_SWIGLU_BWD && EPI != EPI_SWIGLU_BWD_W;
     if constexpr (XPIPE) {
       static_assert(KK % 2 == 0, "fragment sets alternate by sub-step parity");
       // opens step s: its loads have landed (at most the younger steps' loads are outstanding; the first step of a
@@ -641,11 +642,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             constexpr int TOUCH_AT = KK >= 2 ? KK - 2 : 0;      // one sub-step ahead of the refill it runs before (later: slower)
             if constexpr (TOUCH) {
               if (kk == TOUCH_AT && is_toucher && (kt + NSTAGE + 1) * BKT <= klen) {   // whole k-steps only: every touched address exists
-                touch4s(a_base + (long)(kt + NSTAGE) * a_step, ta_off, lds_dump);
-              }
-            }
-            if constexpr (TOUCH_K) {
-              if (kk == TOUCH_AT && is_toucher && (kt & 1) == 0 && (kt + NSTAGE + 2) * BKT <= klen) {
                 touch4s(a_base + (long)(kt + NSTAGE) * a_step, ta_off, lds_dump);
               }
             }
