@@ -739,6 +739,16 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     }
     // ---- hand the ring to the next tile, then write this one out -------------------------------------
     const int ep_e = e, ep_m0 = m0, ep_m_end = m_end, ep_n0 = n0, ep_part_slot = part_slot;
+    // SwiGLU' (bf16): the saved G and U of the wave's first block are asked for before the hand-over, ahead of the
+    // next tile's first loads in the memory queue
+    constexpr bool EARLY_GU = !FP8 && (EPI == EPI_SWIGLU_BWD || EPI == EPI_SWIGLU_BWD_W);
+    StageFetch fg_first, fu_first;
+    if constexpr (EARLY_GU) {
+      const int mb = m0 + wm * WTM, nb = n0 + wn * WTN;
+      const bf16* hrow = p.H + (long)mb * 2 * p.N + nb;
+      fg_first = stage_fetch_bf16(hrow, 2L * p.N, m_end - mb, p.N - nb, lane);
+      fu_first = stage_fetch_bf16(hrow + p.N, 2L * p.N, m_end - mb, p.N - nb, lane);
+    }
     slot += 1;
     __syncthreads();                      // every wave has read its last fragments: the ring is free
     const bool has_next = open_tile(slot);
@@ -947,8 +957,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             fg = stage_fetch_bf16(hrow, 2L * p.N, rows_valid, cols_valid, lane);
             fu = stage_fetch_bf16(hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
           };
-          StageFetch fg, fu;
-          fetch_block(0, fg, fu);
+          StageFetch fg = fg_first, fu = fu_first;
           float w_row = 1.0f, dw_sum = 0.f;
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
