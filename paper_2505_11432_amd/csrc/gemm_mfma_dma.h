@@ -109,8 +109,106 @@ __device__ __forceinline__ bf16x8 read_frag_dma(const char* tile, int base, int 
 constexpr int STG_STRIDE = 80;                  // bytes per staged row (64 payload + 16 pad)
 constexpr int STG_BYTES = 32 * STG_STRIDE;      // per wave
 
+// Global accesses of the epilogues are raw buffer instructions on a descriptor that starts at the block's origin
+// (wave-uniform): a lane outside the valid rows or columns gets an offset past the end of the buffer, which the
+// hardware answers with zeros (loads) or drops (stores).  No lane-dependent branch surrounds a memory instruction, so
+// every wave issues the same, known number of them and the compiler's s_waitcnt vmcnt(n) stay exact: with stores
+// inside `if (valid)` blocks it has to assume that none was issued and waits for vmcnt(0), i.e. for every store of
+// the previous block, before each read.
+typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
+constexpr unsigned BUF_SPAN = 0x40000000u;      // 1 GiB from the block origin; a 32-row block spans far less
+constexpr unsigned BUF_OOB = 0x80000000u;       // offset of a masked lane
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t block_rsrc(const void* origin) {
+  char* base = const_cast<char*>(uniform_ptr(static_cast<const char*>(origin)));
+  return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)BUF_SPAN, 0x00020000);   // raw buffer, 32-bit data format
+}
+__device__ __forceinline__ unsigned block_offset(int r, int c, long ld, int esz, int rows_valid, int cols_valid) {
+  return (r < rows_valid && c < cols_valid) ? (unsigned)(((long)r * ld + c) * esz) : BUF_OOB;
+}
+
 // 32 rows x 32 bf16 columns from registers to global memory (row-major, leading dimension ld elements).
 __device__ __forceinline__ void stage_store_bf16(char* stg, const bf16x4 (&v)[4], bf16* g, long ld, int rows_valid,
+                                                 int cols_valid, int lane) {
+  const int row = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) *reinterpret_cast<bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2) = v[q];
+  const __amdgpu_buffer_rsrc_t rs = block_rsrc(g);
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    const u32x4v val = *reinterpret_cast<const u32x4v*>(stg + r * STG_STRIDE + c * 2);
+    __builtin_amdgcn_raw_buffer_store_b128(val, rs, block_offset(r, c, ld, 2, rows_valid, cols_valid), 0, 0);
+  }
+}
+
+// 32 rows x 32 bf16 columns from global memory into registers (same lane layout as the accumulators).
+__device__ __forceinline__ void stage_load_bf16(char* stg, bf16x4 (&v)[4], const bf16* g, long ld, int rows_valid,
+                                                int cols_valid, int lane) {
+  const __amdgpu_buffer_rsrc_t rs = block_rsrc(g);
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    const u32x4v val = __builtin_amdgcn_raw_buffer_load_b128(rs, block_offset(r, c, ld, 2, rows_valid, cols_valid), 0, 0);
+    *reinterpret_cast<u32x4v*>(stg + r * STG_STRIDE + c * 2) = val;
+  }
+  const int row = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2);
+}
+
+// The same load in two phases, so that the global reads of the next 32x32 block can be in flight while the
+// current block is processed: fetch (global -> registers, zero where masked) and unpack (registers -> LDS patch ->
+// accumulator lane layout).
+struct StageFetch { u32x4v v[2]; };
+__device__ __forceinline__ StageFetch stage_fetch_bf16(const bf16* g, long ld, int rows_valid, int cols_valid, int lane) {
+  StageFetch f;
+  const __amdgpu_buffer_rsrc_t rs = block_rsrc(g);
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    f.v[pass] = __builtin_amdgcn_raw_buffer_load_b128(rs, block_offset(r, c, ld, 2, rows_valid, cols_valid), 0, 0);
+  }
+  return f;
+}
+__device__ __forceinline__ void stage_unpack_bf16(char* stg, const StageFetch& f, bf16x4 (&v)[4], int lane) {
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
+    *reinterpret_cast<u32x4v*>(stg + r * STG_STRIDE + c * 2) = f.v[pass];
+  }
+  const int row = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2);
+}
+
+// 32 rows x 32 fp32 columns, as two halves of 16 columns; optional read-modify-write accumulation.
+__device__ __forceinline__ void stage_store_f32(char* stg, const f32x16& acc, float* g, long ld, int rows_valid,
+                                                int cols_valid, bool accumulate, int lane) {
+  const int row = lane & 31, h = lane >> 5;
+  const __amdgpu_buffer_rsrc_t rs = block_rsrc(g);
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int qq = 0; qq < 2; ++qq) {
+      const int q = half * 2 + qq;
+      const f32x4 t = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+      *reinterpret_cast<f32x4*>(stg + row * STG_STRIDE + (8 * qq + 4 * h) * 4) = t;
+    }
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int r = pass * 16 + (lane >> 2), c = half * 16 + (lane & 3) * 4;
+      f32x4 val = *reinterpret_cast<const f32x4*>(stg + r * STG_STRIDE + (lane & 3) * 16);
+      const unsigned off = block_offset(r, c, ld, 4, rows_valid, cols_valid);
+      if (accumulate) val += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));   // (uniform)
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, val), rs, off, 0, 0);
+    }
+  }
+}
+
+// ---- the same three with plain global accesses inside `if (valid)` (the e4m3 kernels: their register budget does
+// not take the descriptors)
+// 32 rows x 32 bf16 columns from registers to global memory (row-major, leading dimension ld elements).
+__device__ __forceinline__ void stage_store_bf16_g(char* stg, const bf16x4 (&v)[4], bf16* g, long ld, int rows_valid,
                                                  int cols_valid, int lane) {
   const int row = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -124,7 +222,7 @@ __device__ __forceinline__ void stage_store_bf16(char* stg, const bf16x4 (&v)[4]
 }
 
 // 32 rows x 32 bf16 columns from global memory into registers (same lane layout as the accumulators).
-__device__ __forceinline__ void stage_load_bf16(char* stg, bf16x4 (&v)[4], const bf16* g, long ld, int rows_valid,
+__device__ __forceinline__ void stage_load_bf16_g(char* stg, bf16x4 (&v)[4], const bf16* g, long ld, int rows_valid,
                                                 int cols_valid, int lane) {
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
@@ -138,33 +236,8 @@ __device__ __forceinline__ void stage_load_bf16(char* stg, bf16x4 (&v)[4], const
   for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2);
 }
 
-// The same load in two phases, so that the global reads of the next 32x32 block can be in flight while the
-// current block is processed: fetch (global -> registers, zero where masked) and unpack (registers -> LDS patch ->
-// accumulator lane layout).
-struct StageFetch { uint4 v[2]; };
-__device__ __forceinline__ StageFetch stage_fetch_bf16(const bf16* g, long ld, int rows_valid, int cols_valid, int lane) {
-  StageFetch f;
-#pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
-    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
-    f.v[pass] = make_uint4(0, 0, 0, 0);
-    if (r < rows_valid && c < cols_valid) f.v[pass] = *reinterpret_cast<const uint4*>(g + (long)r * ld + c);
-  }
-  return f;
-}
-__device__ __forceinline__ void stage_unpack_bf16(char* stg, const StageFetch& f, bf16x4 (&v)[4], int lane) {
-#pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
-    const int r = pass * 16 + (lane >> 2), c = (lane & 3) * 8;
-    *reinterpret_cast<uint4*>(stg + r * STG_STRIDE + c * 2) = f.v[pass];
-  }
-  const int row = lane & 31, h = lane >> 5;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const bf16x4*>(stg + row * STG_STRIDE + (8 * q + 4 * h) * 2);
-}
-
 // 32 rows x 32 fp32 columns, as two halves of 16 columns; optional read-modify-write accumulation.
-__device__ __forceinline__ void stage_store_f32(char* stg, const f32x16& acc, float* g, long ld, int rows_valid,
+__device__ __forceinline__ void stage_store_f32_g(char* stg, const f32x16& acc, float* g, long ld, int rows_valid,
                                                 int cols_valid, bool accumulate, int lane) {
   const int row = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -297,6 +370,16 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr bool GATHER_A = EPI == EPI_SWIGLU_W;                              // A rows selected by index map (Section 4.2)
   static_assert(!FOLD || (!FP8 && MODE == ROWSEG && LA == KMAJOR), "the folded order exists for the bf16 row-segmented kernels");
   constexpr int BN_OUT = SWI ? BN / 2 : BN;
+  // Store instructions a wave issues in the epilogue of a full tile (branch-free buffer stores, bf16 kernels): two
+  // per 32x32 bf16 block, four per fp32 block; 0 = not known at compile time.
+  constexpr int EPI_STORES_RAW = FP8 ? 0
+                                 : EPI == EPI_STORE ? TM * TN * (sizeof(TC) == 4 ? 4 : 2)
+                                 : SWI ? TM * TN * 3
+                                 : EPI == EPI_SWIGLU_BWD ? TM * TN * 6
+                                 : EPI == EPI_SWIGLU_BWD_W ? TM * TN * 6 + TM
+                                 : 0;
+  constexpr int EPI_STORES = (NSTAGE - 2) * LOADS + EPI_STORES_RAW <= 63 ? EPI_STORES_RAW : 0;   // vmcnt is a 6-bit field
+  bool epi_stores = false;         // the previous tile's epilogue issued exactly EPI_STORES stores (wave-uniform)
   constexpr int GN = 8, XCDS = 8;   // GN n-tiles per group: a window of 32 tiles is 4 m-tiles x 8 n-tiles (measured against 8 x 4, 16 x 2, 2 x 16)
   static_assert(A_BYTES % (1024 * NL) == 0 && B_BYTES % (1024 * NL) == 0, "tile does not split over the loader waves");
   static_assert(NSTAGE >= 2 && (NSTAGE - 2) * LOADS < 64, "pipeline depth exceeds the vmcnt range");
@@ -596,6 +679,19 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // Wait until this wave's loads for step s have landed.  vmcnt counts loads and stores together, in issue order, so
+    // the wait names how many younger operations may still be outstanding: the loads of the (NSTAGE - 2) following
+    // steps, and, in the first NSTAGE - 1 steps of a tile (whose loads were issued before the previous tile's
+    // epilogue), that epilogue's stores when their number is known (epi_stores; 0 = unknown: wait for everything).
+    auto wait_step = [&](int s) __attribute__((always_inline)) {
+      if (s + NSTAGE - 2 < nk) {
+        if constexpr (EPI_STORES > 0) {
+          if (s < NSTAGE - 1 && epi_stores) { wait_vmcnt<(NSTAGE - 2) * LOADS + EPI_STORES>(); return; }
+        }
+        if (s > 0) { wait_vmcnt<(NSTAGE - 2) * LOADS>(); return; }
+      }
+      wait_vmcnt<0>();
+    };
     // ---- k loop ------------------------------------------------------------------------------------
     // bf16 kernels: the fragments of a sub-step are read one sub-step ahead, also across the step barrier.  The
     // barrier that opens step s+1 sits before the last sub-step's MFMAs of step s (whose fragments are in registers
@@ -612,8 +708,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       // refilled right away
       auto open_step = [&](int s) __attribute__((always_inline)) {
         if (!is_toucher) {                  // (the touching wave has no tile loads of its own to wait for)
-          if (s > 0 && s + NSTAGE - 2 < nk) wait_vmcnt<(NSTAGE - 2) * LOADS>();
-          else wait_vmcnt<0>();
+          wait_step(s);
         }
         __syncthreads();
         if (s + NSTAGE - 1 < nk) issue(s + NSTAGE - 1);
@@ -664,8 +759,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       // my loads for step kt have landed once at most the younger steps' loads are outstanding; the first
       // step of a tile also drains the previous tile's epilogue stores, which share the counter
       if (!is_toucher) {                    // (the touching wave has no tile loads of its own to wait for)
-        if (kt > 0 && kt + NSTAGE - 2 < nk) wait_vmcnt<(NSTAGE - 2) * LOADS>();
-        else wait_vmcnt<0>();
+        wait_step(kt);
       }
       __syncthreads();
       if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
@@ -739,6 +833,9 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     }
     // ---- hand the ring to the next tile, then write this one out -------------------------------------
     const int ep_e = e, ep_m0 = m0, ep_m_end = m_end, ep_n0 = n0, ep_part_slot = part_slot;
+    // a full tile that is no split-K part and does not read-modify-write issues every store of its epilogue
+    epi_stores = EPI_STORES > 0 && part_slot < 0 && !p.accumulate && m0 + BM <= m_end &&
+                 n0 + BN_OUT <= (SWI ? p.f : p.N);
     // SwiGLU' (bf16): the saved G and U of the wave's first block are asked for before the hand-over, ahead of the
     // next tile's first loads in the memory queue
     constexpr bool EARLY_GU = !FP8 && (EPI == EPI_SWIGLU_BWD || EPI == EPI_SWIGLU_BWD_W);
@@ -783,7 +880,17 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
           }
         }
       };
-      // every 32x32 MFMA tile goes through the wave's LDS patch (see stage_store_* above)
+      // every 32x32 MFMA tile goes through the wave's LDS patch (see stage_store_* above); bf16 kernels use the
+      // branch-free buffer accesses, e4m3 kernels the plain ones
+      auto store_bf16 = [&](const bf16x4 (&v)[4], bf16* g, long ld, int rv, int cv) __attribute__((always_inline)) {
+        if constexpr (FP8) stage_store_bf16_g(stg, v, g, ld, rv, cv, lane); else stage_store_bf16(stg, v, g, ld, rv, cv, lane);
+      };
+      auto load_bf16 = [&](bf16x4 (&v)[4], const bf16* g, long ld, int rv, int cv) __attribute__((always_inline)) {
+        if constexpr (FP8) stage_load_bf16_g(stg, v, g, ld, rv, cv, lane); else stage_load_bf16(stg, v, g, ld, rv, cv, lane);
+      };
+      auto store_f32 = [&](const f32x16& a, float* g, long ld, int rv, int cv, bool accumulate) __attribute__((always_inline)) {
+        if constexpr (FP8) stage_store_f32_g(stg, a, g, ld, rv, cv, accumulate, lane); else stage_store_f32(stg, a, g, ld, rv, cv, accumulate, lane);
+      };
       if (SPLITK && ep_part_slot >= 0) {
         // one K part of a split tile: the whole fp32 tile goes to the partial buffer, no masks
         float* part_tile = p.splitk_ws + (long)ep_part_slot * (BM * BN);
@@ -792,7 +899,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
             dequant_block(i, j);
-            stage_store_f32(stg, acc[i][j], part_tile + (long)(wm * WTM + i * 32) * BN + wn * WTN + j * 32, BN, 32, 32, false, lane);
+            store_f32(acc[i][j], part_tile + (long)(wm * WTM + i * 32) * BN + wn * WTN + j * 32, BN, 32, 32, false);
           }
       } else if constexpr (EPI == EPI_STORE) {
 #pragma unroll
@@ -808,13 +915,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             dequant_block(i, j);
             if constexpr (sizeof(TC) == 4) {
               float* g = static_cast<float*>(p.C) + (long)e * p.c_es + (long)mb * p.ldc + nb;
-              stage_store_f32(stg, acc[i][j], g, p.ldc, rows_valid, cols_valid, p.accumulate != 0, lane);
+              store_f32(acc[i][j], g, p.ldc, rows_valid, cols_valid, p.accumulate != 0);
             } else {
               bf16* g = static_cast<bf16*>(p.C) + (long)e * p.c_es + (long)mb * p.ldc + nb;
               bf16x4 v[4];
               if (p.accumulate) {
                 bf16x4 old[4];
-                stage_load_bf16(stg, old, g, p.ldc, rows_valid, cols_valid, lane);
+                load_bf16(old, g, p.ldc, rows_valid, cols_valid);
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -826,7 +933,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 #pragma unroll
                   for (int t = 0; t < 4; ++t) v[q][t] = static_cast<bf16>(acc[i][j][4 * q + t]);
               }
-              stage_store_bf16(stg, v, g, p.ldc, rows_valid, cols_valid, lane);
+              store_bf16(v, g, p.ldc, rows_valid, cols_valid);
             }
           }
         }
@@ -872,9 +979,9 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
                 a[q][t] = static_cast<bf16>(w_row * (gf * sigmoid_f32(gf) * static_cast<float>(u[q][t])));
               }
             bf16* hrow = p.H + (long)mb * 2 * p.f + nb;
-            stage_store_bf16(stg, g, hrow, 2L * p.f, rows_valid, cols_valid, lane);
-            stage_store_bf16(stg, u, hrow + p.f, 2L * p.f, rows_valid, cols_valid, lane);
-            stage_store_bf16(stg, a, p.A_out + (long)mb * p.f + nb, p.f, rows_valid, cols_valid, lane);
+            store_bf16(g, hrow, 2L * p.f, rows_valid, cols_valid);
+            store_bf16(u, hrow + p.f, 2L * p.f, rows_valid, cols_valid);
+            store_bf16(a, p.A_out + (long)mb * p.f + nb, p.f, rows_valid, cols_valid);
           }
         }
       } else {
@@ -900,9 +1007,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
               a[q][t] = static_cast<bf16>(FOLD ? w_row * av : av);
             }
           bf16* drow = p.dH + (long)mb * 2 * p.N + nb;
-          stage_store_bf16(stg, dg, drow, 2L * p.N, rows_valid, cols_valid, lane);
-          stage_store_bf16(stg, du, drow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
-          if (p.A_out) stage_store_bf16(stg, a, p.A_out + (long)mb * p.N + nb, p.N, rows_valid, cols_valid, lane);
+          store_bf16(dg, drow, 2L * p.N, rows_valid, cols_valid);
+          store_bf16(du, drow + p.N, 2L * p.N, rows_valid, cols_valid);
+          if constexpr (FP8) {
+            if (p.A_out) store_bf16(a, p.A_out + (long)mb * p.N + nb, p.N, rows_valid, cols_valid);
+          } else {
+            store_bf16(a, p.A_out + (long)mb * p.N + nb, p.N, p.A_out ? rows_valid : 0, cols_valid);   // no A_out: all lanes masked
+          }
         };
         // lanes l and l + 32 hold the two column halves of row l.  Every row of the expert's segment gets exactly one
         // partial per (n-tile, wave along n); blocks past N contribute zero.
@@ -913,8 +1024,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
         auto write_dw = [&](int i, float dw_sum) __attribute__((always_inline)) {
           if constexpr (FOLD) {
             const float tot = dw_sum + __shfl_xor(dw_sum, 32);
-            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
-            if (lane < 32 && m < m_end) p.dw_part[(long)((n0 / BN) * WN + wn) * p.M + m] = tot;
+            const int mb = m0 + wm * WTM + i * 32;
+            const __amdgpu_buffer_rsrc_t rs = block_rsrc(p.dw_part + (long)((n0 / BN) * WN + wn) * p.M + mb);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, tot), rs,
+                                                  (lane < 32 && mb + lane < m_end) ? (unsigned)lane * 4u : BUF_OOB, 0, 0);
           }
         };
         if constexpr (FP8) {
@@ -932,8 +1045,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
               if (cols_valid <= 0) continue;
               bf16x4 g[4], u[4];
               const bf16* hrow = p.H + (long)mb * 2 * p.N + nb;
-              stage_load_bf16(stg, g, hrow, 2L * p.N, rows_valid, cols_valid, lane);
-              stage_load_bf16(stg, u, hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
+              load_bf16(g, hrow, 2L * p.N, rows_valid, cols_valid);
+              load_bf16(u, hrow + p.N, 2L * p.N, rows_valid, cols_valid);
               dequant_block(i, j);
               swiglu_bwd_block(acc[i][j], g, u, mb, nb, rows_valid, cols_valid, 1.0f, dw_sum);
             }
@@ -957,8 +1070,12 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             fg = stage_fetch_bf16(hrow, 2L * p.N, rows_valid, cols_valid, lane);
             fu = stage_fetch_bf16(hrow + p.N, 2L * p.N, rows_valid, cols_valid, lane);
           };
+          // Every block runs whether or not it has valid rows or columns (the masks live in the buffer offsets): a
+          // uniform skip of single blocks would again make the number of stores in flight unknown to the compiler.
+          // A wave without any valid row skips all of it.
           StageFetch fg = fg_first, fu = fu_first;
           float w_row = 1.0f, dw_sum = 0.f;
+          if (m0 + wm * WTM < m_end)
 #pragma unroll
           for (int b = 0; b < NB; ++b) {
             if (b % TN == 0) { w_row = row_weight(b / TN); dw_sum = 0.f; }
@@ -968,8 +1085,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             stage_unpack_bf16(stg, fg, g, lane);
             stage_unpack_bf16(stg, fu, u, lane);
             if (b + 1 < NB) fetch_block(b + 1, fg, fu);
-            if (rows_valid > 0 && cols_valid > 0)
-              swiglu_bwd_block(acc[b / TN][b % TN], g, u, mb, nb, rows_valid, cols_valid, w_row, dw_sum);
+            __builtin_amdgcn_sched_barrier(0);      // the read-ahead stays ahead of this block's arithmetic and stores
+            swiglu_bwd_block(acc[b / TN][b % TN], g, u, mb, nb, rows_valid, cols_valid, w_row, dw_sum);
             if (b % TN == TN - 1) write_dw(b / TN, dw_sum);
           }
         }
