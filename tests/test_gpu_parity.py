@@ -239,6 +239,24 @@ def test_layer_small_bf16(B, cfg):
     check_layer(cfg, inp, z, layer, TOL["bf16"])
 
 
+MANY_TILES_BF16 = [
+    # More tiles than workgroups with a short contraction, so that every workgroup starts a tile of one to four k-steps
+    # while the stores of its previous tile's epilogue are still in flight (row-segmented kernels: 512 row tiles, K of
+    # 128 and 256) ...
+    MoEConfig("short_k", T=65536, d=256, E=4, k=2, f=128, dtype="bf16", w_std=0.06, wr_std=0.5),
+    # ... and the same for the weight-gradient kernel: 512 + 256 output tiles over 256 tokens per expert
+    MoEConfig("short_m", T=2048, d=1024, E=16, k=2, f=1024, dtype="bf16", w_std=0.03, wr_std=0.2),
+]
+
+
+@pytest.mark.parametrize("cfg", MANY_TILES_BF16, ids=lambda c: c.name)
+def test_layer_many_tiles_short_contraction(B, cfg):
+    inp = make_inputs(cfg, seed=3)
+    z = O.router_logits(inp["x"], inp["W_r"], inp["bias"]).astype(np.float32)
+    layer = run_layer(B, cfg, inp, z)
+    check_layer(cfg, inp, z, layer, TOL["bf16"])
+
+
 def test_layer_bf16_gradients_in_bf16_and_accumulate(B):
     cfg = SMALL_BF16[0]
     inp = make_inputs(cfg, seed=2)
