@@ -719,7 +719,7 @@ def _fused_layer(cfg, inp, z, td, expert_range=None, with_router=True):
     return layer
 
 
-@pytest.mark.parametrize("cfg", SMALL_BF16, ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", SMALL_BF16 + MANY_TILES_BF16, ids=lambda c: c.name)
 def test_layer_fused_order(B, cfg):
     """Every result against the plain layer of the oracle (the reordering changes no value, only rounding), the
     kept and returned intermediates against the oracle's statement of the reordered operators."""
