@@ -372,7 +372,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr int BN_OUT = SWI ? BN / 2 : BN;
   // Store instructions a wave issues in the epilogue of a full tile (branch-free buffer stores, bf16 kernels): two
   // per 32x32 bf16 block, four per fp32 block; 0 = not known at compile time.
-  constexpr int EPI_STORES_RAW = FP8 ? 0
+  constexpr bool PLAIN_EPI = FP8 && !(MODE == ROWSEG && (SWI || EPI == EPI_STORE));   // epilogue with plain (branchy) global accesses
+  constexpr int EPI_STORES_RAW = PLAIN_EPI ? 0
                                  : EPI == EPI_STORE ? TM * TN * (sizeof(TC) == 4 ? 4 : 2)
                                  : SWI ? TM * TN * 3
                                  : EPI == EPI_SWIGLU_BWD ? TM * TN * 6
@@ -883,13 +884,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       // every 32x32 MFMA tile goes through the wave's LDS patch (see stage_store_* above); bf16 kernels use the
       // branch-free buffer accesses, e4m3 kernels the plain ones
       auto store_bf16 = [&](const bf16x4 (&v)[4], bf16* g, long ld, int rv, int cv) __attribute__((always_inline)) {
-        if constexpr (FP8) stage_store_bf16_g(stg, v, g, ld, rv, cv, lane); else stage_store_bf16(stg, v, g, ld, rv, cv, lane);
+        if constexpr (PLAIN_EPI) stage_store_bf16_g(stg, v, g, ld, rv, cv, lane); else stage_store_bf16(stg, v, g, ld, rv, cv, lane);
       };
       auto load_bf16 = [&](bf16x4 (&v)[4], const bf16* g, long ld, int rv, int cv) __attribute__((always_inline)) {
-        if constexpr (FP8) stage_load_bf16_g(stg, v, g, ld, rv, cv, lane); else stage_load_bf16(stg, v, g, ld, rv, cv, lane);
+        if constexpr (PLAIN_EPI) stage_load_bf16_g(stg, v, g, ld, rv, cv, lane); else stage_load_bf16(stg, v, g, ld, rv, cv, lane);
       };
       auto store_f32 = [&](const f32x16& a, float* g, long ld, int rv, int cv, bool accumulate) __attribute__((always_inline)) {
-        if constexpr (FP8) stage_store_f32_g(stg, a, g, ld, rv, cv, accumulate, lane); else stage_store_f32(stg, a, g, ld, rv, cv, accumulate, lane);
+        if constexpr (PLAIN_EPI) stage_store_f32_g(stg, a, g, ld, rv, cv, accumulate, lane); else stage_store_f32(stg, a, g, ld, rv, cv, accumulate, lane);
       };
       if (SPLITK && ep_part_slot >= 0) {
         // one K part of a split tile: the whole fp32 tile goes to the partial buffer, no masks
