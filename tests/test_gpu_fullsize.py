@@ -134,6 +134,34 @@ def test_full_size_is_deterministic():
     assert torch.equal(g1a, b.d_w1) and torch.equal(g2a, b.d_w2)
 
 
+def test_full_size_back_to_back_steps_reproduce():
+    """Steps enqueued without a host synchronisation between them (the benchmark's launch pattern: the stores of one
+    tile's epilogue, and of one kernel's last tiles, are still in flight when the next loads are issued) give the first
+    step's results bit for bit."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = CONFIGS["mixtral"]
+    inp = make_inputs(cfg, seed=0)
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm)
+    x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
+    w_r = dev_bf16(np.ascontiguousarray(inp["W_r"].T))
+    bias = torch.from_numpy(inp["bias"]).to(DEV)
+    w1, w2 = dev_bf16(inp["W1"]), dev_bf16(inp["W2"])
+
+    def step():
+        layer.forward(x, w_r, bias, w1, w2)
+        layer.backward(x, w_r, w1, w2, dy)
+
+    step()
+    torch.cuda.synchronize()
+    names = ("y", "dx", "d_xp", "h_save", "d_w1", "d_w2", "d_w_r", "d_logits")
+    first = {n: getattr(layer, n).clone() for n in names}
+    for _ in range(4):
+        step()
+    torch.cuda.synchronize()
+    for n in names:
+        assert torch.equal(first[n], getattr(layer, n)), n
+
+
 def test_full_size_fp8_forward_and_fp8_backward_sampled():
     """mixtral_fp8 with all six expert GEMMs on e4m3 operands, at full size.  Stage by stage on samples: casts bit for
     bit against the oracle's quantisers applied to the kernel's own pre-cast rows / column slices, GEMM outputs against
