@@ -148,8 +148,8 @@ int mfma_wgrad(const void* P, const void* Q, const int32_t* offsets, int Mo, int
   a.C = C; a.ldc = N; a.c_es = (long)Mo * N; a.offsets = offsets; a.E = E; a.M = Mo; a.N = N; a.K = 0;
   a.accumulate = accumulate;
   const long blocks = (long)E * cdiv(Mo, 256) * cdiv(N, 256);
-  if (c_dt == MOE_F32) return launch<256, 256, 32, 4, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, float>(a, blocks, s);
-  return launch<256, 256, 32, 4, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, bf16>(a, blocks, s);
+  if (c_dt == MOE_F32) return launch<256, 256, 64, 2, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, float>(a, blocks, s);
+  return launch<256, 256, 64, 2, 2, 4, MNMAJOR, MNMAJOR, KSEG, EPI_STORE, bf16>(a, blocks, s);
 }
 
 // e4m3 operands (codes with per-row / per-output-channel scales), 32x32x64 f8f6f4 MFMA, bf16 results:

@@ -455,7 +455,8 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr bool TOUCH = MODE == ROWSEG && NSTAGE == 2 && SPLIT && !FP8 && EPI != EPI_SWIGLU_BWD_W;   // (that epilogue has no register to spare)
   // the same for the bf16 weight-gradient kernel (four stages of 32 k-rows): two k-steps per touch, every other step
   constexpr bool TOUCH_K = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 4;
-  const bool is_toucher = (TOUCH || TOUCH_K) && wave == NL;
+  constexpr bool TOUCH_K2 = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 2 && BKT == 64;
+  const bool is_toucher = (TOUCH || TOUCH_K || TOUCH_K2) && wave == NL;
   const unsigned lds_dump = smem_lds + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES;
   unsigned ta_off = 0;
   // rotation of this workgroup's load order within the A / B tile (see open_tile); only where it pays: the e4m3
@@ -591,8 +592,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       if constexpr (GATHER_A) arow = p.a_rowmap[m0 + arow];
       ta_off = (unsigned)arow * (unsigned)(p.lda * ESZ);
     }
+    if constexpr (TOUCH_K2) {
+      // weight gradient, 64-deep steps: this workgroup's quarter (16 k-rows x 4 lines) of the A tile of one k-step
+      const int qa = (r - mt * gw) & 3;
+      ta_off = (unsigned)(qa * 16 + (lane >> 2)) * (unsigned)(p.lda * ESZ) + (unsigned)(min(m0 + (lane & 3) * 64, p.M - 8) * ESZ);
+    }
     if constexpr (TOUCH_K) {
-      // weight gradient: lanes 0..31 take this workgroup's quarter (8 k-rows x 4 lines) of the A tile of one k-step,
+      // weight gradient, 32-deep steps: lanes 0..31 take this workgroup's quarter (8 k-rows x 4 lines) of the A tile of one k-step,
       // lanes 32..63 the same quarter of the following k-step
       const int qa = (r - mt * gw) & 3;
       const int kr = (lane >> 5) * BKT + (((lane & 31) >> 2));
@@ -697,11 +703,12 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     // bf16 kernels: the fragments of a sub-step are read one sub-step ahead, also across the step barrier.  The
     // barrier that opens step s+1 sits before the last sub-step's MFMAs of step s (whose fragments are in registers
     // by then), so the first fragment reads of a step, which all eight waves issue at once, overlap MFMAs instead of
-    // leaving the matrix cores idle at every step start: -1.6 to -2.2 % on the forward kernels and dgrad1.  Measured
-    // kernel by kernel (builds side by side): no gain in the dgrad2 kernels, whose epilogues need the registers of
-    // the second fragment set (the fused-order one would reload registers inside the loop), a loss of 1 % in the
-    // weight-gradient kernel, and the e4m3 kernels have no room for a second set of 32-byte fragments.
-    constexpr bool XPIPE = !FP8 && MODE != KSEG && EPI != EPI_SWIGLU_BWD && EPI != EPI_SWIGLU_BWD_W;
+    // leaving the matrix cores idle at every step start: -1.6 to -2.2 % on the forward kernels and dgrad1, -4 to -6 %
+    // on the weight-gradient kernel with 64-deep steps (with 32-deep steps, two sub-steps each, it gains nothing).
+    // Measured kernel by kernel (builds side by side): no gain in the dgrad2 kernels, whose epilogues need the
+    // registers of the second fragment set (the fused-order one would reload registers inside the loop), and the
+    // e4m3 kernels have no room for a second set of 32-byte fragments.
+    constexpr bool XPIPE = !FP8 && (MODE != KSEG || NSTAGE == 2) && EPI != EPI_SWIGLU_BWD && EPI != EPI_SWIGLU_BWD_W;
     if constexpr (XPIPE) {
       static_assert(KK % 2 == 0, "fragment sets alternate by sub-step parity");
       // opens step s: its loads have landed (at most the younger steps' loads are outstanding; the first step of a
@@ -736,7 +743,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 #pragma unroll
           for (int kk = 0; kk < KK; ++kk) {
             constexpr int TOUCH_AT = KK >= 2 ? KK - 2 : 0;      // one sub-step ahead of the refill it runs before (later: slower)
-            if constexpr (TOUCH) {
+            if constexpr (TOUCH || TOUCH_K2) {
               if (kk == TOUCH_AT && is_toucher && (kt + NSTAGE + 1) * BKT <= klen) {   // whole k-steps only: every touched address exists
                 touch4s(a_base + (long)(kt + NSTAGE) * a_step, ta_off, lds_dump);
               }
@@ -829,7 +836,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       p.clk_out[2 * blockIdx.x + 1] += __builtin_amdgcn_s_memrealtime() - rt0;
     }
 
-    if constexpr (TOUCH || TOUCH_K) {
+    if constexpr (TOUCH || TOUCH_K || TOUCH_K2) {
       if (is_toucher) wait_vmcnt<0>();      // no touch may still be on its way into LDS when the patches are used
     }
     // ---- hand the ring to the next tile, then write this one out -------------------------------------
