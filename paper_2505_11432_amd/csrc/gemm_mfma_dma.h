@@ -452,7 +452,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   // slower); at the end of the step they gain 1.2 to 3 %; one or two steps further ahead: no change; touching the B
   // panel as well, or half of A, or from two waves: slower again (each touch instruction costs the address unit as
   // much as a 1 KB tile load).  Not for e4m3 operands: half the time per k-step for the same loads, touches cost 2 %.
-  constexpr bool TOUCH = MODE == ROWSEG && NSTAGE == 2 && SPLIT && !FP8 && EPI != EPI_SWIGLU_BWD_W;   // (that epilogue has no register to spare)
+  constexpr bool TOUCH = MODE == ROWSEG && NSTAGE == 2 && SPLIT && !FP8;
   // the same for the bf16 weight-gradient kernel (four stages of 32 k-rows): two k-steps per touch, every other step
   constexpr bool TOUCH_K = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 4;
   constexpr bool TOUCH_K2 = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 2 && BKT == 64;
