@@ -24,7 +24,7 @@ PEAK_HBM_GBPS = 8000.0
 # L2-fill + write-back bytes per grouped-GEMM launch (average of the six launches of one step) on the default
 # workload, from rocprofv3 --pmc FETCH_SIZE (x2.000, the factor a 1 GiB copy gives) and WRITE_SIZE (x1.000);
 # the counter runs are summarised in profiles/grouped_gemm_mixtral_hbm_counters.txt.
-MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"mixtral": 8.34e9}
+MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"mixtral": 7.98e9}
 
 
 def parse():
