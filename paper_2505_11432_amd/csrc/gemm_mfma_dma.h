@@ -458,19 +458,28 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr bool TOUCH_K2 = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 2 && BKT == 64;
   const bool is_toucher = (TOUCH || TOUCH_K || TOUCH_K2) && wave == NL;
   const unsigned lds_dump = smem_lds + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES;
+  const unsigned scale_lds = lds_dump + 256;                                   // block-scale ring: 2 stages x (256 + 256) bytes
+  const char* scale_smem = smem + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES + 256;
   unsigned ta_off = 0;
   // rotation of this workgroup's load order within the A / B tile (see open_tile); only where it pays: the e4m3
   // row-segmented kernels (in the others the extra scalar state pushes tile offsets out of registers)
   constexpr bool ROT = FP8 && MODE == ROWSEG;
   int rot_a = 0, rot_b = 0;
   // block scales of the current and the next k-step for this lane's fragment rows (byte 0 of each register)
-  int sa_cur[TM], sb_cur[TN], sa_nxt[TM], sb_nxt[TN];
-  const uint8_t* sa_ptr[TM];
-  const uint8_t* sb_ptr[TN];
+  // Block scales (e4m3 weight gradients): the 256 + 256 E8M0 bytes of a k-step travel global -> LDS with the tiles
+  // (two 4-byte direct-to-LDS loads by loader wave 0, into a two-stage ring of 512 bytes) and every wave reads its
+  // rows' bytes from there.  Fetching them per lane from global memory took six more vector-memory instructions per
+  // wave and k-step, 48 per workgroup next to the 64 tile loads, and the address unit is what the load issue is
+  // bound by: the k-step was 0.4 us longer.
+  static_assert(!BSCALE || (BM == 256 && BN == 256), "one 4-byte load per lane covers the 256 channels of a tile side");
+  int sa_cur[TM], sb_cur[TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) { sa_cur[i] = sa_nxt[i] = 127; sa_ptr[i] = nullptr; }
+  for (int i = 0; i < TM; ++i) sa_cur[i] = 127;
 #pragma unroll
-  for (int j = 0; j < TN; ++j) { sb_cur[j] = sb_nxt[j] = 127; sb_ptr[j] = nullptr; }
+  for (int j = 0; j < TN; ++j) sb_cur[j] = 127;
+  const char* sa_base = nullptr;        // scale row of the tile's first k-step (wave-uniform)
+  const char* sb_base = nullptr;
+  unsigned sa_voff = 0, sb_voff = 0;    // this lane's four channels
   const long a_step = (LA == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.lda * ESZ;   // bytes per k-step
   const long b_step = (LB == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.ldb * ESZ;
 
@@ -607,25 +616,14 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     m0 = real_m0; n0 = real_n0;
     if constexpr (BSCALE) {
       const long g0 = k_begin / BKT;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        sa_ptr[i] = p.a_e8m0 + g0 * p.a_e8_ld + min(m0 + wm * WTM + i * 32 + (lane & 31), p.M - 1);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        sb_ptr[j] = p.b_e8m0 + g0 * p.b_e8_ld + min(n0 + wn * WTN + j * 32 + (lane & 31), p.N - 1);
+      sa_base = uniform_ptr(reinterpret_cast<const char*>(p.a_e8m0) + g0 * p.a_e8_ld);
+      sb_base = uniform_ptr(reinterpret_cast<const char*>(p.b_e8m0) + g0 * p.b_e8_ld);
+      // channels past the end repeat the last four (their rows and columns are masked when the tile is stored)
+      sa_voff = (unsigned)min(m0 + 4 * lane, p.M - 4);
+      sb_voff = (unsigned)min(n0 + 4 * lane, p.N - 4);
     }
     return true;
   };
-  // fetch the block scales of k-step ks of the open tile into the "next" registers
-  auto load_scales = [&](int ks) __attribute__((always_inline)) {
-    if constexpr (BSCALE) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i) sa_nxt[i] = sa_ptr[i][(long)ks * p.a_e8_ld];
-#pragma unroll
-      for (int j = 0; j < TN; ++j) sb_nxt[j] = sb_ptr[j][(long)ks * p.b_e8_ld];
-    }
-  };
-
   // Issue the loads of k-step `ks` of the open tile into ring slot ks % NSTAGE.  Only the last step can be ragged.
   auto issue = [&](int ks) __attribute__((always_inline)) {
     if constexpr (PROBE == 1) return;
@@ -634,6 +632,13 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     const int k_left = klen - ks * BKT;          // valid k in this step
     const char* ab = a_base + (long)ks * a_step;     // scalar arithmetic
     const char* bb = b_base + (long)ks * b_step;
+    if constexpr (BSCALE) {
+      if (lw == 0) {
+        const unsigned dst = scale_lds + (unsigned)(ks % NSTAGE) * 512u;
+        touch4s(sa_base + (long)ks * p.a_e8_ld, sa_voff, dst);
+        touch4s(sb_base + (long)ks * p.b_e8_ld, sb_voff, dst + 256u);
+      }
+    }
     if (k_left >= BKT) {
       // the e4m3 weight-gradient kernel asks for the B tile first, the others for the A tile: measured
       constexpr bool B_FIRST = FP8 && MODE == KSEG;
@@ -673,7 +678,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
   if (!open_tile(slot)) return;
   issue_prologue();
-  if (nk > 0) load_scales(0);
 
   for (;;) {
     unsigned long long clk0 = 0, rt0 = 0;
@@ -773,12 +777,12 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
 
       if constexpr (BSCALE) {
-        // the wait above covered the scale loads issued one step ago
+        // this step's scale bytes landed with its tiles (same wait, same barrier)
+        const unsigned char* sc = reinterpret_cast<const unsigned char*>(scale_smem) + (kt % NSTAGE) * 512;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) sa_cur[i] = sa_nxt[i];
+        for (int i = 0; i < TM; ++i) sa_cur[i] = sc[wm * WTM + i * 32 + (lane & 31)];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) sb_cur[j] = sb_nxt[j];
-        if (kt + 1 < nk) load_scales(kt + 1);
+        for (int j = 0; j < TN; ++j) sb_cur[j] = sc[256 + wn * WTN + j * 32 + (lane & 31)];
       }
       const char* at = smem + (kt % NSTAGE) * STAGE_BYTES;
       const char* bt = at + A_BYTES;
@@ -859,7 +863,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     const bool has_next = open_tile(slot);
     if (has_next) {
       issue_prologue();
-      if (nk > 0) load_scales(0);
     }
     {
       const int e = ep_e, m0 = ep_m0, m_end = ep_m_end, n0 = ep_n0;
@@ -1108,7 +1111,7 @@ template <int BM, int BN, int BKT, int NSTAGE, Layout LA, Layout LB, int ESZ = 2
 constexpr int dma_smem_bytes() {
   // the ring, the per-expert tile table and one epilogue patch per wave (at most 8 waves)
   return NSTAGE * (DmaTileBytes<LA, BM, BKT, ESZ>::value + DmaTileBytes<LB, BN, BKT, ESZ>::value) + (MOE_MAX_EXPERTS + 8) * 4 +
-         8 * STG_BYTES + 256;       // + the dump area of the L2 touches
+         8 * STG_BYTES + 256 + 1024;       // + the dump area of the L2 touches + the block-scale ring
 }
 
 }  // namespace mfma
