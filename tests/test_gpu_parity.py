@@ -301,6 +301,8 @@ def test_quant_fp8_bit_exact(B, src_dtype, rows, cols):
 FP8_CASES = [
     MoEConfig("fp8_ragged", T=611, d=272, E=6, k=2, f=336, dtype="bf16", w_std=0.06, wr_std=0.5),
     MoEConfig("fp8_tiles", T=700, d=512, E=4, k=2, f=640, dtype="bf16", w_std=0.05, wr_std=0.3),
+    # more weight-gradient tiles than workgroups (512 and 256), two or three 128-token steps each
+    MoEConfig("fp8_many_tiles", T=2048, d=1024, E=16, k=2, f=1024, dtype="bf16", w_std=0.03, wr_std=0.2),
 ]
 
 
