@@ -303,6 +303,8 @@ FP8_CASES = [
     MoEConfig("fp8_tiles", T=700, d=512, E=4, k=2, f=640, dtype="bf16", w_std=0.05, wr_std=0.3),
     # more weight-gradient tiles than workgroups (512 and 256), two or three 128-token steps each
     MoEConfig("fp8_many_tiles", T=2048, d=1024, E=16, k=2, f=1024, dtype="bf16", w_std=0.03, wr_std=0.2),
+    # the same with four or five steps per tile, experts of unequal size and a partly filled last round (360 + 180 tiles)
+    MoEConfig("fp8_many_tiles_uneven", T=3000, d=768, E=12, k=2, f=1280, dtype="bf16", w_std=0.03, wr_std=0.6),
 ]
 
 
