@@ -458,7 +458,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   constexpr bool TOUCH_K2 = MODE == KSEG && !FP8 && SPLIT && LA == MNMAJOR && LB == MNMAJOR && NSTAGE == 2 && BKT == 64;
   const bool is_toucher = (TOUCH || TOUCH_K || TOUCH_K2) && wave == NL;
   const unsigned lds_dump = smem_lds + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES;
-  const unsigned scale_lds = lds_dump + 256;                                   // block-scale ring: 4 slots x (256 + 256) bytes
+  const unsigned scale_lds = lds_dump + 256;                                   // block-scale ring: 2 stages x (256 + 256) bytes
   const char* scale_smem = smem + RING_BYTES + TABLE_BYTES + 8 * STG_BYTES + 256;
   unsigned ta_off = 0;
   // rotation of this workgroup's load order within the A / B tile (see open_tile); only where it pays: the e4m3
@@ -467,7 +467,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   int rot_a = 0, rot_b = 0;
   // block scales of the current and the next k-step for this lane's fragment rows (byte 0 of each register)
   // Block scales (e4m3 weight gradients): the 256 + 256 E8M0 bytes of a k-step travel global -> LDS with the tiles
-  // (two 4-byte direct-to-LDS loads by loader wave 0, into a four-slot ring of 512 bytes each) and every wave reads its
+  // (two 4-byte direct-to-LDS loads by loader wave 0, into a two-stage ring of 512 bytes) and every wave reads its
   // rows' bytes from there.  Fetching them per lane from global memory took six more vector-memory instructions per
   // wave and k-step, 48 per workgroup next to the 64 tile loads, and the address unit is what the load issue is
   // bound by: the k-step was 0.4 us longer.
@@ -480,11 +480,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   const char* sa_base = nullptr;        // scale row of the tile's first k-step (wave-uniform)
   const char* sb_base = nullptr;
   unsigned sa_voff = 0, sb_voff = 0;    // this lane's four channels
-  // Ring slots are taken by a running count of the steps issued / consumed over all tiles of the workgroup, four slots
-  // deep, so a slot is rewritten four steps after it was read.  (Indexed per tile by k-step parity, like the tile ring,
-  // the first step of a tile landed in the slot of the previous tile's last step whenever that tile had an odd number
-  // of steps, and the weight gradients of multi-tile workgroups came out wrong: the many-tiles e4m3 parity case.)
-  unsigned sc_issue = 0, sc_use = 0;
   const long a_step = (LA == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.lda * ESZ;   // bytes per k-step
   const long b_step = (LB == KMAJOR) ? (long)BKT * ESZ : (long)BKT * p.ldb * ESZ;
 
@@ -639,11 +634,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     const char* bb = b_base + (long)ks * b_step;
     if constexpr (BSCALE) {
       if (lw == 0) {
-        const unsigned dst = scale_lds + (sc_issue & 3u) * 512u;
+        const unsigned dst = scale_lds + (unsigned)(ks % NSTAGE) * 512u;
         touch4s(sa_base + (long)ks * p.a_e8_ld, sa_voff, dst);
         touch4s(sb_base + (long)ks * p.b_e8_ld, sb_voff, dst + 256u);
       }
-      sc_issue += 1;
     }
     if (k_left >= BKT) {
       // the e4m3 weight-gradient kernel asks for the B tile first, the others for the A tile: measured
@@ -784,8 +778,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
 
       if constexpr (BSCALE) {
         // this step's scale bytes landed with its tiles (same wait, same barrier)
-        const unsigned char* sc = reinterpret_cast<const unsigned char*>(scale_smem) + (sc_use & 3u) * 512;
-        sc_use += 1;
+        const unsigned char* sc = reinterpret_cast<const unsigned char*>(scale_smem) + (kt % NSTAGE) * 512;
 #pragma unroll
         for (int i = 0; i < TM; ++i) sa_cur[i] = sc[wm * WTM + i * 32 + (lane & 31)];
 #pragma unroll
@@ -1118,7 +1111,7 @@ template <int BM, int BN, int BKT, int NSTAGE, Layout LA, Layout LB, int ESZ = 2
 constexpr int dma_smem_bytes() {
   // the ring, the per-expert tile table and one epilogue patch per wave (at most 8 waves)
   return NSTAGE * (DmaTileBytes<LA, BM, BKT, ESZ>::value + DmaTileBytes<LB, BN, BKT, ESZ>::value) + (MOE_MAX_EXPERTS + 8) * 4 +
-         8 * STG_BYTES + 256 + 2048;       // + the dump area of the L2 touches + the block-scale ring
+         8 * STG_BYTES + 256 + 1024;       // + the dump area of the L2 touches + the block-scale ring
 }
 
 }  // namespace mfma
