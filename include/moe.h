@@ -91,6 +91,25 @@ int moe_route(const float* logits /*[T,E]*/, int T, int E, int k, int renorm,
               int32_t* perm /*[T*k]*/, int32_t* inv_perm /*[T*k]*/,
               void* workspace, size_t ws_bytes, void* stream);
 
+/* ---- moe_route without a workspace, for callers that cannot allocate ---------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the
+ * same computation and outputs as moe_route, bit for bit, but the scratch (the per-chunk expert
+ * histograms) is a static device array of MOE_ROUTE_NOALLOC_SCRATCH_BYTES inside the library
+ * instead of a caller workspace.  The call allocates nothing and frees nothing; the first call
+ * on a device looks up that device's copy of the array (no allocation, but make it before a
+ * graph capture starts).  Limit: ceil(T / c) * E * 4 <= MOE_ROUTE_NOALLOC_SCRATCH_BYTES, where
+ * c = 64, 128, 256, ... is the smallest chunk with ceil(T / c) <= 1024 -- any T for E <= 64,
+ * T <= 16384 for E = 256; beyond it the call returns MOE_ERR_UNSUPPORTED and moe_route is the
+ * one to use.  All calls on one GPU share that GPU's array: two calls that overlap in time on
+ * one GPU (different streams) race; calls on one stream, or on different GPUs, do not.  The
+ * array keeps the last call's contents and nothing in it needs clearing: every entry a call
+ * reads it has written itself. */
+#define MOE_ROUTE_NOALLOC_SCRATCH_BYTES ((size_t)256 * 1024)
+int moe_route_noalloc(const float* logits /*[T,E]*/, int T, int E, int k, int renorm,
+                      int32_t* topk_idx /*[T,k]*/, float* topk_w /*[T,k]*/,
+                      int32_t* counts /*[E]*/, int32_t* offsets /*[E+1]*/,
+                      int32_t* perm /*[T*k]*/, int32_t* inv_perm /*[T*k]*/, void* stream);
+
 /* The same for one GPU's expert-parallel share (Section 3.2: after the all-gather of the tokens a
  * local scatter keeps only those routed to local experts; Section 3.1: each rank holds E/n
  * experts).  The gate runs over all E experts; only assignments whose expert lies in

@@ -27,6 +27,7 @@ EXPORTS = (
     "moe_expert_ffn_bwd_fp8", "moe_tgroup_tokens", "moe_quant_fp8_tgroup", "moe_route_range",
     "moe_route_capacity_workspace_bytes", "moe_route_capacity", "moe_balance_loss", "moe_balance_loss_bwd",
     "moe_row_map", "moe_expert_ffn_fused_workspace_bytes", "moe_expert_ffn_fused_fwd", "moe_expert_ffn_fused_bwd",
+    "moe_route_noalloc",
 )
 
 
@@ -69,6 +70,7 @@ def _load() -> ctypes.CDLL:
         "moe_router_fwd": (I, [P, P, P, I, I, I, I, P, P]),
         "moe_router_bwd": (I, [P, P, P, I, I, I, I, P, P, P, Z, P]),
         "moe_route": (I, [P, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
+        "moe_route_noalloc": (I, [P, I, I, I, I, P, P, P, P, P, P, P]),
         "moe_route_range": (I, [P, I, I, I, I, I, I, P, P, P, P, P, P, P, Z, P]),
         "moe_route_capacity_workspace_bytes": (Z, [I, I, I]),
         "moe_route_capacity": (I, [P, I, I, I, I, I, I, P, P, P, P, P, P, P, P, Z, P]),
@@ -155,6 +157,12 @@ def moe_route(logits, k, renorm, topk_idx, topk_w, counts, offsets, perm, inv_pe
     _check("moe_route", _lib.moe_route(_p(logits), T, E, k, renorm, _p(topk_idx), _p(topk_w), _p(counts),
                                        _p(offsets), _p(perm), _p(inv_perm), _p(workspace),
                                        workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_route_noalloc(logits, k, renorm, topk_idx, topk_w, counts, offsets, perm, inv_perm):
+    T, E = logits.shape
+    _check("moe_route_noalloc", _lib.moe_route_noalloc(_p(logits), T, E, k, renorm, _p(topk_idx), _p(topk_w), _p(counts),
+                                                       _p(offsets), _p(perm), _p(inv_perm), _stream()))
 
 
 def moe_route_bwd(logits, topk_idx, topk_w, d_topk_w, E, renorm, d_logits):

@@ -1,0 +1,93 @@
+"""moe_route_noalloc (the entry point for callers that cannot allocate) against moe_route, through the raw C ABI:
+two calls in a row on one stream, the second with a smaller input, every output bit for bit; then the size
+limit.  The static scratch keeps the first call's contents when the second one runs."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2505_11432_amd", "libmoe_hip.so")
+
+P, I, Z = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+
+
+def _lib():
+    if not os.path.exists(LIB):
+        from paper_2505_11432_amd.build import build
+        build(verbose=False)
+    lib = ctypes.CDLL(LIB)
+    lib.moe_route.restype = I
+    lib.moe_route.argtypes = [P, I, I, I, I, P, P, P, P, P, P, P, Z, P]
+    lib.moe_route_noalloc.restype = I
+    lib.moe_route_noalloc.argtypes = [P, I, I, I, I, P, P, P, P, P, P, P]
+    lib.moe_workspace_bytes.restype = Z
+    lib.moe_workspace_bytes.argtypes = [I] * 6
+    return lib
+
+
+def _outputs(T, E, k):
+    import torch
+    dev = "cuda:0"
+    M = T * k
+    # filled with a pattern so that an entry a call failed to write shows up in the comparison
+    return dict(idx=torch.full((T, k), -7, dtype=torch.int32, device=dev), w=torch.full((T, k), -7.0, device=dev),
+                counts=torch.full((E,), -7, dtype=torch.int32, device=dev),
+                offsets=torch.full((E + 1,), -7, dtype=torch.int32, device=dev),
+                perm=torch.full((M,), -7, dtype=torch.int32, device=dev),
+                inv_perm=torch.full((M,), -7, dtype=torch.int32, device=dev))
+
+
+def _logits(T, E, seed):
+    import torch
+    rng = np.random.Generator(np.random.PCG64([seed, 77]))
+    z = rng.standard_normal((T, E)).astype(np.float32)
+    z[: T // 8] = np.round(z[: T // 8] * 2) / 2          # ties: the order inside an expert must still be unique
+    return torch.from_numpy(z).to("cuda:0")
+
+
+def _run_pair(lib, T, E, k, renorm, seed):
+    import torch
+    print(f"moe_route_noalloc vs moe_route: T={T} E={E} k={k} renorm={renorm} seed={seed}", flush=True)
+    z = _logits(T, E, seed)
+    ref, got = _outputs(T, E, k), _outputs(T, E, k)
+    ws_bytes = lib.moe_workspace_bytes(T, 16, E, k, 16, 1)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    rc = lib.moe_route(z.data_ptr(), T, E, k, renorm, ref["idx"].data_ptr(), ref["w"].data_ptr(), ref["counts"].data_ptr(),
+                       ref["offsets"].data_ptr(), ref["perm"].data_ptr(), ref["inv_perm"].data_ptr(), ws.data_ptr(),
+                       ws_bytes, stream)
+    assert rc == 0
+    rc = lib.moe_route_noalloc(z.data_ptr(), T, E, k, renorm, got["idx"].data_ptr(), got["w"].data_ptr(),
+                               got["counts"].data_ptr(), got["offsets"].data_ptr(), got["perm"].data_ptr(),
+                               got["inv_perm"].data_ptr(), stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    for name in ref:
+        a, b = ref[name].cpu().numpy(), got[name].cpu().numpy()
+        assert np.array_equal(a.view(np.int32), b.view(np.int32)), name      # bit for bit, the float weights included
+    assert int(got["offsets"][-1]) == T * k
+    assert int(got["counts"].sum()) == T * k
+
+
+@pytest.mark.gpu
+def test_route_noalloc_matches_route_twice_second_smaller():
+    import torch
+    lib = _lib()
+    before = torch.cuda.memory_allocated()
+    _run_pair(lib, 5000, 64, 8, 1, seed=1)        # 79 chunks x 64 experts of scratch
+    _run_pair(lib, 333, 8, 2, 0, seed=2)          # smaller: 6 chunks x 8 experts, over the first call's leftovers
+    _run_pair(lib, 16384, 256, 16, 1, seed=3)     # exactly at the limit: 256 chunks x 256 experts x 4 bytes
+    assert torch.cuda.memory_allocated() == before        # (the test's own tensors are gone; the library holds none)
+
+
+def test_route_noalloc_rejects_sizes_beyond_the_scratch():
+    lib = _lib()
+    fake = P(4096)
+    # 1024 chunks x 256 experts x 4 bytes = 1 MiB > 256 KiB: refused before any GPU work
+    assert lib.moe_route_noalloc(fake, 70000, 256, 2, 1, fake, fake, fake, fake, fake, fake, None) == -2
+    assert lib.moe_route_noalloc(fake, 16448, 256, 2, 1, fake, fake, fake, fake, fake, fake, None) == -2
+    assert lib.moe_route_noalloc(fake, 16, 8, 9, 1, fake, fake, fake, fake, fake, fake, None) == -1     # k > E
+    assert lib.moe_route_noalloc(None, 16, 8, 2, 1, fake, fake, fake, fake, fake, fake, None) == -1
+    assert lib.moe_route_noalloc(None, 0, 8, 2, 1, None, None, None, None, None, None, None) == 0
