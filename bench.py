@@ -54,10 +54,9 @@ def parse():
 
 
 def ensure_built():
-    lib = os.path.join(ROOT, "paper_2505_11432_amd", "libmoe_hip.so")
-    if not os.path.exists(lib):
-        from paper_2505_11432_amd.build import build
-        build(verbose=False)
+    # builds when the library is missing or was built from other sources than the ones in the tree
+    from paper_2505_11432_amd.build import ensure_built as ensure
+    ensure()
 
 
 def to_dev_bf16(a, torch):

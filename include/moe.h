@@ -22,8 +22,9 @@
  *     per token, M = T*k dispatched rows.  Assignment id a = t*k + j (token t, slot j).
  *   - d and f must be multiples of 16; 1 <= k <= E <= MOE_MAX_EXPERTS; k <= MOE_MAX_TOPK.
  *   - T = 0 is valid and does nothing.  Non-finite logits give an unspecified routing.
- *   - Calls on different streams may run concurrently as long as their buffers (workspace
- *     included) do not overlap.
+ *   - Calls on different streams or from different threads may run concurrently as long as
+ *     their buffers (workspace included) do not overlap; the library keeps no mutable state
+ *     beyond per-device set-up flags, which are atomic (see moe_init).
  */
 #ifndef MOE_HIP_MOE_H
 #define MOE_HIP_MOE_H
@@ -54,6 +55,14 @@ int moe_abi_version(void);
 /* hipError_t value of the last failed HIP call made by this thread (0 if none). */
 int moe_last_hip_error(void);
 const char* moe_status_string(int status);
+
+/* Optional one-time set-up for the CURRENT device: raises the dynamic-LDS limit of every
+ * grouped-GEMM kernel and looks up the static scratch of moe_route_noalloc.  Without it each
+ * kernel does its own set-up on its first launch on a device (thread-safe, but not a stream
+ * operation): a caller that records the calls of this library into a HIP graph either calls
+ * moe_init() first or runs every call once, eagerly, before the capture starts.  Idempotent;
+ * allocates nothing; call it again after switching to another device. */
+int moe_init(void);
 
 /* Bytes of scratch that the largest consumer (moe_expert_ffn_bwd) needs for these sizes;
  * valid for every call of this library with the same sizes.  0 on invalid sizes. */
@@ -166,7 +175,9 @@ int moe_route_bwd(const float* logits, const int32_t* topk_idx, const float* top
 /* ---- dispatch / combine (Section 3.2: scatter and gather driven by the row map) -------
  * moe_dispatch: xp[inv_perm[t*k+j], :] = x[t, :] for every slot j, i.e. xp[r,:] =
  * x[perm[r] / k, :]  (* row_mul[t*k+j] if row_mul != NULL; with row_mul = topk_w this is
- * the backward of the weighted combine).  Every row of xp below T*k is written.
+ * the backward of the weighted combine).  The rows of assignments that have a row (inv_perm >= 0) are
+ * written; after moe_route that is every row below T*k; after moe_route_range or
+ * moe_route_capacity the rows at or past offsets[E] are left untouched.
  * dt = MOE_F32 | MOE_BF16 | MOE_F8E4M3.  For MOE_F8E4M3 rows are 1-byte codes and the
  * per-token scale x_scale[t] is copied to xp_scale[row]; row_mul must then be NULL. */
 int moe_dispatch(const void* x /*[T,d]*/, const float* x_scale /*[T] or NULL*/, moe_dtype dt,
@@ -287,6 +298,14 @@ int moe_quant_fp8(const void* src, moe_dtype src_dt, int rows, int cols, moe_qmo
                   float* scales /*[rows] or [ceil(rows/128),cols]*/, void* stream);
 int moe_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int cols,
                     moe_qmode mode, void* dst, moe_dtype dst_dt, void* stream);
+
+/* Batched transpose, dst[b][c][r] = src[b][r][c] for b < batch (src [batch,rows,cols], dst
+ * [batch,cols,rows], dense, element type dt; MOE_F8E4M3 = bytes).  A set-up helper, not a step of
+ * the layer: the FP8 backward (Section 7 "FP8 training", per-channel quantisation for the backward
+ * pass) needs the weights cast along their other axis, i.e. moe_quant_fp8 over W1[e]^T and W2[e]^T.
+ * src and dst must not overlap.  batch <= 65535, rows <= 64 * 65535. */
+int moe_transpose(const void* src, moe_dtype dt, int batch, int rows, int cols, void* dst,
+                  void* stream);
 
 /* ---- FP8 backward GEMMs of the expert FFN (Section 7 "FP8 training": per-token quantisation
  * in the forward orientation, per-channel quantisation within 128-token groups for the

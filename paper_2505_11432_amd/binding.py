@@ -27,7 +27,7 @@ EXPORTS = (
     "moe_expert_ffn_bwd_fp8", "moe_tgroup_tokens", "moe_quant_fp8_tgroup", "moe_route_range",
     "moe_route_capacity_workspace_bytes", "moe_route_capacity", "moe_balance_loss", "moe_balance_loss_bwd",
     "moe_row_map", "moe_expert_ffn_fused_workspace_bytes", "moe_expert_ffn_fused_fwd", "moe_expert_ffn_fused_bwd",
-    "moe_route_noalloc",
+    "moe_route_noalloc", "moe_init", "moe_transpose",
 )
 
 
@@ -57,6 +57,12 @@ class MoEError(RuntimeError):
 
 
 def _load() -> ctypes.CDLL:
+    from . import build as _build
+    if not _build.is_current():
+        # missing, or built from other sources than the ones in the tree: never load a stale library
+        import sys
+        sys.stderr.write(f"{LIB_PATH} is missing or older than its sources: building it\n")
+        _build.build(verbose=False)
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2505_11432_amd.build` "
                           "(there is no fallback path)")
@@ -64,6 +70,7 @@ def _load() -> ctypes.CDLL:
     P, I, Z = c_void_p, c_int, c_size_t
     sig = {
         "moe_abi_version": (I, []),
+        "moe_init": (I, []),
         "moe_last_hip_error": (I, []),
         "moe_status_string": (c_char_p, [I]),
         "moe_workspace_bytes": (Z, [I, I, I, I, I, I]),
@@ -86,6 +93,7 @@ def _load() -> ctypes.CDLL:
         "moe_dequant_fp8": (I, [P, P, I, I, I, P, I, P]),
         "moe_expert_ffn_bwd_fp8": (I, [ctypes.POINTER(FfnBwdFp8Args), P]),
         "moe_tgroup_tokens": (Z, [I, I]),
+        "moe_transpose": (I, [P, I, I, I, I, P, P]),
         "moe_row_map": (I, [P, P, P, I, I, I, P, P, P]),
         "moe_expert_ffn_fused_workspace_bytes": (Z, [I, I, I, I]),
         "moe_expert_ffn_fused_fwd": (I, [P, P, P, P, P, P, I, I, I, I, I, P, P, P, Z, P]),
@@ -131,6 +139,10 @@ def _check(fn: str, status: int):
 
 def moe_abi_version() -> int:
     return _lib.moe_abi_version()
+
+
+def moe_init():
+    _check("moe_init", _lib.moe_init())
 
 
 def moe_workspace_bytes(T, d, E, k, f, act) -> int:
@@ -219,6 +231,13 @@ def moe_dequant_fp8(codes, scales, mode, dst):
     rows, cols = codes.shape
     _check("moe_dequant_fp8", _lib.moe_dequant_fp8(_p(codes), _p(scales), rows, cols, mode, _p(dst),
                                                    dtype_code(dst.dtype), _stream()))
+
+
+def moe_transpose(src, dst):
+    """src [batch, rows, cols] -> dst [batch, cols, rows]."""
+    batch, rows, cols = src.shape
+    assert tuple(dst.shape) == (batch, cols, rows) and dst.dtype == src.dtype
+    _check("moe_transpose", _lib.moe_transpose(_p(src), dtype_code(src.dtype), batch, rows, cols, _p(dst), _stream()))
 
 
 def moe_tgroup_tokens(rows: int, E: int) -> int:

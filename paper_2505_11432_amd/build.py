@@ -7,6 +7,7 @@ file as libmoe_hip.so; the Python binding loads it with ctypes.
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -16,6 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libmoe_hip.so")
+STAMP_PATH = LIB_PATH + ".sha256"      # hash of the sources the library was built from
+INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON_FLAGS = [
@@ -28,6 +31,34 @@ COMMON_FLAGS = [
 
 def sources() -> list[str]:
     return sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
+
+
+def source_hash() -> str:
+    """SHA-256 over every file the library is compiled from (kernels, internal headers, the public header) and
+    the compiler flags."""
+    h = hashlib.sha256(" ".join(COMMON_FLAGS).encode())
+    files = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h"))]
+    files += [os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h")]
+    for path in sorted(files):
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def is_current() -> bool:
+    """True when the library exists and was built from the sources as they are now."""
+    if not (os.path.exists(LIB_PATH) and os.path.exists(STAMP_PATH)):
+        return False
+    with open(STAMP_PATH) as fh:
+        return fh.read().strip() == source_hash()
+
+
+def ensure_built() -> str:
+    """Build unless an up-to-date library is there: a library left over from older sources is rebuilt, never used."""
+    if not is_current():
+        build(verbose=False)
+    return LIB_PATH
 
 
 def _compile(src: str) -> str:
@@ -45,6 +76,9 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
+    if os.path.exists(STAMP_PATH):
+        os.remove(STAMP_PATH)           # no stamp while the library and the sources may disagree
+    stamp = source_hash()
     srcs = sources()
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
         objs = list(pool.map(_compile, srcs))
@@ -52,6 +86,8 @@ def build(verbose: bool = True) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
+    with open(STAMP_PATH, "w") as fh:
+        fh.write(stamp + "\n")
     if verbose:
         print(f"built {LIB_PATH} from {len(srcs)} sources")
     return LIB_PATH

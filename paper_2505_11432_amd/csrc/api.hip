@@ -174,6 +174,12 @@ const char* moe_status_string(int status) {
   }
 }
 
+int moe_init(void) {
+  const int rc = mfma_configure_all();
+  if (rc != MOE_OK) return rc;
+  return route_noalloc_prepare();
+}
+
 size_t moe_workspace_bytes(int T, int d, int E, int k, int f, moe_dtype act) {
   if (!sizes_ok(T, d, E, k, f)) return 0;
   if (act != MOE_F32 && act != MOE_BF16 && act != MOE_F8E4M3) return 0;
@@ -500,6 +506,15 @@ int moe_dequant_fp8(const uint8_t* codes, const float* scales, int rows, int col
   if (!codes || !scales || !dst) return MOE_ERR_INVALID;
   if (!aligned16(codes) || !aligned16(dst)) return MOE_ERR_UNSUPPORTED;
   return launch_dequant_fp8(codes, scales, rows, cols, mode, dst, dst_dt, as_stream(stream));
+}
+
+int moe_transpose(const void* src, moe_dtype dt, int batch, int rows, int cols, void* dst, void* stream) {
+  if (batch < 0 || rows < 0 || cols < 0 || batch > 65535) return MOE_ERR_INVALID;
+  if (dt != MOE_F32 && dt != MOE_BF16 && dt != MOE_F8E4M3) return MOE_ERR_UNSUPPORTED;
+  if (batch == 0 || rows == 0 || cols == 0) return MOE_OK;
+  if (!src || !dst || src == dst) return MOE_ERR_INVALID;
+  if ((long)cdiv(rows, 64) > 65535) return MOE_ERR_UNSUPPORTED;
+  return launch_transpose(src, dt, batch, rows, cols, dst, as_stream(stream));
 }
 
 size_t moe_tgroup_tokens(int rows, int E) {

@@ -54,7 +54,6 @@ struct Args {
   int a_phys_rows;                   //   rows of that buffer (for the 32-bit offset check)
   const float* row_w;                // [M] gate weight of each row: A_out = w * SwiGLU(G, U) in both epilogues
   float* dw_part;                    // EPI_SWIGLU_BWD_W: [n-tiles * waves along n][M] partial sums of <dA'[r,:], A[r,:]>
-  unsigned long long* clk_out;       // tuning aid (NULL in the library): per-block {core clocks, 100 MHz ticks}
 };
 
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }

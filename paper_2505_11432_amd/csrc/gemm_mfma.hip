@@ -1,6 +1,9 @@
 // Launchers of the grouped MFMA GEMM (asynchronous global->LDS pipeline) for the bf16 expert FFN
 // (Section 4.1: FC1 -> SwiGLU -> FC2 and the backward of each) and for the router matmul.
 // Tile shapes, wave layouts and pipeline depths were picked by measurement on MI355X.
+#include <atomic>
+#include <vector>
+
 #include "gemm_mfma_dma.h"
 
 namespace moe {
@@ -8,24 +11,57 @@ namespace {
 
 using namespace mfma;
 
-// One persistent workgroup per CU, in whole rounds of 8 (one per XCD).
-int persistent_grid(int* grid) {
-  static int cached[64] = {0};
-  int dev = 0;
-  MOE_HIP_TRY(hipGetDevice(&dev));
-  if (dev < 0 || dev >= 64) return MOE_ERR_UNSUPPORTED;
-  if (cached[dev] == 0) {
+constexpr int kMaxDevices = 64;
+
+// One persistent workgroup per CU, in whole rounds of 8 (one per XCD).  The CU count of a device is looked up once;
+// concurrent first calls may both look it up and store the same value.
+int persistent_grid(int dev, int* grid) {
+  static std::atomic<int> cached[kMaxDevices];
+  int g = cached[dev].load(std::memory_order_acquire);
+  if (g == 0) {
     int cus = 0;
     MOE_HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    cached[dev] = cus >= 8 ? cus / 8 * 8 : 8;
+    g = cus >= 8 ? cus / 8 * 8 : 8;
+    cached[dev].store(g, std::memory_order_release);
   }
-  *grid = cached[dev];
+  *grid = g;
   return MOE_OK;
 }
+
+// Every kernel instantiation needs its dynamic-LDS limit raised once per device before its first launch.  Each
+// instantiation registers its set-up function when the library is loaded, so that moe_init can run all of them
+// ahead of time (a first call under graph capture must not be the one that sets the attribute).
+typedef int (*configure_fn)(int dev);
+std::vector<configure_fn>& configure_registry() {
+  static std::vector<configure_fn> r;
+  return r;
+}
+
+template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC, typename TIN>
+struct KernelSetup {
+  static constexpr int smem = dma_smem_bytes<BM, BN, BKT, NS, LA, LB, (int)sizeof(TIN)>();
+  static auto kernel() { return grouped_gemm_dma_kernel<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC, TIN>; }
+  // Idempotent and safe to race: the attribute value is the same on every call, the per-device bit only saves work.
+  static int configure(int dev) {
+    static std::atomic<unsigned long long> done{0};
+    const unsigned long long bit = 1ull << dev;
+    if (done.load(std::memory_order_acquire) & bit) return MOE_OK;
+    MOE_HIP_TRY(hipFuncSetAttribute((const void*)kernel(), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+    done.fetch_or(bit, std::memory_order_release);
+    return MOE_OK;
+  }
+  struct Registrar { Registrar() { configure_registry().push_back(&configure); } };
+  static Registrar registrar;
+};
+template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC, typename TIN>
+typename KernelSetup<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC, TIN>::Registrar
+    KernelSetup<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC, TIN>::registrar;
 
 template <int BM, int BN, int BKT, int NS, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC,
           typename TIN = bf16>
 int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
+  using Setup = KernelSetup<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC, TIN>;
+  (void)&Setup::registrar;           // instantiates the registration of this kernel
   if (tiles_upper_bound <= 0) return MOE_OK;
   {
     // the kernel addresses each operand as a 64-bit tile base plus a 32-bit per-lane byte offset
@@ -37,16 +73,16 @@ int launch(const Args& a, long tiles_upper_bound, hipStream_t s) {
     const unsigned long long b_span = (LB == KMAJOR) ? b_rows * a.ldb * esz : ((unsigned long long)BKT * a.ldb + a.N) * esz;
     if (a_span >= lim || b_span >= lim) return MOE_ERR_UNSUPPORTED;
   }
+  int dev = 0;
+  MOE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
   int blocks = 0;
-  const int rc = persistent_grid(&blocks);
+  int rc = persistent_grid(dev, &blocks);
   if (rc != MOE_OK) return rc;
-  auto kern = grouped_gemm_dma_kernel<BM, BN, BKT, NS, WM, WN, LA, LB, MODE, EPI, TC, 0, TIN>;
-  constexpr int smem = dma_smem_bytes<BM, BN, BKT, NS, LA, LB, (int)sizeof(TIN)>();
-  static bool configured = false;    // one flag per instantiation; the attribute is per function
-  if (!configured) {
-    MOE_HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-    configured = true;
-  }
+  rc = Setup::configure(dev);
+  if (rc != MOE_OK) return rc;
+  auto kern = Setup::kernel();
+  constexpr int smem = Setup::smem;
   Args args = a;
   constexpr bool kSplitK = MODE == ROWSEG && EPI == EPI_STORE && sizeof(TC) == 2;
   if (!kSplitK || args.accumulate || blocks > MOE_SPLITK_MAX_PARTS) args.splitk_ws = nullptr;
@@ -245,6 +281,20 @@ int mfma_router_fwd(const void* x, const void* w_r, const float* bias, int T, in
   if (E <= 32) return launch<64, 32, 64, 8, 2, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, cdiv(T, 64), s);
   if (E <= 64) return launch<64, 64, 64, 8, 2, 1, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, cdiv(T, 64), s);
   return launch<256, 128, 64, 2, 4, 2, KMAJOR, KMAJOR, PLAIN, EPI_BIAS_F32, float>(a, mt * cdiv(E, 128), s);
+}
+
+// Sets up every grouped-GEMM kernel of this library for the current device (see moe_init).
+int mfma_configure_all() {
+  int dev = 0;
+  MOE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
+  int grid = 0;
+  int rc = persistent_grid(dev, &grid);
+  for (configure_fn fn : configure_registry()) {
+    if (rc != MOE_OK) break;
+    rc = fn(dev);
+  }
+  return rc;
 }
 
 }  // namespace moe

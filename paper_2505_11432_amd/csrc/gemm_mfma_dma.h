@@ -343,7 +343,7 @@ __global__ void __launch_bounds__(256) splitk_fixup_kernel(const float* __restri
 }
 
 template <int BM, int BN, int BKT, int NSTAGE, int WM, int WN, Layout LA, Layout LB, Mode MODE, Epi EPI, typename TC,
-          int PROBE = 0, typename TIN = bf16>   // TIN = uint8_t: e4m3 codes, K-major operands only   // PROBE (tuning only): 1 = no global loads, 2 = no LDS reads / MFMAs, 3 = all tiles load tile 0
+          typename TIN = bf16>   // TIN = uint8_t: e4m3 codes, K-major operands only
 __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) {
   constexpr int NW = WM * WN;
   constexpr int WTM = BM / WM, WTN = BN / WN;
@@ -539,8 +539,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     }
     const char* Ag = static_cast<const char*>(p.A);
     const char* Bg = static_cast<const char*>(p.B) + (long)e * p.b_es * ESZ;
-    const int real_m0 = m0, real_n0 = n0;
-    if constexpr (PROBE == 3) { m0 = 0; n0 = 0; Bg = static_cast<const char*>(p.B); }      // every tile loads the same panels (all L2 hits)
     // Base of each operand at the tile's first k (wave-uniform) and this lane's fixed byte offset from it.
     // Load j of loader wave lw fills DMA slot q = lw + j*NL of the tile (1 KiB of LDS each).
     if constexpr (GATHER_A) a_base = uniform_ptr(Ag + (long)k_begin * ESZ);          // row offsets are absolute
@@ -613,7 +611,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       const int kr = (lane >> 5) * BKT + (((lane & 31) >> 2));
       ta_off = (unsigned)(kr + qa * 8) * (unsigned)(p.lda * ESZ) + (unsigned)(min(m0 + (lane & 3) * 64, p.M - 8) * ESZ);
     }
-    m0 = real_m0; n0 = real_n0;
     if constexpr (BSCALE) {
       const long g0 = k_begin / BKT;
       sa_base = uniform_ptr(reinterpret_cast<const char*>(p.a_e8m0) + g0 * p.a_e8_ld);
@@ -626,7 +623,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   };
   // Issue the loads of k-step `ks` of the open tile into ring slot ks % NSTAGE.  Only the last step can be ragged.
   auto issue = [&](int ks) __attribute__((always_inline)) {
-    if constexpr (PROBE == 1) return;
     if (!is_loader) return;
     const unsigned stage = smem_lds + (unsigned)(ks % NSTAGE) * STAGE_BYTES;
     const int k_left = klen - ks * BKT;          // valid k in this step
@@ -680,8 +676,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
   issue_prologue();
 
   for (;;) {
-    unsigned long long clk0 = 0, rt0 = 0;
-    if (p.clk_out) { clk0 = __builtin_readcyclecounter(); rt0 = __builtin_amdgcn_s_memrealtime(); }
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -728,7 +722,7 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       // A wave whose rows all lie past the expert's last row has nothing to multiply (wave-uniform; it still issues
       // its loads and takes part in the barriers).  In a nearly empty last tile of an expert only one or two waves
       // per CU then use the matrix cores, and the k-step shrinks to what the loads need.
-      const bool wave_active = PROBE != 2 && (MODE != ROWSEG || m0 + wm * WTM < m_end);
+      const bool wave_active = MODE != ROWSEG || m0 + wm * WTM < m_end;
       if (!wave_active) {
         for (int s = 0; s < nk; ++s) open_step(s);
       } else if (nk > 0) {
@@ -786,7 +780,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
       }
       const char* at = smem + (kt % NSTAGE) * STAGE_BYTES;
       const char* bt = at + A_BYTES;
-      if constexpr (PROBE == 2) continue;
       if constexpr (MODE == ROWSEG) {
         // A wave whose rows all lie past the expert's last row has nothing to multiply (wave-uniform; it still
         // issued its loads and takes part in the barriers).  In a nearly empty last tile of an expert only one or
@@ -834,10 +827,6 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
       }
-    }
-    if (p.clk_out && tid == 0 && blockIdx.x < 2048) {
-      p.clk_out[2 * blockIdx.x] += __builtin_readcyclecounter() - clk0;
-      p.clk_out[2 * blockIdx.x + 1] += __builtin_amdgcn_s_memrealtime() - rt0;
     }
 
     if constexpr (TOUCH || TOUCH_K || TOUCH_K2) {

@@ -139,8 +139,12 @@ int mfma_router_dwr(const void* g, const void* x, const int32_t* chunk_offsets, 
                     int accumulate, hipStream_t s);
 int mfma_router_dx(const void* g, const void* w_r, int T, int d, int E, void* dx, hipStream_t s);
 size_t router_bwd_ws_bytes(int T, int d, int E);
+int mfma_configure_all();          // per-device set-up of every grouped-GEMM kernel (moe_init)
+int route_noalloc_prepare();       // looks up this device's static routing scratch (moe_init)
 int launch_router_bwd(const void* x, const void* w_r, const float* d_logits, moe_dtype dt, int T, int d, int E,
                       float* d_w_r, void* dx, void* ws, hipStream_t s);
+
+int launch_transpose(const void* src, moe_dtype dt, int batch, int rows, int cols, void* dst, hipStream_t s);
 
 int launch_swiglu_fwd(const void* H, void* A, int M, int f, const int32_t* row_limit, moe_dtype dt, hipStream_t s);
 int launch_swiglu_bwd(const void* H, const void* dA, void* dH, int M, int f, const int32_t* row_limit,

@@ -31,6 +31,7 @@ class MoELayer:
         assert not (capacity is not None and (fp8 or expert_range is not None))
         self.E_local = E if expert_range is None else expert_range[1] - expert_range[0]
         assert not (fp8 and expert_range is not None), "the fp8 path needs offsets[E] = M"
+        assert not (fp8 and balance is not None), "the fp8 path has no balance loss"
         self.dtype, self.renorm, self.fp8, self.device = dtype, renorm, fp8, device
         M = self.M
         dev = dict(device=device)
@@ -128,16 +129,18 @@ class MoELayer:
 
     def set_fp8_backward_weights(self, w1, w2):
         """Second, transposed-orientation E4M3 copies of the weights for the dgrad GEMMs (one scale per input
-        channel), also kept across steps, and the buffers the FP8 backward writes.  The transposition is a
-        layout change of a parameter done once at set-up (torch), not a step of the timed path."""
+        channel), also kept across steps, and the buffers the FP8 backward writes.  Set-up, not a step of the
+        timed path."""
         E, two_f, d = w1.shape
         f = two_f // 2
         M = self.M
         dev = dict(device=w1.device)
         u8 = dict(dtype=torch.uint8, **dev)
         f32 = dict(dtype=torch.float32, **dev)
-        w1t = w1.transpose(1, 2).contiguous()          # [E, d, 2f]
-        w2t = w2.transpose(1, 2).contiguous()          # [E, f, d]
+        w1t = torch.empty((E, d, two_f), dtype=w1.dtype, **dev)
+        w2t = torch.empty((E, f, d), dtype=w2.dtype, **dev)
+        B.moe_transpose(w1, w1t)
+        B.moe_transpose(w2, w2t)
         self.w1t_codes = torch.empty((E, d, two_f), **u8)
         self.w1t_scale = torch.empty((E, d), **f32)
         self.w2t_codes = torch.empty((E, f, d), **u8)
@@ -224,23 +227,27 @@ class MoELayer:
             c("router_fwd", B.moe_router_fwd, x, w_r, bias, self.logits)
         else:
             self.logits.copy_(logits)
-        if self.balance is not None:
-            # the loss counts every assignment, dropped or not: take the counts of the plain row map first
-            c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
-              self.offsets, self.perm, self.inv_perm, self.workspace)
+        def balance_loss():
+            # the loss counts every assignment, dropped or not, local or not: `counts` of moe_route / moe_route_range
             c("balance_loss", B.moe_balance_loss, self.logits, self.counts, self.k, self.balance[0], self.balance[1],
               self.aux_loss, self.group_f, self.group_p, self.workspace)
+
         if self.capacity is not None:
+            if self.balance is not None:
+                c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
+                  self.offsets, self.perm, self.inv_perm, self.workspace)
+                balance_loss()
             c("route", B.moe_route_capacity, self.logits, self.k, self.renorm, self.capacity[0], self.capacity[1],
               self.topk_idx, self.topk_w, self.score, self.counts, self.offsets, self.perm, self.inv_perm, self.route_ws)
-        elif self.balance is not None:
-            pass
-        elif self.expert_range is None:
-            c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
-              self.offsets, self.perm, self.inv_perm, self.workspace)
         else:
-            c("route", B.moe_route_range, self.logits, self.k, self.renorm, self.expert_range[0], self.expert_range[1],
-              self.topk_idx, self.topk_w, self.counts, self.offsets, self.perm, self.inv_perm, self.workspace)
+            if self.expert_range is None:
+                c("route", B.moe_route, self.logits, self.k, self.renorm, self.topk_idx, self.topk_w, self.counts,
+                  self.offsets, self.perm, self.inv_perm, self.workspace)
+            else:
+                c("route", B.moe_route_range, self.logits, self.k, self.renorm, self.expert_range[0], self.expert_range[1],
+                  self.topk_idx, self.topk_w, self.counts, self.offsets, self.perm, self.inv_perm, self.workspace)
+            if self.balance is not None:
+                balance_loss()
         if self.fused:
             c("row_map", B.moe_row_map, self.perm, self.topk_w, self.offsets, self.row_token, self.row_w)
             c("expert_ffn_fwd", B.moe_expert_ffn_fused_fwd, x, self.row_token, self.row_w, self.offsets, w1, w2, self.k,

@@ -13,9 +13,8 @@ HEADER = os.path.join(ROOT, "include", "moe.h")
 
 @pytest.fixture(scope="module")
 def lib():
-    if not os.path.exists(LIB):
-        from paper_2505_11432_amd.build import build
-        build(verbose=False)
+    from paper_2505_11432_amd.build import ensure_built
+    ensure_built()
     return ctypes.CDLL(LIB)
 
 
@@ -172,3 +171,24 @@ def test_fused_order_argument_errors_without_gpu(lib):
     assert bwd(fake, 2, fake, need) == -2            # weight gradients are fp32 or bf16
     assert bwd(fake, 0, null, need) == -1
     assert bwd(fake, 0, fake, need - 1) == -3
+
+
+def test_stale_library_is_detected(monkeypatch):
+    """The build stamps the library with a hash of its sources; a library from other sources is not current."""
+    from paper_2505_11432_amd import build
+    build.ensure_built()
+    assert build.is_current()
+    real = build.source_hash()
+    monkeypatch.setattr(build, "source_hash", lambda: "0" * 64)
+    assert not build.is_current()
+    monkeypatch.undo()
+    assert build.source_hash() == real and build.is_current()
+
+
+def test_transpose_and_init_argument_errors(lib):
+    P = ctypes.c_void_p
+    fake, other = P(4096), P(8192)
+    assert lib.moe_transpose(fake, 1, 1, 8, 8, fake, None) == -1          # in place is not supported
+    assert lib.moe_transpose(None, 1, 1, 8, 8, other, None) == -1
+    assert lib.moe_transpose(fake, 9, 1, 8, 8, other, None) == -2
+    assert lib.moe_transpose(None, 1, 0, 8, 8, None, None) == 0

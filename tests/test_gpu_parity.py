@@ -538,6 +538,18 @@ def test_layer_fp8_backward_gemms(B, cfg):
           "dW1", f"{max_norm_err(dW1, to_np(layer.d_w1)):.2e}", "dW2", f"{max_norm_err(dW2, to_np(layer.d_w2)):.2e}")
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32, torch.uint8])
+@pytest.mark.parametrize("batch,rows,cols", [(1, 64, 64), (3, 100, 37), (2, 1, 300), (4, 130, 257)])
+def test_transpose_exact(B, dtype, batch, rows, cols):
+    B.moe_init()                                                 # idempotent set-up call; must not disturb anything
+    g = torch.Generator(device="cpu").manual_seed(rows * 1000 + cols)
+    src = torch.randint(0, 250, (batch, rows, cols), generator=g).to(dtype).to(DEV)
+    dst = torch.full((batch, cols, rows), 7, dtype=dtype, device=DEV)
+    B.moe_transpose(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(dst.cpu(), src.cpu().transpose(1, 2).contiguous())
+
+
 # ---- expert-parallel share: routing restricted to an expert range ---------------------------------------------
 @pytest.mark.parametrize("T,E,k,lo,hi", [(300, 12, 3, 4, 9), (1000, 32, 3, 8, 12), (257, 8, 2, 0, 8), (129, 6, 2, 3, 3),
                                          (64, 5, 5, 4, 5), (2000, 64, 8, 56, 64)])
@@ -697,6 +709,46 @@ def test_layer_with_capacity_and_balance_loss(B):
     l_ref, _, _ = O.balance_loss(z, full["idx"], G, alpha)
     assert abs(float(layer.aux_loss[0]) - l_ref) <= 1e-5 * abs(l_ref)
     dz_ref = O.route_bwd(z, r["idx"], r["w"], bwd["dw"]) + O.balance_loss_bwd(z, full["idx"], G, alpha)
+    errs = {"H": max_norm_err(to_np(layer.h_save)[:n], fwd["H"]), "y": max_norm_err(to_np(layer.y), fwd["y"]),
+            "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]), "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
+            "dz": max_norm_err(to_np(layer.d_logits), dz_ref),
+            "dW1": max_norm_err(to_np(layer.d_w1), bwd["dW1"]), "dW2": max_norm_err(to_np(layer.d_w2), bwd["dW2"])}
+    bad = {k_: v for k_, v in errs.items() if not v < tol}
+    assert not bad, bad
+
+
+def test_layer_expert_parallel_share_with_balance_loss(B):
+    """Balance loss on an expert-parallel share: the loss and its gradient see the GLOBAL counts and all E experts,
+    the row map and every row buffer only the local experts (the offsets buffer holds E_local + 1 entries)."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = MoEConfig("epbal", T=520, d=128, E=12, k=3, f=160, dtype="bf16", w_std=0.09, wr_std=0.6)
+    inp = make_inputs(cfg, seed=9)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    z[:, 1] += 0.7
+    G, alpha = 4, 0.03
+    td = torch.bfloat16
+    lo, hi = 3, 6                                               # device 1 of 4
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, expert_range=(lo, hi), balance=(G, alpha))
+    assert layer.offsets.numel() == hi - lo + 1
+    x, dy, wr = to_dev(inp["x"], td), to_dev(inp["dy"], td), to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"][lo:hi], td), to_dev(inp["W2"][lo:hi], td)
+    for t in (layer.xp, layer.yp, layer.d_yp, layer.d_xp, layer.h_save):
+        t.fill_(float("nan"))
+    layer.forward(x, wr, None, w1, w2, logits=to_dev(z))
+    layer.backward(x, wr, w1, w2, dy, with_router=False)
+    torch.cuda.synchronize()
+    fwd = O.layer_fwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, lo, hi)
+    bwd = O.layer_bwd_range(inp["x"], z, inp["W1"][lo:hi], inp["W2"][lo:hi], cfg.k, inp["dy"], fwd)
+    n = int(fwd["offsets"][-1])
+    assert np.array_equal(to_np(layer.offsets), fwd["offsets"]) and np.array_equal(to_np(layer.inv_perm), fwd["inv_perm"])
+    assert np.array_equal(to_np(layer.perm)[:n], fwd["perm"])
+    full = O.route(z, cfg.k)
+    assert np.array_equal(to_np(layer.counts), full["counts"])            # global counts
+    l_ref, f_ref, p_ref = O.balance_loss(z, full["idx"], G, alpha)
+    assert abs(float(layer.aux_loss[0]) - l_ref) <= 1e-5 * abs(l_ref)
+    assert np.allclose(to_np(layer.group_f), f_ref, rtol=1e-6) and np.allclose(to_np(layer.group_p), p_ref, rtol=1e-5)
+    dz_ref = O.route_bwd(z, fwd["idx"], fwd["w"], bwd["dw"]) + O.balance_loss_bwd(z, full["idx"], G, alpha)
+    tol = TOL["bf16"]
     errs = {"H": max_norm_err(to_np(layer.h_save)[:n], fwd["H"]), "y": max_norm_err(to_np(layer.y), fwd["y"]),
             "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]), "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
             "dz": max_norm_err(to_np(layer.d_logits), dz_ref),

@@ -14,9 +14,8 @@ P, I, Z = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 
 
 def _lib():
-    if not os.path.exists(LIB):
-        from paper_2505_11432_amd.build import build
-        build(verbose=False)
+    from paper_2505_11432_amd.build import ensure_built
+    ensure_built()
     lib = ctypes.CDLL(LIB)
     lib.moe_route.restype = I
     lib.moe_route.argtypes = [P, I, I, I, I, P, P, P, P, P, P, P, Z, P]
