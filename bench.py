@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="time K replays of one HIP graph holding the whole step (forward + backward) instead of K eager "
                          "steps; the per-call times and the roofline figure then come from an extra eager pass of K steps")
+    ap.add_argument("--permute-only", default=None, metavar="WORKLOAD",
+                    help="time only dispatch / combine / gate gradient on this workload's activations and print that block")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy, the known-size reference for HBM byte counters")
     return ap.parse_args()
@@ -106,6 +108,60 @@ def cpu_baseline(cfg, inp, tokens):
                       f"numpy float64 forward+backward, {dt:.1f} s"}
 
 
+def permute_large(name="finegrained", reps=20):
+    """Dispatch, combine and gate gradient alone on the activations of a workload whose row buffers (>= 600 MB per
+    pass) do not fit the 256 MB Infinity Cache, so the figure is an HBM rate.  Activations and routing only: no
+    expert weights are drawn.  Bytes per call are the algorithmic ones: every token row and every dispatched row
+    crosses HBM once ((T + T*k) * d * 2 for bf16; the gate gradient only reads)."""
+    import numpy as np
+    import torch
+    from paper_2505_11432_amd import binding as B
+    from synth.moe_inputs import CONFIGS, make_inputs
+    cfg = CONFIGS[name]
+    inp = make_inputs(cfg, seed=0, with_weights=False)
+    dev = "cuda:0"
+    T, d, E, k, M = cfg.T, cfg.d, cfg.E, cfg.k, cfg.M
+    x, dy = to_dev_bf16(inp["x"], torch), to_dev_bf16(inp["dy"], torch)
+    w_r = to_dev_bf16(np.ascontiguousarray(inp["W_r"].T), torch)
+    bias = torch.from_numpy(inp["bias"]).to(dev) if cfg.bias != "none" else None
+    i32 = dict(dtype=torch.int32, device=dev)
+    logits = torch.empty((T, E), device=dev)
+    idx, w = torch.empty((T, k), **i32), torch.empty((T, k), device=dev)
+    counts, offsets = torch.empty((E,), **i32), torch.empty((E + 1,), **i32)
+    perm, inv_perm = torch.empty((M,), **i32), torch.empty((M,), **i32)
+    ws = torch.empty((max(B.moe_workspace_bytes(T, 16, E, k, 16, B.BF16), 256),), dtype=torch.uint8, device=dev)
+    xp = torch.empty((M, d), dtype=torch.bfloat16, device=dev)
+    y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+    dw = torch.empty((T, k), device=dev)
+    B.moe_router_fwd(x, w_r, bias, logits)
+    B.moe_route(logits, k, cfg.renorm, idx, w, counts, offsets, perm, inv_perm, ws)
+    calls = {
+        "dispatch": lambda: B.moe_dispatch(x, None, inv_perm, None, k, xp, None),
+        "dispatch_scaled": lambda: B.moe_dispatch(x, None, inv_perm, w.view(-1), k, xp, None),
+        "combine": lambda: B.moe_combine(xp, None, inv_perm, w, k, y),
+        "combine_unweighted": lambda: B.moe_combine(xp, None, inv_perm, None, k, y),
+        "gate_grad": lambda: B.moe_gate_grad(dy, xp, None, inv_perm, k, dw),
+    }
+    nbytes = float(T + M) * d * 2
+    out = {"workload": f"{cfg.name}: T={T} d_model={d} E={E} top-{k}, bf16 rows, activations and routing only",
+           "bytes_per_call": nbytes, "reps": reps, "ms": {}, "gbps": {}, "peak": PEAK_HBM_GBPS}
+    for cname, fn in calls.items():
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out["ms"][cname] = ms
+        out["gbps"][cname] = nbytes / ms / 1e6
+    out["frac"] = {c: v / PEAK_HBM_GBPS for c, v in out["gbps"].items()}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -116,6 +172,10 @@ def main():
     import numpy as np
     import torch
     from paper_2505_11432_amd import binding as B          # fails loudly if the HIP library is missing
+    if args.permute_only:
+        torch.cuda.set_device(0)
+        print(json.dumps({"permute_large": permute_large(args.permute_only)}))
+        return
     from paper_2505_11432_amd.layer import MoELayer
     from synth.moe_inputs import CONFIGS, make_inputs
 

@@ -17,7 +17,8 @@ __device__ __forceinline__ float bcast(float v, int src) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src));
 }
 
-template <typename T, bool kScaled>
+// One wave per token; CU chunks of 64 lanes x 16 bytes are read before their k copies are written.
+template <typename T, bool kScaled, int CU>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) dispatch_kernel(const T* __restrict__ x,
                                                                        const float* __restrict__ x_scale,
                                                                        const int32_t* __restrict__ inv_perm,
@@ -30,29 +31,35 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) dispatch_kernel(const T* 
   const int nwaves = gridDim.x * kWavesPerBlock;
   const int nvec = d / V;
   for (int t = wave; t < T_; t += nwaves) {
-    int my_row = 0;
+    int my_row = -1;
     float my_mul = 1.f;
     if (lane < k) {
       my_row = inv_perm[(long)t * k + lane];          // < 0: the expert is not local, no copy
       if constexpr (kScaled) my_mul = row_mul[(long)t * k + lane];
       if (x_scale != nullptr && my_row >= 0) xp_scale[my_row] = x_scale[t];
     }
-    if (__ballot(lane < k && my_row >= 0) == 0) continue;      // no local expert wants this token: do not read it
-    for (int c0 = 0; c0 < nvec; c0 += 64) {
-      const int c = c0 + lane;
-      const bool active = c < nvec;
-      Vec16<T> v;
-      if (active) v = *reinterpret_cast<const Vec16<T>*>(x + (long)t * d + (long)c * V);
+    if (__ballot(my_row >= 0) == 0) continue;      // no local expert wants this token: do not read it
+    for (int c0 = 0; c0 < nvec; c0 += 64 * CU) {
+      Vec16<T> v[CU];
+#pragma unroll
+      for (int q = 0; q < CU; ++q) {
+        const int c = c0 + q * 64 + lane;
+        if (c < nvec) v[q] = *reinterpret_cast<const Vec16<T>*>(x + (long)t * d + (long)c * V);
+      }
       for (int j = 0; j < k; ++j) {
         const int r = bcast(my_row, j);
-        Vec16<T> o = v;
-        if constexpr (kScaled) {
-          const float m = bcast(my_mul, j);
+        const float m = bcast(my_mul, j);
 #pragma unroll
-          for (int i = 0; i < V; ++i) o.v[i] = from_f32<T>(to_f32(v.v[i]) * m);
+        for (int q = 0; q < CU; ++q) {
+          const int c = c0 + q * 64 + lane;
+          Vec16<T> o = v[q];
+          if constexpr (kScaled) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) o.v[i] = from_f32<T>(to_f32(v[q].v[i]) * m);
+          }
+          if (c < nvec && r >= 0)
+            __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o), reinterpret_cast<u32x4*>(xp + (long)r * d + (long)c * V));
         }
-        if (active && r >= 0)
-          __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o), reinterpret_cast<u32x4*>(xp + (long)r * d + (long)c * V));
       }
     }
   }
@@ -83,63 +90,117 @@ template <> struct RowLoader<uint8_t> {
   }
 };
 
-template <typename TIN, typename TOUT>
+// Raw 16-byte chunk -> V floats (bf16 / fp32 rows: plain conversion; e4m3 codes: the hardware converter).
+template <typename TIN> __device__ __forceinline__ void decode16(const u32x4& raw, float (&out)[RowLoader<TIN>::V]) {
+  if constexpr (sizeof(TIN) == 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[4 * i + 0] = __builtin_amdgcn_cvt_f32_fp8((int)raw[i], 0);
+      out[4 * i + 1] = __builtin_amdgcn_cvt_f32_fp8((int)raw[i], 1);
+      out[4 * i + 2] = __builtin_amdgcn_cvt_f32_fp8((int)raw[i], 2);
+      out[4 * i + 3] = __builtin_amdgcn_cvt_f32_fp8((int)raw[i], 3);
+    }
+  } else {
+    const Vec16<TIN> v = __builtin_bit_cast(Vec16<TIN>, raw);
+#pragma unroll
+    for (int i = 0; i < RowLoader<TIN>::V; ++i) out[i] = to_f32(v.v[i]);
+  }
+}
+
+// V floats -> TOUT, written as whole 16-byte vectors (streamed: nothing reads the row again soon).
+template <typename TOUT, int V> __device__ __forceinline__ void store_row_chunk(TOUT* dst, const float (&acc)[V]) {
+  constexpr int PER = 16 / sizeof(TOUT);
+#pragma unroll
+  for (int s = 0; s < V / PER; ++s) {
+    Vec16<TOUT> o;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) o.v[i] = from_f32<TOUT>(acc[s * PER + i]);
+    __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o), reinterpret_cast<u32x4*>(dst + s * PER));
+  }
+}
+
+// One wave per token.  The row is walked in groups of CU chunks of 64 lanes x 16 bytes; for each group the chunks of
+// KU slots are all requested before the first of them is used, so a lane keeps KU * CU loads in flight (eight for every
+// k) instead of one.  The k terms are still added in ascending slot order in fp32, whatever KU is.
+template <typename TIN, typename TOUT, int KU, int CU>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) combine_kernel(const TIN* __restrict__ yp,
                                                                       const float* __restrict__ yp_scale,
                                                                       const int32_t* __restrict__ inv_perm,
                                                                       const float* __restrict__ topk_w, int T_, int k,
                                                                       int d, TOUT* __restrict__ y) {
-  constexpr int V = RowLoader<TIN>::V;      // elements per lane per step
+  constexpr int V = RowLoader<TIN>::V;      // elements per lane per chunk
   const int lane = threadIdx.x % 64;
   const int wave = blockIdx.x * kWavesPerBlock + threadIdx.x / 64;
   const int nwaves = gridDim.x * kWavesPerBlock;
   const int nvec = d / V;
   for (int t = wave; t < T_; t += nwaves) {
-    int my_row = 0;
+    int my_row = -1;                         // lanes at or past k: a slot without a row
     float my_w = 1.f;
     if (lane < k) {
       my_row = inv_perm[(long)t * k + lane];
       if (topk_w != nullptr) my_w = topk_w[(long)t * k + lane];
       if (yp_scale != nullptr && my_row >= 0) my_w *= yp_scale[my_row];
     }
-    for (int c0 = 0; c0 < nvec; c0 += 64) {
-      const int c = c0 + lane;
-      const bool active = c < nvec;
-      float acc[V];
+    for (int c0 = 0; c0 < nvec; c0 += 64 * CU) {
+      float acc[CU][V];
 #pragma unroll
-      for (int i = 0; i < V; ++i) acc[i] = 0.f;
-      for (int j = 0; j < k; ++j) {
-        const int r = bcast(my_row, j);
-        const float w = bcast(my_w, j);
-        if (active && r >= 0) {                  // r < 0: no local row, the term is left to another share
-          float v[V];
-          RowLoader<TIN>::load(yp + (long)r * d + (long)c * V, v);
+      for (int q = 0; q < CU; ++q)
 #pragma unroll
-          for (int i = 0; i < V; ++i) acc[i] = fmaf(w, v[i], acc[i]);
+        for (int i = 0; i < V; ++i) acc[q][i] = 0.f;
+      for (int j0 = 0; j0 < k; j0 += KU) {
+        u32x4 raw[KU][CU];
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+          const int r = bcast(my_row, j0 + u);      // r < 0: no local row (the term is left to another share) or j >= k
+#pragma unroll
+          for (int q = 0; q < CU; ++q) {
+            const int c = c0 + q * 64 + lane;
+            raw[u][q] = u32x4{0u, 0u, 0u, 0u};
+            if (r >= 0 && c < nvec) raw[u][q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(yp + (long)r * d + (long)c * V));
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+          const int r = bcast(my_row, j0 + u);
+          const float w = bcast(my_w, j0 + u);
+          if (r >= 0) {                             // (wave-uniform) a skipped term leaves the sum untouched
+#pragma unroll
+            for (int q = 0; q < CU; ++q) {
+              float v[V];
+              decode16<TIN>(raw[u][q], v);
+#pragma unroll
+              for (int i = 0; i < V; ++i) acc[q][i] = fmaf(w, v[i], acc[q][i]);
+            }
+          }
         }
       }
-      if (active) {
-        TOUT* dst = y + (long)t * d + (long)c * V;
 #pragma unroll
-        for (int i = 0; i < V; ++i) dst[i] = from_f32<TOUT>(acc[i]);
+      for (int q = 0; q < CU; ++q) {
+        const int c = c0 + q * 64 + lane;
+        if (c < nvec) store_row_chunk<TOUT, V>(y + (long)t * d + (long)c * V, acc[q]);
       }
     }
   }
 }
 
-template <typename TDY, typename TIN>
+// d_topk_w[t,j] = <dy[t,:], yp[row(t,j),:]>.  Same walk as the combine: per group of CU chunks the dy chunks and the
+// chunks of KU slots are all requested before the first use.
+template <typename TDY, typename TIN, int KU, int CU>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) gate_grad_kernel(const TDY* __restrict__ dy,
                                                                         const TIN* __restrict__ yp,
                                                                         const float* __restrict__ yp_scale,
                                                                         const int32_t* __restrict__ inv_perm, int T_,
                                                                         int k, int d, float* __restrict__ d_topk_w) {
   constexpr int V = RowLoader<TIN>::V;
+  constexpr int DYV = 16 / sizeof(TDY);          // dy elements per 16-byte load
+  constexpr int DYL = V / DYV;                   // 16-byte loads of dy per chunk of V elements
+  static_assert(V % DYV == 0, "a chunk of yp covers whole 16-byte pieces of dy");
   const int lane = threadIdx.x % 64;
   const int wave = blockIdx.x * kWavesPerBlock + threadIdx.x / 64;
   const int nwaves = gridDim.x * kWavesPerBlock;
   const int nvec = d / V;
   for (int t = wave; t < T_; t += nwaves) {
-    int my_row = 0;
+    int my_row = -1;
     float my_scale = 1.f;
     if (lane < k) {
       my_row = inv_perm[(long)t * k + lane];
@@ -148,28 +209,51 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) gate_grad_kernel(const TD
     float acc[MOE_MAX_TOPK];
 #pragma unroll
     for (int j = 0; j < MOE_MAX_TOPK; ++j) acc[j] = 0.f;
-    for (int c0 = 0; c0 < nvec; c0 += 64) {
-      const int c = c0 + lane;
-      const bool active = c < nvec;
-      float g[V];
+    if (__ballot(my_row >= 0) != 0)              // no local row at all: every gradient of this token is 0
+    for (int c0 = 0; c0 < nvec; c0 += 64 * CU) {
+      u32x4 graw[CU][DYL];
 #pragma unroll
-      for (int i = 0; i < V; ++i) g[i] = 0.f;
-      if (active) {
-        const TDY* src = dy + (long)t * d + (long)c * V;
+      for (int q = 0; q < CU; ++q) {
+        const int c = c0 + q * 64 + lane;
 #pragma unroll
-        for (int i = 0; i < V; ++i) g[i] = to_f32(src[i]);
+        for (int h = 0; h < DYL; ++h) {
+          graw[q][h] = u32x4{0u, 0u, 0u, 0u};
+          if (c < nvec) graw[q][h] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dy + (long)t * d + (long)c * V + h * DYV));
+        }
       }
 #pragma unroll
-      for (int j = 0; j < MOE_MAX_TOPK; ++j) {
-        if (j < k) {
-          const int r = bcast(my_row, j);
-          if (active && r >= 0) {
-            float v[V];
-            RowLoader<TIN>::load(yp + (long)r * d + (long)c * V, v);
-            float s = 0.f;
+      for (int j0 = 0; j0 < MOE_MAX_TOPK; j0 += KU) {
+        if (j0 < k) {
+          u32x4 raw[KU][CU];
 #pragma unroll
-            for (int i = 0; i < V; ++i) s = fmaf(g[i], v[i], s);
-            acc[j] += s;
+          for (int u = 0; u < KU; ++u) {
+            const int r = bcast(my_row, j0 + u);
+#pragma unroll
+            for (int q = 0; q < CU; ++q) {
+              const int c = c0 + q * 64 + lane;
+              raw[u][q] = u32x4{0u, 0u, 0u, 0u};
+              if (r >= 0 && c < nvec) raw[u][q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(yp + (long)r * d + (long)c * V));
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < CU; ++q) {
+            float g[V];
+#pragma unroll
+            for (int h = 0; h < DYL; ++h) {
+              float part[DYV];
+              decode16<TDY>(graw[q][h], part);
+#pragma unroll
+              for (int i = 0; i < DYV; ++i) g[h * DYV + i] = part[i];
+            }
+#pragma unroll
+            for (int u = 0; u < KU; ++u) {
+              float v[V];
+              decode16<TIN>(raw[u][q], v);
+              float sum = 0.f;
+#pragma unroll
+              for (int i = 0; i < V; ++i) sum = fmaf(g[i], v[i], sum);
+              acc[j0 + u] += sum;                 // rows that were not loaded are all zero
+            }
           }
         }
       }
@@ -177,11 +261,11 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) gate_grad_kernel(const TD
 #pragma unroll
     for (int j = 0; j < MOE_MAX_TOPK; ++j) {
       if (j < k) {
-        float s = acc[j];
+        float sum = acc[j];
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-        s *= bcast(my_scale, j);
-        if (lane == 0) d_topk_w[(long)t * k + j] = s;
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off);
+        sum *= bcast(my_scale, j);
+        if (lane == 0) d_topk_w[(long)t * k + j] = sum;
       }
     }
   }
@@ -198,14 +282,15 @@ int row_grid(int T) {
 int launch_dispatch(const void* x, const float* x_scale, moe_dtype dt, const int32_t* inv_perm, const float* row_mul,
                     int T, int k, int d, void* xp, float* xp_scale, hipStream_t s) {
   const dim3 grid(row_grid(T)), block(64 * kWavesPerBlock);
+  constexpr int CP = 4, CS = 4;      // chunks read before their copies are written (measured: 1, 2, 4)
   if (dt == MOE_F32) {
-    if (row_mul) dispatch_kernel<float, true><<<grid, block, 0, s>>>((const float*)x, nullptr, inv_perm, row_mul, T, k, d, (float*)xp, nullptr);
-    else dispatch_kernel<float, false><<<grid, block, 0, s>>>((const float*)x, nullptr, inv_perm, nullptr, T, k, d, (float*)xp, nullptr);
+    if (row_mul) dispatch_kernel<float, true, CS><<<grid, block, 0, s>>>((const float*)x, nullptr, inv_perm, row_mul, T, k, d, (float*)xp, nullptr);
+    else dispatch_kernel<float, false, CP><<<grid, block, 0, s>>>((const float*)x, nullptr, inv_perm, nullptr, T, k, d, (float*)xp, nullptr);
   } else if (dt == MOE_BF16) {
-    if (row_mul) dispatch_kernel<bf16, true><<<grid, block, 0, s>>>((const bf16*)x, nullptr, inv_perm, row_mul, T, k, d, (bf16*)xp, nullptr);
-    else dispatch_kernel<bf16, false><<<grid, block, 0, s>>>((const bf16*)x, nullptr, inv_perm, nullptr, T, k, d, (bf16*)xp, nullptr);
+    if (row_mul) dispatch_kernel<bf16, true, CS><<<grid, block, 0, s>>>((const bf16*)x, nullptr, inv_perm, row_mul, T, k, d, (bf16*)xp, nullptr);
+    else dispatch_kernel<bf16, false, CP><<<grid, block, 0, s>>>((const bf16*)x, nullptr, inv_perm, nullptr, T, k, d, (bf16*)xp, nullptr);
   } else {
-    dispatch_kernel<uint8_t, false><<<grid, block, 0, s>>>((const uint8_t*)x, x_scale, inv_perm, nullptr, T, k, d, (uint8_t*)xp, xp_scale);
+    dispatch_kernel<uint8_t, false, CP><<<grid, block, 0, s>>>((const uint8_t*)x, x_scale, inv_perm, nullptr, T, k, d, (uint8_t*)xp, xp_scale);
   }
   MOE_LAUNCH_CHECK();
   return MOE_OK;
@@ -277,11 +362,14 @@ int launch_gate_grad_reduce(const float* part, int parts, long ld, const int32_t
 int launch_combine(const void* yp, const float* yp_scale, moe_dtype dt, const int32_t* inv_perm, const float* topk_w,
                    int T, int k, int d, void* y, moe_dtype y_dt, hipStream_t s) {
   const dim3 grid(row_grid(T)), block(64 * kWavesPerBlock);
-#define MOE_COMBINE_CASE(DI, DO, TI, TO)                                                                       \
-  if (dt == DI && y_dt == DO) {                                                                                \
-    combine_kernel<TI, TO><<<grid, block, 0, s>>>((const TI*)yp, yp_scale, inv_perm, topk_w, T, k, d, (TO*)y); \
-    MOE_LAUNCH_CHECK();                                                                                        \
-    return MOE_OK;                                                                                             \
+// loads in flight per lane (slots x chunks), picked by measurement on 600 MB row buffers: 2 x 8, 4 x 4, 8 x 2
+#define MOE_COMBINE_CASE(DI, DO, TI, TO)                                                                              \
+  if (dt == DI && y_dt == DO) {                                                                                       \
+    if (k <= 2) combine_kernel<TI, TO, 2, 8><<<grid, block, 0, s>>>((const TI*)yp, yp_scale, inv_perm, topk_w, T, k, d, (TO*)y);      \
+    else if (k <= 4) combine_kernel<TI, TO, 4, 4><<<grid, block, 0, s>>>((const TI*)yp, yp_scale, inv_perm, topk_w, T, k, d, (TO*)y); \
+    else combine_kernel<TI, TO, 8, 2><<<grid, block, 0, s>>>((const TI*)yp, yp_scale, inv_perm, topk_w, T, k, d, (TO*)y);             \
+    MOE_LAUNCH_CHECK();                                                                                               \
+    return MOE_OK;                                                                                                    \
   }
   MOE_COMBINE_CASE(MOE_F32, MOE_F32, float, float)
   MOE_COMBINE_CASE(MOE_BF16, MOE_BF16, bf16, bf16)
@@ -295,12 +383,13 @@ int launch_combine(const void* yp, const float* yp_scale, moe_dtype dt, const in
 int launch_gate_grad(const void* dy, moe_dtype dy_dt, const void* yp, const float* yp_scale, moe_dtype dt,
                      const int32_t* inv_perm, int T, int k, int d, float* d_topk_w, hipStream_t s) {
   const dim3 grid(row_grid(T)), block(64 * kWavesPerBlock);
-#define MOE_GG_CASE(DD, DI, TD, TI)                                                                               \
-  if (dy_dt == DD && dt == DI) {                                                                                  \
-    gate_grad_kernel<TD, TI><<<grid, block, 0, s>>>((const TD*)dy, (const TI*)yp, yp_scale, inv_perm, T, k, d,    \
-                                                    d_topk_w);                                                    \
-    MOE_LAUNCH_CHECK();                                                                                           \
-    return MOE_OK;                                                                                                \
+#define MOE_GG_CASE(DD, DI, TD, TI)                                                                                    \
+  if (dy_dt == DD && dt == DI) {                                                                                       \
+    if (k <= 2) gate_grad_kernel<TD, TI, 2, 4><<<grid, block, 0, s>>>((const TD*)dy, (const TI*)yp, yp_scale, inv_perm, T, k, d, d_topk_w);      \
+    else if (k <= 4) gate_grad_kernel<TD, TI, 4, 1><<<grid, block, 0, s>>>((const TD*)dy, (const TI*)yp, yp_scale, inv_perm, T, k, d, d_topk_w); \
+    else gate_grad_kernel<TD, TI, 8, 1><<<grid, block, 0, s>>>((const TD*)dy, (const TI*)yp, yp_scale, inv_perm, T, k, d, d_topk_w);             \
+    MOE_LAUNCH_CHECK();                                                                                                \
+    return MOE_OK;                                                                                                     \
   }
   MOE_GG_CASE(MOE_F32, MOE_F32, float, float)
   MOE_GG_CASE(MOE_BF16, MOE_BF16, bf16, bf16)
