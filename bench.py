@@ -21,10 +21,21 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_FP8_TFLOPS = 5000.0       # MI355X dense fp8 MFMA, published
 PEAK_HBM_GBPS = 8000.0
-# L2-fill + write-back bytes per grouped-GEMM launch (average of the six launches of one step) on the default
-# workload, from rocprofv3 --pmc FETCH_SIZE (x2.000, the factor a 1 GiB copy gives) and WRITE_SIZE (x1.000);
-# the counter runs are summarised in profiles/grouped_gemm_mixtral_hbm_counters.txt.
-MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"mixtral": 7.98e9}
+# L2-fill + write-back bytes per grouped-GEMM launch (average of the six launches of one step) come from the
+# committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary of the same command: a stored figure, read from that
+# file's TRAFFIC_BYTES_PER_LAUNCH line (counters cannot be collected from inside a timing run).
+TRAFFIC_SUMMARY = {"mixtral": "profiles/grouped_gemm_mixtral_hbm_counters.txt"}
+
+
+def stored_traffic(workload):
+    """(bytes per launch, source file) from the committed counter summary of this workload, or (None, None)."""
+    rel = TRAFFIC_SUMMARY.get(workload)
+    if rel is None or not os.path.exists(os.path.join(ROOT, rel)):
+        return None, None
+    for line in open(os.path.join(ROOT, rel)):
+        if line.startswith("TRAFFIC_BYTES_PER_LAUNCH"):
+            return float(line.split("=")[1].split()[0]), rel
+    return None, None
 
 
 def parse():
@@ -48,6 +59,10 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="time K replays of one HIP graph holding the whole step (forward + backward) instead of K eager "
                          "steps; the per-call times and the roofline figure then come from an extra eager pass of K steps")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also measure the practical ceilings (register-only MFMA loop, plain copy, library GEMM as context) "
+                         "and report the GEMM figure as a fraction of the measured MFMA-loop rate beside the published peak")
+    ap.add_argument("--no-permute-large", action="store_true", help="skip the dispatch / combine timing on the large row buffers")
     ap.add_argument("--permute-only", default=None, metavar="WORKLOAD",
                     help="time only dispatch / combine / gate gradient on this workload's activations and print that block")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -159,6 +174,88 @@ def permute_large(name="finegrained", reps=20):
         out["ms"][cname] = ms
         out["gbps"][cname] = nbytes / ms / 1e6
     out["frac"] = {c: v / PEAK_HBM_GBPS for c, v in out["gbps"].items()}
+    return out
+
+
+def ceilings(cfg, fp8_path=False):
+    """The practical ceilings beside the published peaks (include/moe_ceilings.h): a register-only MFMA loop on
+    constant and on random operand bits, a plain 1 GiB copy and read, and, as context only, the library GEMM
+    (torch.matmul) on one expert's FC1 shape and on all dispatched rows at once."""
+    import ctypes
+    import torch
+    from paper_2505_11432_amd.build import CEILINGS_LIB_PATH
+    lib = ctypes.CDLL(CEILINGS_LIB_PATH)
+    P, I, Z = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.moe_ceiling_mfma_loop.argtypes = [I, P, I, I, P, P]
+    lib.moe_ceiling_mfma_lds_loop.argtypes = [P, I, I, P, P]
+    lib.moe_ceiling_copy.argtypes = [P, P, Z, P]
+    lib.moe_ceiling_read.argtypes = [P, Z, P, P]
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream().cuda_stream
+    wgs = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros((wgs * 512,), device=dev)
+    g = torch.Generator(device="cpu").manual_seed(0)
+
+    def timed(fn, reps):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def mfma(fp8, operands, iters=100000):
+        ms = timed(lambda: lib.moe_ceiling_mfma_loop(int(fp8), operands.data_ptr(), iters, wgs, sink.data_ptr(), stream), 3)
+        return wgs * 8 * iters * 8 * 2.0 * 32 * 32 * (64 if fp8 else 16) / ms / 1e9
+
+    n_lane_slots = 2 * 6 * 64
+    def bf16_operands(values):            # values [slots, 8] float -> 32 bytes per lane (bf16 in the first 16)
+        buf = torch.zeros((n_lane_slots, 16), dtype=torch.bfloat16)
+        buf[:, :8] = values.to(torch.bfloat16)
+        return buf.to(dev)
+    out = {}
+    out["mfma_loop_bf16_const_tflops"] = mfma(False, bf16_operands(torch.ones((n_lane_slots, 8))))
+    out["mfma_loop_bf16_random_tflops"] = mfma(False, bf16_operands(torch.randn((n_lane_slots, 8), generator=g)))
+    out["mfma_loop_bf16_weightlike_tflops"] = mfma(False, bf16_operands(0.02 * torch.randn((n_lane_slots, 8), generator=g)))
+    image = torch.randn((65536,), generator=g).to(torch.bfloat16).to(dev)                     # 128 KiB of N(0,1) bf16
+    ms = timed(lambda: lib.moe_ceiling_mfma_lds_loop(image.data_ptr(), 40000, wgs, sink.data_ptr(), stream), 3)
+    out["mfma_lds_fed_loop_bf16_random_tflops"] = wgs * 8 * 40000 * 8 * 2.0 * 32 * 32 * 16 / ms / 1e9
+    codes = torch.randint(0, 0x7f, (n_lane_slots, 32), generator=g, dtype=torch.int16)          # finite e4m3 magnitudes
+    codes = (codes | (torch.randint(0, 2, (n_lane_slots, 32), generator=g, dtype=torch.int16) << 7)).to(torch.uint8)
+    out["mfma_loop_fp8_const_tflops"] = mfma(True, torch.full((n_lane_slots, 32), 0x38, dtype=torch.uint8).to(dev))
+    out["mfma_loop_fp8_random_tflops"] = mfma(True, codes.to(dev))
+    nbytes = 1 << 30
+    src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    ms = timed(lambda: lib.moe_ceiling_copy(src.data_ptr(), dst.data_ptr(), nbytes, stream), 10)
+    out["copy_gbps"] = 2.0 * nbytes / ms / 1e6
+    ms = timed(lambda: lib.moe_ceiling_read(src.data_ptr(), nbytes, sink.data_ptr(), stream), 10)
+    out["read_gbps"] = nbytes / ms / 1e6
+    del src, dst
+    # context only: the vendor library on dense GEMMs of the FC1 shape, same value distributions as the workload
+    rows_e = cfg.M // cfg.E
+    for name, rows in (("library_gemm_fc1_one_expert_tflops", rows_e), ("library_gemm_fc1_all_rows_tflops", cfg.M)):
+        a = torch.randn((rows, cfg.d), generator=g).to(torch.bfloat16).to(dev)
+        w = (0.02 * torch.randn((2 * cfg.f, cfg.d), generator=g)).to(torch.bfloat16).to(dev)
+        c = torch.empty((rows, 2 * cfg.f), dtype=torch.bfloat16, device=dev)
+        ms = timed(lambda: torch.matmul(a, w.t(), out=c), 10)
+        out[name] = 2.0 * rows * cfg.d * 2 * cfg.f / ms / 1e9
+        del a, w, c
+    # the weight-gradient shape of one expert: [2f, rows_e] x [rows_e, d], contraction over the expert's tokens
+    dh = torch.randn((rows_e, 2 * cfg.f), generator=g).to(torch.bfloat16).to(dev)
+    xe = torch.randn((rows_e, cfg.d), generator=g).to(torch.bfloat16).to(dev)
+    c = torch.empty((2 * cfg.f, cfg.d), dtype=torch.bfloat16, device=dev)
+    ms = timed(lambda: torch.matmul(dh.t(), xe, out=c), 10)
+    out["library_gemm_wgrad1_one_expert_tflops"] = 2.0 * rows_e * cfg.d * 2 * cfg.f / ms / 1e9
+    del dh, xe, c
+    out["note"] = ("mfma_loop_*: register-only loop of 32x32 MFMAs, 8 waves per CU; const = all-ones operands, random = "
+                   "N(0,1) bf16 / uniformly random finite e4m3 codes, weightlike = N(0, 0.02); mfma_lds_fed_loop: the bf16 loop with "
+                   "its fragments read from LDS (N(0,1) data) at the grouped GEMM's ratio; library_gemm_*: "
+                   f"torch.matmul on the FC1 shape [rows,{cfg.d}] x [{cfg.d},{2 * cfg.f}] and on one expert's weight-gradient "
+                   "shape, bf16, context only")
     return out
 
 
@@ -279,9 +376,21 @@ def main():
     # bf16 path: these two calls are exactly the six GEMM launches (fp8 path: plus the two row casts in the forward)
     gemm_ms = per_call["expert_ffn_fwd"] + per_call["expert_ffn_bwd"]
     gemm_tflops = gemm_flops / gemm_ms / 1e9
-    # all six GEMMs on the fp8 cores: price against the fp8 peak (the casts inside the two calls are counted as time)
-    peak = PEAK_FP8_TFLOPS if (fp8 and args.fp8_backward) else PEAK_BF16_TFLOPS
-    row_bytes = (cfg.T + M) * cfg.d * 2.0
+    # Each GEMM is priced against the peak of the cores it runs on (the casts inside the two calls count as time):
+    # bf16 path 2.5 PFLOP/s; all six on e4m3 operands 5.0; e4m3 forward with bf16 backward: the blend that the
+    # forward's 6*M*d*f at 5.0 and the backward's 12*M*d*f at 2.5 would take.
+    if not fp8:
+        peak = PEAK_BF16_TFLOPS
+    elif args.fp8_backward:
+        peak = PEAK_FP8_TFLOPS
+    else:
+        peak = 18.0 / (6.0 / PEAK_FP8_TFLOPS + 12.0 / PEAK_BF16_TFLOPS)
+    # algorithmic bytes of the row movers: what is read plus what is written, in the types that are moved
+    esz_rows = 1 if fp8 else 2                                   # dispatched rows: e4m3 codes or bf16
+    tokens_read = int((layer.inv_perm.view(cfg.T, cfg.k) >= 0).any(dim=1).sum())     # dispatch skips tokens without a local row
+    dispatch_bytes = float(tokens_read + M) * cfg.d * esz_rows + (float(tokens_read + M) * 4 if fp8 else 0.0)
+    combine_bytes = float(M) * cfg.d * esz_rows + float(cfg.T) * cfg.d * 2 + (float(M) * 4 if fp8 else 0.0)
+    traffic, traffic_source = stored_traffic(cfg.name) if not (fp8 or args.fused or capacity or balance) else (None, None)
 
     out = {
         "metric": "MoE layer fwd+bwd tokens/s; grouped-GEMM TFLOPS as % of MI355X MFMA peak",
@@ -306,19 +415,30 @@ def main():
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",
                      "achieved": gemm_tflops, "peak": peak, "unit": "TFLOP/s",
                      "frac": gemm_tflops / peak,
-                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "flops_per_launch_avg": gemm_flops / 6, "launch_ms_avg": gemm_ms / 6},
         "gemm_tflops": {"fwd": 6.0 * M * cfg.d * cfg.f / per_call["expert_ffn_fwd"] / 1e9,
                         "bwd": 12.0 * M * cfg.d * cfg.f / per_call["expert_ffn_bwd"] / 1e9},
         # activations held from the forward to the backward, beyond x itself and the routing tables
         "kept_activation_bytes": (M * 2 * cfg.f * 2 + M * 8) if args.fused else (M * 2 * cfg.f * 2 + 2 * M * cfg.d * (1 if fp8 else 2)),
-        "hbm_gbps": {"dispatch": row_bytes / per_call["dispatch"] / 1e6 if "dispatch" in per_call else None,
-                     "combine": row_bytes / per_call["combine"] / 1e6,
-                     "peak": PEAK_HBM_GBPS},
+        "hbm_gbps": {"dispatch": dispatch_bytes / per_call["dispatch"] / 1e6 if "dispatch" in per_call else None,
+                     "combine": combine_bytes / per_call["combine"] / 1e6,
+                     "dispatch_bytes": dispatch_bytes, "combine_bytes": combine_bytes,
+                     "peak": PEAK_HBM_GBPS,
+                     "note": "this workload's row buffers may fit the 256 MB Infinity Cache; permute_large is the HBM figure"},
         "ms_per_call": per_call,
         "setup_s": setup_s,
         "launch": "one HIP graph per step" if args.graph else "eager",
     }
+    if not args.no_permute_large:
+        del layer
+        torch.cuda.empty_cache()
+        out["permute_large"] = permute_large("finegrained")
+    if args.ceilings:
+        out["ceilings"] = ceilings(cfg)
+        key = "mfma_loop_fp8_random_tflops" if (fp8 and args.fp8_backward) else "mfma_loop_bf16_random_tflops"
+        out["roofline"]["measured_ceiling"] = out["ceilings"][key]
+        out["roofline"]["frac_of_measured_ceiling"] = gemm_tflops / out["ceilings"][key]
     if not args.no_cpu_baseline:
         tokens = args.cpu_tokens or max(cfg.T // 4, 1)
         out["cpu_baseline"] = (cpu_baseline_fp8(cfg, inp, tokens, args.fp8_backward) if fp8

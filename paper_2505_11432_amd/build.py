@@ -17,6 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libmoe_hip.so")
+CEILINGS_SRC = os.path.join(CSRC, "ceilings", "ceilings.hip")       # measurement aids: a library of their own
+CEILINGS_LIB_PATH = os.path.join(HERE, "libmoe_ceilings.so")
 STAMP_PATH = LIB_PATH + ".sha256"      # hash of the sources the library was built from
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 
@@ -39,6 +41,7 @@ def source_hash() -> str:
     h = hashlib.sha256(" ".join(COMMON_FLAGS).encode())
     files = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h"))]
     files += [os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h")]
+    files.append(CEILINGS_SRC)
     for path in sorted(files):
         h.update(os.path.basename(path).encode())
         with open(path, "rb") as fh:
@@ -48,7 +51,7 @@ def source_hash() -> str:
 
 def is_current() -> bool:
     """True when the library exists and was built from the sources as they are now."""
-    if not (os.path.exists(LIB_PATH) and os.path.exists(STAMP_PATH)):
+    if not (os.path.exists(LIB_PATH) and os.path.exists(CEILINGS_LIB_PATH) and os.path.exists(STAMP_PATH)):
         return False
     with open(STAMP_PATH) as fh:
         return fh.read().strip() == source_hash()
@@ -80,8 +83,14 @@ def build(verbose: bool = True) -> str:
         os.remove(STAMP_PATH)           # no stamp while the library and the sources may disagree
     stamp = source_hash()
     srcs = sources()
-    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs) + 1)) as pool:
+        ceil_obj = pool.submit(_compile, CEILINGS_SRC)
         objs = list(pool.map(_compile, srcs))
+        ceil_obj = ceil_obj.result()
+    res = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", CEILINGS_LIB_PATH, ceil_obj],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"link failed:\n{res.stderr}")
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

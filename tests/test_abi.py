@@ -192,3 +192,26 @@ def test_transpose_and_init_argument_errors(lib):
     assert lib.moe_transpose(None, 1, 1, 8, 8, other, None) == -1
     assert lib.moe_transpose(fake, 9, 1, 8, 8, other, None) == -2
     assert lib.moe_transpose(None, 1, 0, 8, 8, None, None) == 0
+
+
+def test_ceilings_library_exports_its_header():
+    """libmoe_ceilings.so (measurement aids of bench.py) exports every symbol include/moe_ceilings.h declares."""
+    from paper_2505_11432_amd import build
+    build.ensure_built()
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "moe_ceilings.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(moe_ceiling_[a-z0-9_]+)\s*\(", text)))
+    assert names == ["moe_ceiling_copy", "moe_ceiling_mfma_lds_loop", "moe_ceiling_mfma_loop", "moe_ceiling_read"]
+    lib2 = ctypes.CDLL(build.CEILINGS_LIB_PATH)
+    for n in names:
+        assert hasattr(lib2, n), n
+    assert lib2.moe_ceiling_copy(None, None, ctypes.c_size_t(16), None) == -1
+    assert lib2.moe_ceiling_mfma_loop(0, None, 10, 1, None, None) == -1
+
+
+def test_profile_labels():
+    from paper_2505_11432_amd.profile_summary import label
+    base = "_ZN3moe4mfma23grouped_gemm_dma_kernelILi256ELi256ELi64ELi2ELi2ELi4ELNS0_6LayoutE1ELS2_1ELNS0_4ModeE1ELNS0_3EpiE0E"
+    assert label(base + "fDF16bEEvNS0_4ArgsE") == "grouped_gemm<256x256x64 s2 w2x4 TN kseg store out=f32 in=bf16>"
+    assert label(base.replace("LayoutE1ELS2_1E", "LayoutE0ELS2_0E").replace("ModeE1", "ModeE0").replace("EpiE0", "EpiE1")
+                 + "DF16bhEEvNS0_4ArgsE") == "grouped_gemm<256x256x64 s2 w2x4 NT rowseg swiglu out=bf16 in=e4m3>"
+    assert label("_ZN3moe12_GLOBAL__N_114combine_kernelIDF16bDF16bLi8ELi2EEEvPKT_") == "combine_kernel"
