@@ -405,3 +405,145 @@ def test_full_size_fused_order_sampled(name):
     print(name, "fused", {k_: f"{v:.2e}" for k_, v in errs.items()})
     bad = {k_: v for k_, v in errs.items() if not v < TOL}
     assert not bad, bad
+
+
+def test_full_size_one_whole_expert_every_output_tile():
+    """Mixtral workload at full size: for the largest expert, every element of every output of the six grouped GEMMs
+    (H, Y, d_xp for all of its rows; the full dW1[e] and dW2[e]) against the oracle, so that every output tile of one
+    expert is covered, the ragged last m-tile and the tiles of workgroups that run several tiles included."""
+    cfg = CONFIGS["mixtral"]
+    inp = make_inputs(cfg, seed=0)
+    layer = run_full(cfg, inp)
+    k, E = cfg.k, cfg.E
+    z = layer.logits.cpu().numpy()
+    r = O.route(z, k, cfg.renorm)
+    assert np.array_equal(to_np(layer.perm), r["perm"]) and np.array_equal(to_np(layer.offsets), r["offsets"])
+    e = int(np.argmax(r["counts"]))
+    lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
+    print(f"whole expert {e}: rows {lo}..{hi} ({hi - lo} rows, {(hi - lo + 255) // 256} m-tiles)", flush=True)
+    a_e = r["perm"][lo:hi].astype(np.int64)
+    xp_e = inp["x"][a_e // k].astype(np.float64)
+    dY_e = inp["dy"][a_e // k].astype(np.float64) * r["w"].reshape(-1)[a_e][:, None]
+    off_e = np.array([0, hi - lo], dtype=np.int32)
+    W1e, W2e = inp["W1"][e:e + 1], inp["W2"][e:e + 1]
+    H, _, Y = O.expert_ffn_fwd(xp_e, off_e, W1e, W2e)
+    dxp, dW1, dW2, _ = O.expert_ffn_bwd(xp_e, H, dY_e, off_e, W1e, W2e)
+    errs = {"H": max_norm_err(to_np(layer.h_save[lo:hi]), H), "Y": max_norm_err(to_np(layer.yp[lo:hi]), Y),
+            "dxp": max_norm_err(to_np(layer.d_xp[lo:hi]), dxp)}
+    del H, Y, dxp
+    errs["dW1"] = max_norm_err(to_np(layer.d_w1[e]), dW1[0])
+    errs["dW2"] = max_norm_err(to_np(layer.d_w2[e]), dW2[0])
+    print("whole expert:", {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < TOL}
+    assert not bad, bad
+
+
+def _fp8_layer_full(backward):
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = CONFIGS["mixtral_fp8"]
+    inp = make_inputs(cfg, seed=0)
+    layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=True)
+    x, dy = dev_bf16(inp["x"]), dev_bf16(inp["dy"])
+    w_r = dev_bf16(np.ascontiguousarray(inp["W_r"].T))
+    w1, w2 = dev_bf16(inp["W1"]), dev_bf16(inp["W2"])
+    layer.set_fp8_weights(w1, w2)
+    layer.forward_fp8(x, w_r, None)
+    if backward == "fp8":
+        layer.set_fp8_backward_weights(w1, w2)
+        layer.backward_fp8_gemm(x, w_r, dy)
+    else:
+        layer.backward_fp8(x, w_r, w1, w2, dy)
+    torch.cuda.synchronize()
+    return cfg, inp, layer
+
+
+def test_full_size_fp8_whole_expert_weight_gradients_on_the_kernels_codes():
+    """All-e4m3 step at full size: the full dW1[e] and dW2[e] of the largest expert from the kernel's own transposed
+    codes and E8M0 group scales (which the sampled test compares bit for bit with the oracle's quantiser), so every
+    output tile of the block-scaled weight-gradient GEMMs of one expert is covered."""
+    cfg, inp, layer = _fp8_layer_full("fp8")
+    I = layer.bwd8
+    offsets = to_np(layer.offsets).astype(np.int64)
+    po = to_np(I["pad_offsets"]).astype(np.int64)
+    e = int(np.argmax(np.diff(offsets)))
+    n = int(offsets[e + 1] - offsets[e])
+    off_e = np.array([0, n])
+    print(f"whole expert {e}: {n} rows, {(n + 127) // 128} token groups", flush=True)
+
+    def deq(name):
+        codes = to_np(I[name + "_t"][:, po[e]:po[e] + n]).T                       # [n, channels]
+        ng = (n + 127) // 128
+        exps = to_np(I[name + "_e8m0"][po[e] // 128: po[e] // 128 + ng]).astype(np.int64) - 127
+        return O.dequant_tokengroup_pow2(np.ascontiguousarray(codes), exps, off_e)
+
+    dy_g, a_g = deq("dy"), deq("a")
+    err2 = max_norm_err(to_np(layer.d_w2[e]), dy_g.T @ a_g)
+    del dy_g, a_g
+    dh_g, x_g = deq("dh"), deq("x")
+    err1 = max_norm_err(to_np(layer.d_w1[e]), dh_g.T @ x_g)
+    print(f"whole expert e4m3 weight gradients: dW1 {err1:.2e} dW2 {err2:.2e}")
+    assert err1 < 6e-2 and err2 < 6e-2
+
+
+def test_full_size_fp8_forward_with_straight_through_bf16_backward_sampled():
+    """mixtral_fp8 in its required form (e4m3 forward, straight-through bf16 backward on the master weights) at full
+    size: sampled tokens against the oracle fed the kernel's codes (stage-wise, as in the small cases), and the
+    weight-gradient slices of three experts summed over all of their rows."""
+    cfg, inp, layer = _fp8_layer_full("bf16")
+    T, k, d, f, E = cfg.T, cfg.k, cfg.d, cfg.f, cfg.E
+    z = layer.logits.cpu().numpy()
+    r = O.route(z, k, cfg.renorm)
+    assert np.array_equal(to_np(layer.perm), r["perm"])
+    offsets = r["offsets"].astype(np.int64)
+    rng = np.random.default_rng(21)
+    # dy cast (per channel in 128-token groups, token order): bit-exact on whole groups
+    g0 = int(rng.integers(0, T // 128)) * 128
+    c_ref, s_ref = O.quant_colgroup128(inp["dy"][g0:g0 + 256])
+    assert np.array_equal(to_np(layer.dy_codes[g0:g0 + 256]), c_ref)
+    assert np.array_equal(to_np(layer.dy_scale[g0 // 128: g0 // 128 + 2]).astype(np.float32), s_ref)
+    dy_hat = to_np(layer.dy_deq)                                                 # [T, d], checked against the codes below
+    assert np.array_equal(dy_hat[g0:g0 + 256], O.dequant_colgroup128(c_ref, s_ref).astype(np.float32).astype(np.float64)) or \
+        max_norm_err(dy_hat[g0:g0 + 256], O.dequant_colgroup128(c_ref, s_ref)) < 2 ** -8
+    # sampled tokens: rows of the backward GEMMs from the kernel's codes (A_hat, xp_hat) and saved H
+    toks = np.sort(rng.choice(T, size=96, replace=False))
+    a_ids = (toks[:, None] * k + np.arange(k)[None, :]).reshape(-1)
+    rows = r["inv_perm"][a_ids].astype(np.int64)
+    e_of = r["idx"].reshape(-1)[a_ids]
+    order = np.argsort(e_of, kind="stable")
+    rows_s, e_s, a_s = rows[order], e_of[order], a_ids[order]
+    offs = np.concatenate([[0], np.cumsum(np.bincount(e_s, minlength=E))]).astype(np.int32)
+    rt = torch.from_numpy(rows_s).to(DEV)
+    xp_hat = O.dequant_rows(to_np(layer.xp[rt]), to_np(layer.xp_scale[rt]).astype(np.float32))
+    A_hat = O.dequant_rows(to_np(layer.a_codes[rt]), to_np(layer.a_scale[rt]).astype(np.float32))
+    Y_hat = O.dequant_rows(to_np(layer.yp[rt]), to_np(layer.yp_scale[rt]).astype(np.float32))
+    H = to_np(layer.h_save[rt])
+    w_s = r["w"].reshape(-1)[a_s]
+    dY_s = dy_hat[a_s // k] * w_s[:, None]
+    dxp_s, _, _, _ = O.expert_ffn_bwd(xp_hat, H, dY_s, offs, inp["W1"], inp["W2"], A=A_hat)
+    errs = {"dYp": max_norm_err(to_np(layer.d_yp[rt]), dY_s), "dxp": max_norm_err(to_np(layer.d_xp[rt]), dxp_s)}
+    back = np.empty_like(order)
+    back[order] = np.arange(order.size)
+    dw_ref = np.einsum("td,tkd->tk", dy_hat[toks], Y_hat[back].reshape(len(toks), k, d))
+    tt = torch.from_numpy(toks).to(DEV)
+    errs["dw"] = max_norm_err(to_np(layer.d_topk_w[tt]), dw_ref)
+    dz_ref = O.route_bwd(z[toks], r["idx"][toks], r["w"][toks], dw_ref, cfg.renorm)
+    dx_ref = dxp_s[back].reshape(len(toks), k, d).sum(axis=1) + dz_ref @ inp["W_r"].astype(np.float64).T
+    errs["dx"] = max_norm_err(to_np(layer.dx[tt]), dx_ref)
+    # weight-gradient slices over all rows of three experts, from the kernel's codes
+    for e in (0, int(np.argmax(r["counts"])), E - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        j0 = int(rng.integers(0, f // 64)) * 64
+        sl = np.r_[j0:j0 + 64, f + j0:f + j0 + 64]
+        slt = torch.from_numpy(sl).to(DEV)
+        a_e = r["perm"][lo:hi].astype(np.int64)
+        dY_e = dy_hat[a_e // k] * r["w"].reshape(-1)[a_e][:, None]
+        xp_e = O.dequant_rows(to_np(layer.xp[lo:hi]), to_np(layer.xp_scale[lo:hi]).astype(np.float32))
+        A_e = O.dequant_rows(to_np(layer.a_codes[lo:hi, j0:j0 + 64]), to_np(layer.a_scale[lo:hi]).astype(np.float32))
+        H_e = to_np(layer.h_save[lo:hi][:, slt])
+        off_e = np.array([0, hi - lo], dtype=np.int32)
+        _, dW1s, dW2s, _ = O.expert_ffn_bwd(xp_e, H_e, dY_e, off_e, inp["W1"][e:e + 1, sl, :], inp["W2"][e:e + 1, :, j0:j0 + 64], A=A_e)
+        errs[f"dW1[{e}]"] = max_norm_err(to_np(layer.d_w1[e][slt]), dW1s[0])
+        errs[f"dW2[{e}]"] = max_norm_err(to_np(layer.d_w2[e][:, j0:j0 + 64]), dW2s[0])
+    print("mixtral_fp8, bf16 backward, full size:", {k_: f"{v:.2e}" for k_, v in errs.items()})
+    bad = {k_: v for k_, v in errs.items() if not v < 6e-2}
+    assert not bad, bad

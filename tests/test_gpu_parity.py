@@ -361,7 +361,11 @@ def test_layer_fp8_forward_backward(B, cfg):
     ca, sa = O.quant_rows(A_pre)
     ca_gpu, sa_gpu = to_np(layer.a_codes), to_np(layer.a_scale).astype(np.float32)
     diff = ca_gpu.astype(np.int32) != ca.astype(np.int32)
-    assert diff.mean() < 5e-3, f"A codes differ on {diff.mean():.2%} of the elements"
+    # Expected rate: the kernel's fp32 SwiGLU (hardware exp2 and reciprocal, about 2^-22 relative) and the float64
+    # value round to different bf16 numbers with probability 2 * 2^-22 / 2^-8 = 1.2e-4 per element, and two
+    # neighbouring bf16 numbers (7 mantissa bits) straddle an e4m3 rounding boundary (3 bits) once in 16: about 8e-6,
+    # plus the rows whose maximum moved.  Measured 0.7e-6 to 2.4e-6; the bound leaves a factor of six.
+    assert diff.mean() < 5e-5, f"A codes differ on {diff.mean():.2e} of the elements"
     assert np.all(np.abs((ca_gpu & 0x7F).astype(np.int32) - (ca & 0x7F).astype(np.int32))[diff] <= 1)
     assert np.allclose(sa_gpu, sa, rtol=2 ** -7)
     # (4) FC2 on the kernel's A codes, then the cast of Y: bit-exact on the kernel's own pre-cast Y
@@ -395,10 +399,47 @@ def test_layer_fp8_forward_backward(B, cfg):
     print(cfg.name, {k_: f"{v:.2e}" for k_, v in errs.items()})
     bad = {k_: v for k_, v in errs.items() if not v < tol}
     assert not bad, bad
-    # information only: end to end against the oracle taking its own cast decisions, and against no casts at all
-    plain = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], k)
-    print("   y end to end vs fp8 oracle:", f"{max_norm_err(to_np(layer.y), fwd['y']):.2e}",
-          " vs unquantised oracle:", f"{max_norm_err(to_np(layer.y), plain['y']):.2e}")
+    # (7) end to end against the oracle taking its OWN cast decisions (nothing handed over but the logits)
+    e2e = fp8_end_to_end_forward(to_np(layer.y), fwd, k)
+    bwd_own = O.layer_bwd_fp8(inp["x"], z, inp["W1"], inp["W2"], k, inp["dy"], fwd)
+    for name, got in (("dx", to_np(layer.dx)), ("dW1", dW1), ("dW2", dW2), ("dw", to_np(layer.d_topk_w))):
+        e2e[f"{name} max-norm"] = max_norm_err(got, bwd_own[name])
+        e2e[f"{name} L2"] = rel_l2(got, bwd_own[name])
+    print("   end to end:", {k_: f"{v:.2e}" for k_, v in e2e.items()}, f"A-code flips {diff.mean():.2e}")
+    assert e2e["y L2"] < tol and e2e["y fraction beyond 6e-2"] < 1e-3
+    assert e2e["y worst excess over one step"] < 3e-2 and e2e["y max-norm"] < 9e-2
+    for name in ("dx", "dW1", "dW2", "dw"):
+        assert e2e[f"{name} max-norm"] < tol and e2e[f"{name} L2"] < tol, (name, e2e)
+
+
+def rel_l2(got, ref) -> float:
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    return float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+
+
+def fp8_end_to_end_forward(y_gpu, fwd, k):
+    """Distance of the layer output from the fp8 oracle that takes every cast decision itself.
+
+    Two casts sit between the kernel's arithmetic and y.  The kernel computes the SwiGLU output from the bf16-rounded
+    H, the oracle from float64 values, so their pre-cast A differ in the last bf16 bit and a few per cent of the A
+    codes land on the neighbouring code (6 to 12 % of that element); summed over the expert width this moves the
+    pre-cast FC2 output by about sqrt(p) * 0.09 = 2 % of its typical magnitude.  The cast of the FC2 output then flips
+    a few per cent of its codes as well, each by one e4m3 step, 2^(e-3) times the row scale: up to 32/448 = 7.1 % of
+    the row maximum.  No max-norm bound below one top-binade step can therefore hold for ANY implementation whose
+    pre-cast values are not bit-identical to the oracle's.  Asserted instead: (a) the relative L2 distance, which the
+    flips barely move; (b) the fraction of elements further than 6e-2 max|y_ref| from the reference; (c) per element,
+    |y - y_ref| <= sum_j w_j * (32/448) * rowmax_j + 3e-2 max|y_ref| (one top-binade step of each contributing row
+    plus the compounded pre-cast deviation); (d) the max-norm figure, capped at one step plus that deviation."""
+    Yh, w, inv_perm = fwd["Y"], fwd["w"], fwd["inv_perm"]
+    T = w.shape[0]
+    y_ref = fwd["y"]
+    top = np.abs(y_ref).max()
+    rowmax = np.broadcast_to(np.abs(Yh).max(axis=1, keepdims=True), Yh.shape)
+    one_step = O.combine(rowmax * (32.0 / 448.0), inv_perm, w, T, k)
+    delta = np.abs(y_gpu - y_ref)
+    return {"y max-norm": max_norm_err(y_gpu, y_ref), "y L2": rel_l2(y_gpu, y_ref),
+            "y fraction beyond 6e-2": float((delta > 6e-2 * top).mean()),
+            "y worst excess over one step": float(((delta - one_step) / top).max())}
 
 
 # ---- FP8 backward GEMMs -------------------------------------------------------------------------------------
@@ -530,12 +571,21 @@ def test_layer_fp8_backward_gemms(B, cfg):
     print(cfg.name, {k_: f"{v:.2e}" for k_, v in errs.items()})
     bad = {k_: v for k_, v in errs.items() if not v < tol}
     assert not bad, bad
-    # information only: distance to the straight-through bf16 backward of the same forward
-    dx8 = to_np(layer.dx)
-    layer.backward_fp8(x, wr, w1, w2, dy, with_router=False)
-    torch.cuda.synchronize()
-    print("   vs bf16 backward GEMMs: dx", f"{max_norm_err(dx8, to_np(layer.dx)):.2e}",
-          "dW1", f"{max_norm_err(dW1, to_np(layer.d_w1)):.2e}", "dW2", f"{max_norm_err(dW2, to_np(layer.d_w2)):.2e}")
+    # (8) end to end against the oracle taking its own cast decisions in the forward and in the backward.  Here the
+    # operands of every GEMM are codes, so code flips (and, for the token groups, a power-of-two scale that lands on
+    # the other side of 448 * 2^k) enter each sum; an element summed over a few hundred tokens can move by more than
+    # 6e-2 of the tensor maximum, so the max-norm bar is asserted on all but 1e-3 of the elements and capped at 0.1,
+    # and the relative L2 distance is asserted at the bar itself.
+    own = O.layer_bwd_fp8_gemm(inp["x"], z, inp["W1"], inp["W2"], k, inp["dy"], fwd)
+    e2e = {}
+    for name, got in (("dx", to_np(layer.dx)), ("dW1", dW1), ("dW2", dW2), ("dw", to_np(layer.d_topk_w))):
+        ref = own[name]
+        e2e[f"{name} max-norm"] = max_norm_err(got, ref)
+        e2e[f"{name} L2"] = rel_l2(got, ref)
+        e2e[f"{name} beyond"] = float((np.abs(got - ref) > tol * np.abs(ref).max()).mean())
+    print("   end to end:", {k_: f"{v:.2e}" for k_, v in e2e.items()})
+    for name in ("dx", "dW1", "dW2", "dw"):
+        assert e2e[f"{name} L2"] < tol and e2e[f"{name} beyond"] < 1e-3 and e2e[f"{name} max-norm"] < 0.1, (name, e2e)
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32, torch.uint8])
@@ -649,6 +699,60 @@ def test_route_capacity(B, T, E, k, G, cap, skew):
     per_dev = ref["counts"].reshape(G, E // G).sum(axis=1)
     assert per_dev.max() <= cap
     print(f"T={T} E={E} k={k} devices={G} capacity={cap}: kept {n} of {M}, per device {per_dev.tolist()[:8]}")
+
+
+def _capacity_gap_ok(z, k, G, cap, rel_gap):
+    """True when, on the oracle's own fp32 affinities, every overloaded device has its capacity-th and
+    (capacity+1)-th largest affinity further apart than rel_gap (relative): then any scores within that distance of
+    the oracle's give the same kept set, so the oracle can decide alone."""
+    idx = O.topk_select(z, k)
+    s = O.affinity_scores(z, idx).reshape(-1).astype(np.float64)
+    E = z.shape[1]
+    grp = idx.reshape(-1) // (E // G)
+    overloaded = 0
+    for g in range(G):
+        sg = np.sort(s[grp == g])[::-1]
+        if sg.size > cap:
+            overloaded += 1
+            if cap == 0:
+                continue
+            if not sg[cap - 1] - sg[cap] > rel_gap * sg[cap - 1]:
+                return False, overloaded
+    return True, overloaded
+
+
+@pytest.mark.parametrize("T,E,k,G,cap,skew", [(300, 8, 2, 4, 100, 2.0), (1000, 32, 3, 8, 300, 1.0), (513, 64, 8, 8, 400, 0.0),
+                                             (4000, 16, 4, 16, 900, 1.5), (2048, 8, 2, 8, 450, 0.8)])
+def test_route_capacity_oracle_decides_alone(B, T, E, k, G, cap, skew):
+    """The drop decision taken by the oracle from its OWN affinities (no score handed over): seeds are taken in order
+    until the boundary keys of every overloaded device are separated by 1e-4 relative, thirty times the 3e-6 to which
+    the kernel's affinities agree with the oracle's, so both sides must reach the same kept set; then the whole row
+    map is compared bit for bit."""
+    for seed in range(100, 140):
+        z = random_logits(T, E, seed=seed)
+        z[:, 0] += skew
+        ok, overloaded = _capacity_gap_ok(z, k, G, cap, 1e-4)
+        if ok and overloaded > 0:
+            break
+    else:
+        pytest.fail("no seed with separated boundary keys")
+    M = T * k
+    i32 = dict(dtype=torch.int32, device=DEV)
+    out = dict(idx=torch.full((T, k), -7, **i32), w=torch.full((T, k), -7.0, device=DEV), score=torch.full((T, k), -7.0, device=DEV),
+               counts=torch.full((E,), -7, **i32), offsets=torch.full((E + 1,), -7, **i32),
+               perm=torch.full((M,), -7, **i32), inv_perm=torch.full((M,), -7, **i32))
+    ws = torch.empty(B.moe_route_capacity_workspace_bytes(T, E, k), dtype=torch.uint8, device=DEV)
+    B.moe_route_capacity(to_dev(z), k, 1, G, cap, out["idx"], out["w"], out["score"], out["counts"], out["offsets"],
+                         out["perm"], out["inv_perm"], ws)
+    torch.cuda.synchronize()
+    ref = O.route_capacity(z, k, G, cap)                           # no `score`: the oracle's own decision
+    assert 0 < (~ref["keep"]).sum() < M
+    assert np.allclose(to_np(out["score"]), ref["score"], rtol=3e-6, atol=1e-12)
+    for name in ("idx", "counts", "offsets", "inv_perm"):
+        assert np.array_equal(to_np(out[name]), ref[name]), name
+    n = int(ref["offsets"][-1])
+    assert np.array_equal(to_np(out["perm"])[:n], ref["perm"])
+    print(f"seed {seed}: T={T} E={E} k={k} devices={G} capacity={cap}: {overloaded} overloaded devices, kept {n} of {M}")
 
 
 @pytest.mark.parametrize("T,E,k,G", [(300, 8, 2, 4), (1000, 64, 6, 8), (257, 256, 8, 32), (64, 5, 2, 5), (2048, 32, 3, 8)])

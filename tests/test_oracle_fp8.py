@@ -250,3 +250,80 @@ def test_layer_bwd_fp8_gemm_close_to_straight_through_bf16_backward():
         e = np.abs(g8[name] - gs[name]).max() / max(np.abs(gs[name]).max(), 1e-30)
         assert e < 0.12, (name, e)
     assert np.abs(g8["dW1"] - gs["dW1"]).max() > 0
+
+
+def _exact_fp8_layer_inputs():
+    """A layer on which every cast of the fp8 forward is lossless up to the output: all of x, W1, W2, the SwiGLU
+    output A and the FC2 output Y lie on the e4m3 grid of their row, and every row maximum is 7 * 2^j (so that
+    448 / amax and amax / 448 are powers of two).  G = 64 everywhere, where silu(G) = G exactly in float64
+    (1 + e^-64 rounds to 1); U, A = 64 U and Y are small integers times powers of two."""
+    T, d, E, k, f = 32, 16, 3, 2, 8
+    rng = np.random.default_rng(11)
+    pow2 = np.array([0, 1, 2, 4, 8, 16, -1, -2, -4, -8, -16], dtype=np.float32)
+    x = rng.choice(pow2, size=(T, d)).astype(np.float32)
+    x[:, 0] = 8.0          # drives G
+    x[:, 1] = 28.0         # row maximum 7 * 4; no weight reads this column
+    x[:, 2] = 0.0          # the weights keep their own row maxima in this column
+    x[:, 3] = 16.0         # drives the largest U
+    W1 = np.zeros((E, 2 * f, d), dtype=np.float32)
+    W2 = np.zeros((E, d, f), dtype=np.float32)
+    n_dead, n_top = f - 1, 0
+    for e in range(E):
+        W1[e, :f, 0] = 8.0                                   # G = 8 * 8 = 64
+        W1[e, :f, 2] = 14.0                                  # row maximum 7 * 2 (multiplies x[:, 2] = 0)
+        for n in range(f):
+            W1[e, f + n, 2] = 7.0                            # row maximum 7
+            if n == n_dead:
+                continue                                     # U = 0 in this column: FC2's row maxima live here
+            p = 3 if n == n_top else int(rng.integers(4, d))
+            W1[e, f + n, p] = 7.0 if n == n_top else float(rng.choice([1, 2, 3, 4, 5, 6, 7, -3, -5, -7]))
+        for c in range(d):
+            W2[e, c, n_dead] = 7.0                           # row maximum 7 (multiplies A[:, n_dead] = 0)
+            n = n_top if c == 0 else int(rng.integers(0, f - 1))
+            W2[e, c, n] = 4.0 if c == 0 else float(rng.choice([1, 2, 4, -1, -2, -4]))
+    z = rng.standard_normal((T, E)).astype(np.float32)
+    return x, z, W1, W2, k
+
+
+def test_fp8_layer_exact_through_fc2_and_output_when_every_cast_is_lossless():
+    """Pins the axis of the W2 cast, the placement of the A and Y casts and the gate weight after the dequantised
+    Y: on grid-aligned tensors the fp8 layer equals the plain layer bit for bit, up to y."""
+    x, z, W1, W2, k = _exact_fp8_layer_inputs()
+    q = O.layer_fwd_fp8(x, z, W1, W2, k)
+    p = O.layer_fwd(x, z, W1, W2, k)
+    assert np.all(p["H"][:, : W1.shape[1] // 2] == 64.0)
+    assert np.abs(p["A"]).max() == 64.0 * 112.0 and np.count_nonzero(p["Y"]) > p["Y"].size // 2
+    for name in ("xp", "H", "A", "Y", "y"):
+        assert np.array_equal(q[name], p[name]), name
+
+
+def test_fp8_layer_exactness_case_detects_planted_mistakes(monkeypatch):
+    """The same case with a mistake planted in the oracle: W2 cast along its other axis, and the gate weight
+    applied before the Y cast instead of after it; either breaks the equality."""
+    x, z, W1, W2, k = _exact_fp8_layer_inputs()
+    p = O.layer_fwd(x, z, W1, W2, k)
+
+    def wrong_axis(W1_, W2_):
+        E, two_f, d = W1_.shape
+        f = W2_.shape[2]
+        W1h = O.fake_quant_rows(np.float32(W1_).reshape(E * two_f, d)).reshape(E, two_f, d)
+        W2t = np.ascontiguousarray(np.transpose(np.float32(W2_), (0, 2, 1)))
+        W2h = np.transpose(O.fake_quant_rows(W2t.reshape(E * f, d)).reshape(E, f, d), (0, 2, 1))
+        return W1h, W2h
+
+    monkeypatch.setattr(O, "quant_weights", wrong_axis)
+    q = O.layer_fwd_fp8(x, z, W1, W2, k)
+    assert np.array_equal(q["H"], p["H"]) and not np.array_equal(q["Y"], p["Y"])
+    monkeypatch.undo()
+
+    real_combine, real_fq = O.combine, O.fake_quant_rows
+
+    def weight_before_cast(Y_hat, inv_perm, w, T, k_):
+        # what a cast of w * Y would give: quantise the weighted rows, then sum without weights
+        wrow = np.zeros(Y_hat.shape[0])
+        wrow[inv_perm.reshape(-1)] = np.asarray(w, np.float64).reshape(-1)
+        return real_combine(real_fq(Y_hat * wrow[:, None]), inv_perm, None, T, k_)
+
+    monkeypatch.setattr(O, "combine", weight_before_cast)
+    q = O.layer_fwd_fp8(x, z, W1, W2, k)
+    assert not np.array_equal(q["y"], p["y"])
