@@ -56,6 +56,9 @@ def parse():
                     help="bf16 only: the paper's Section 4.1 / 4.2 operator order (FC1 selects its rows from x inside the "
                          "kernel, gate weight after SwiGLU, gate gradient from the dgrad2 epilogue, no dispatched input "
                          "or FC2 output kept for the backward)")
+    ap.add_argument("--keep-a", action="store_true",
+                    help="bf16, plain order: keep the FC2 input from the forward (M*f*2 bytes) instead of writing it again in "
+                         "the backward")
     ap.add_argument("--graph", action="store_true",
                     help="time K replays of one HIP graph holding the whole step (forward + backward) instead of K eager "
                          "steps; the per-call times and the roofline figure then come from an extra eager pass of K steps")
@@ -293,7 +296,8 @@ def main():
     capacity = (devices, int(math.ceil(args.capacity_factor * cfg.T * cfg.k / devices))) if args.capacity_factor > 0 else None
     balance = (devices, args.balance_alpha) if args.balance_alpha > 0 else None
     layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=torch.bfloat16, renorm=cfg.renorm, fp8=fp8,
-                     expert_range=cfg.expert_range, capacity=capacity, balance=balance, fused=args.fused)
+                     expert_range=cfg.expert_range, capacity=capacity, balance=balance, fused=args.fused,
+                     keep_a=args.keep_a)
     if args.fused and fp8:
         print("bench.py: --fused is a bf16 path", file=sys.stderr)
         sys.exit(2)
@@ -409,7 +413,8 @@ def main():
                                (f"; capacity {capacity[1]} rows per device over {capacity[0]} devices, {M} of {cfg.M} rows kept"
                                 if capacity else "") + (f"; balance loss alpha={args.balance_alpha}" if balance else "") +
                                ("; fused operator order (row select inside FC1, gate weight after SwiGLU, FC1 input rows "
-                                "produced again in the backward)" if args.fused else ""),
+                                "produced again in the backward)" if args.fused else "") +
+                               ("; FC2 input kept from the forward" if args.keep_a else ""),
                    "tokens": cfg.T, "expert_rows": counts},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step: FC1+SwiGLU, FC2, "
                                                 "dgrad2+SwiGLU', wgrad2, dgrad1, wgrad1)",
@@ -420,7 +425,8 @@ def main():
         "gemm_tflops": {"fwd": 6.0 * M * cfg.d * cfg.f / per_call["expert_ffn_fwd"] / 1e9,
                         "bwd": 12.0 * M * cfg.d * cfg.f / per_call["expert_ffn_bwd"] / 1e9},
         # activations held from the forward to the backward, beyond x itself and the routing tables
-        "kept_activation_bytes": (M * 2 * cfg.f * 2 + M * 8) if args.fused else (M * 2 * cfg.f * 2 + 2 * M * cfg.d * (1 if fp8 else 2)),
+        "kept_activation_bytes": (M * 2 * cfg.f * 2 + M * 8) if args.fused else (M * 2 * cfg.f * 2 + 2 * M * cfg.d * (1 if fp8 else 2)
+                                                                                   + (M * cfg.f * 2 if args.keep_a else 0)),
         "hbm_gbps": {"dispatch": dispatch_bytes / per_call["dispatch"] / 1e6 if "dispatch" in per_call else None,
                      "combine": combine_bytes / per_call["combine"] / 1e6,
                      "dispatch_bytes": dispatch_bytes, "combine_bytes": combine_bytes,

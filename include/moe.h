@@ -208,9 +208,13 @@ int moe_gate_grad(const void* dy /*[T,d]*/, moe_dtype dy_dt, const void* yp /*[T
  * act_dt = w_dt = MOE_F8E4M3: xp holds codes with per-row scales xp_scale[M]; w1/w2 hold
  * codes with per-output-channel scales w1_scale [E,2f], w2_scale [E,d]; A is quantised per
  * row before FC2; out_dt = MOE_F8E4M3 writes yp as codes with per-row scales yp_scale[M],
- * out_dt = MOE_BF16 writes it unquantised.  a_codes_out [M,f] / a_scale_out [M] (both or neither,
- * fp8 path only) receive the quantised FC2 input, which the backward dequantises and passes as
- * a_override.  The plain paths touch no row >= offsets[E]; the fp8 path requires offsets[E] = M. */
+ * out_dt = MOE_BF16 writes it unquantised.  a_codes_out [M,f] / a_scale_out [M] (both or neither)
+ * receive the quantised FC2 input, which the backward dequantises and passes as a_override.
+ * bf16 path: a_codes_out, if given (a_scale_out NULL), receives the FC2 input A [M,f] in bf16
+ * instead of the workspace; passing it to moe_expert_ffn_bwd as a_override spares the backward
+ * the second write of A (the paper recomputes the FC2 input, Section 4.1: keeping it trades
+ * M*f*2 bytes for that write).  The plain paths touch no row >= offsets[E]; the fp8 path
+ * requires offsets[E] = M. */
 int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt,
                        const int32_t* offsets /*[E+1], device*/,
                        const void* w1 /*[E,2f,d]*/, const float* w1_scale,

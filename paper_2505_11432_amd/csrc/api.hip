@@ -56,8 +56,8 @@ static int ffn_fwd_plain(const void* xp, const int32_t* offsets, const void* w1,
 
 // bf16: every GEMM on the matrix cores, SwiGLU and its derivative fused into the FC1 / dgrad2 epilogues.
 static int ffn_fwd_bf16(const void* xp, const int32_t* offsets, const void* w1, const void* w2, int M, int d, int E,
-                        int f, void* h_save, void* yp, void* ws, hipStream_t s) {
-  void* A = ws;
+                        int f, void* h_save, void* yp, void* a_out, void* ws, hipStream_t s) {
+  void* A = a_out ? a_out : ws;        // the FC2 input: kept for the caller, or scratch
   int rc = mfma_fc1_swiglu(xp, w1, offsets, M, d, E, f, h_save, A, s);
   if (rc != MOE_OK) return rc;
   void* splitk = static_cast<char*>(ws) + align_up((size_t)M * f * 2, 256);
@@ -358,16 +358,16 @@ int moe_expert_ffn_fwd(const void* xp, const float* xp_scale, moe_dtype act_dt, 
       !aligned16(workspace))
     return MOE_ERR_UNSUPPORTED;
   if (!workspace || ws_bytes < ffn_fwd_ws_bytes(M, d, f, act_dt, out_dt)) return MOE_ERR_WORKSPACE;
-  if ((a_codes_out != nullptr) != (a_scale_out != nullptr)) return MOE_ERR_INVALID;
-  if (!fp8 && a_codes_out) return MOE_ERR_INVALID;
+  if (fp8 && (a_codes_out != nullptr) != (a_scale_out != nullptr)) return MOE_ERR_INVALID;
+  if (!fp8 && (a_scale_out || (a_codes_out && act_dt != MOE_BF16))) return MOE_ERR_INVALID;
+  if (!aligned16(a_codes_out)) return MOE_ERR_UNSUPPORTED;
   if (fp8) {
-    if (!aligned16(a_codes_out)) return MOE_ERR_UNSUPPORTED;
     // rows at or beyond offsets[E] are never read by the GEMMs, but the row quantisers walk all M rows
     return ffn_fwd_fp8(xp, xp_scale, offsets, w1, w1_scale, w2, w2_scale, M, d, E, f, h_save, yp, yp_scale, out_dt,
                        a_codes_out, a_scale_out, workspace, as_stream(stream));
   }
   if (act_dt == MOE_BF16)
-    return ffn_fwd_bf16(xp, offsets, w1, w2, M, d, E, f, h_save, yp, workspace, as_stream(stream));
+    return ffn_fwd_bf16(xp, offsets, w1, w2, M, d, E, f, h_save, yp, a_codes_out, workspace, as_stream(stream));
   return ffn_fwd_plain(xp, offsets, w1, w2, act_dt, M, d, E, f, h_save, yp, workspace, as_stream(stream));
 }
 

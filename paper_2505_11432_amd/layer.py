@@ -14,10 +14,13 @@ from . import binding as B
 class MoELayer:
     def __init__(self, T: int, d: int, E: int, k: int, f: int, dtype=torch.bfloat16, renorm: int = 1,
                  fp8: bool = False, grad_dtype=torch.float32, device="cuda:0", expert_range=None, capacity=None,
-                 balance=None, fused: bool = False):
+                 balance=None, fused: bool = False, keep_a: bool = False):
         """fused = True: the Section 4.1 / 4.2 operator order (bf16): FC1 selects its rows from x through the index
         map, the gate weight is applied right after SwiGLU, the combine is unweighted, the gate gradient comes out
         of the dgrad2 epilogue; neither the dispatched input nor the FC2 output is kept for the backward.
+
+        keep_a = True (bf16, plain order): the FC2 input A is kept from the forward (M*f*2 bytes) and handed to the
+        backward, which then does not write it again (the paper recomputes it, Section 4.1; this trades memory for time).
 
         expert_range = (e_lo, e_hi): this GPU's expert-parallel share (Section 3.2): x holds the all-gathered
         tokens, only rows routed to experts e_lo..e_hi-1 are dispatched, w1/w2 and their gradients hold those
@@ -84,6 +87,10 @@ class MoELayer:
             self.aux_loss = torch.zeros((1,), **f32)
             self.group_f = torch.empty((balance[0],), **f32)
             self.group_p = torch.empty((balance[0],), **f32)
+        self.a_keep = None
+        if keep_a:
+            assert not fp8 and not fused and dtype == torch.bfloat16, "keep_a exists for the plain bf16 order"
+            self.a_keep = torch.empty((M, f), **act)
         self.fused = fused
         if fused:
             assert not fp8 and dtype == torch.bfloat16, "the fused operator order exists for bf16"
@@ -256,7 +263,7 @@ class MoELayer:
             return self.y
         c("dispatch", B.moe_dispatch, x, None, self.inv_perm, None, self.k, self.xp, None)
         c("expert_ffn_fwd", B.moe_expert_ffn_fwd, self.xp, None, self.offsets, w1, None, w2, None, self.h_save,
-          self.yp, None, self.workspace)
+          self.yp, None, self.workspace, self.a_keep, None)
         c("combine", B.moe_combine, self.yp, None, self.inv_perm, self.topk_w, self.k, self.y)
         return self.y
 
@@ -270,7 +277,7 @@ class MoELayer:
             c("gate_grad", B.moe_gate_grad, dy, self.yp, None, self.inv_perm, self.k, self.d_topk_w)
             c("dispatch_bwd_of_combine", B.moe_dispatch, dy, None, self.inv_perm, self.topk_w.view(-1), self.k,
               self.d_yp, None)
-            c("expert_ffn_bwd", B.moe_expert_ffn_bwd, self.xp, self.h_save, self.d_yp, None, self.offsets, w1, w2,
+            c("expert_ffn_bwd", B.moe_expert_ffn_bwd, self.xp, self.h_save, self.d_yp, self.a_keep, self.offsets, w1, w2,
               self.d_xp, self.d_w1, self.d_w2, 0, self.workspace)
         # fused order: d_xp comes without the gate weight, which this combine applies once per row
         c("combine_bwd_of_dispatch", B.moe_combine, self.d_xp, None, self.inv_perm, self.topk_w if self.fused else None,

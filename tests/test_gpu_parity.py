@@ -600,6 +600,30 @@ def test_transpose_exact(B, dtype, batch, rows, cols):
     assert torch.equal(dst.cpu(), src.cpu().transpose(1, 2).contiguous())
 
 
+def test_layer_keep_a_matches_recomputation_bit_for_bit(B):
+    """keep_a: the FC2 input kept from the forward and handed to the backward.  The forward computes it from the same
+    bf16-rounded H the backward recomputes it from, so every result equals the default path's bit for bit."""
+    from paper_2505_11432_amd.layer import MoELayer
+    cfg = MoEConfig("keepa", T=700, d=272, E=6, k=2, f=336, dtype="bf16", w_std=0.06, wr_std=0.5)
+    inp = make_inputs(cfg, seed=4)
+    z = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    z[:, 2] = -1e4
+    td = torch.bfloat16
+    x, dy, wr = to_dev(inp["x"], td), to_dev(inp["dy"], td), to_dev(inp["W_r"].T, td)
+    w1, w2 = to_dev(inp["W1"], td), to_dev(inp["W2"], td)
+    out = []
+    for keep in (False, True):
+        layer = MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.f, dtype=td, keep_a=keep)
+        layer.forward(x, wr, None, w1, w2, logits=to_dev(z))
+        layer.backward(x, wr, w1, w2, dy)
+        torch.cuda.synchronize()
+        out.append(layer)
+    for name in ("y", "dx", "d_xp", "h_save", "d_w1", "d_w2", "d_w_r", "d_topk_w"):
+        assert torch.equal(getattr(out[0], name), getattr(out[1], name)), name
+    fwd = O.layer_fwd(inp["x"], z, inp["W1"], inp["W2"], cfg.k)
+    assert max_norm_err(to_np(out[1].a_keep), fwd["A"]) < TOL["bf16"]
+
+
 # ---- expert-parallel share: routing restricted to an expert range ---------------------------------------------
 @pytest.mark.parametrize("T,E,k,lo,hi", [(300, 12, 3, 4, 9), (1000, 32, 3, 8, 12), (257, 8, 2, 0, 8), (129, 6, 2, 3, 3),
                                          (64, 5, 5, 4, 5), (2000, 64, 8, 56, 64)])
