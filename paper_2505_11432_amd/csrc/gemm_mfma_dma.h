@@ -48,6 +48,36 @@ __device__ __forceinline__ void touch4s(const char* sbase, unsigned voff, unsign
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_dump) : "m0");
 }
 
+// Sixteen of those loads in one block: eight from sbase_a, then eight from sbase_b, into LDS slots that lie a fixed
+// 4 KiB apart from lds_first on (a 32 KiB A tile followed by the B tile, four loader waves).  M0 is stepped with
+// scalar adds inside the block, so the sixteen slot addresses need no registers of their own (kept as sixteen
+// loop-invariant scalars they were spilled to vector lanes and read back with v_readlane before every load).
+__device__ __forceinline__ void dma16s_x16(const char* sbase_a, const char* sbase_b, const unsigned (&va)[8],
+                                           const unsigned (&vb)[8], unsigned lds_first) {
+  asm volatile(
+      "s_mov_b32 m0, %18\n\t"
+      "global_load_lds_dwordx4 %0, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %1, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %2, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %3, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %4, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %5, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %6, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %7, %16\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %8, %17\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %9, %17\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %10, %17\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %11, %17\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %12, %17\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %13, %17\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %14, %17\n\ts_add_u32 m0, m0, 0x1000\n\t"
+      "global_load_lds_dwordx4 %15, %17"
+      ::"v"(va[0]), "v"(va[1]), "v"(va[2]), "v"(va[3]), "v"(va[4]), "v"(va[5]), "v"(va[6]), "v"(va[7]),
+        "v"(vb[0]), "v"(vb[1]), "v"(vb[2]), "v"(vb[3]), "v"(vb[4]), "v"(vb[5]), "v"(vb[6]), "v"(vb[7]),
+        "s"(sbase_a), "s"(sbase_b), "s"(lds_first)
+      : "m0", "scc");
+}
+
 __device__ __forceinline__ const char* uniform_ptr(const char* p) {
   const unsigned long long v = reinterpret_cast<unsigned long long>(p);
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
@@ -638,15 +668,19 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     if (k_left >= BKT) {
       // the e4m3 weight-gradient kernel asks for the B tile first, the others for the A tile: measured
       constexpr bool B_FIRST = FP8 && MODE == KSEG;
-      if constexpr (B_FIRST) {
+      if constexpr (A_DMA == 8 && B_DMA == 8 && NL == 4 && A_BYTES == 8 * 4096 && !ROT && !B_FIRST) {
+        dma16s_x16(ab, bb, a_off, b_off, stage + (unsigned)lw * 1024u);
+      } else {
+        if constexpr (B_FIRST) {
 #pragma unroll
-        for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
-      }
+          for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
+        }
 #pragma unroll
-      for (int j = 0; j < A_DMA; ++j) dma16s(ab, a_off[j], stage + (unsigned)(lw + ((j + rot_a) % A_DMA) * NL) * 1024u);
-      if constexpr (!B_FIRST) {
+        for (int j = 0; j < A_DMA; ++j) dma16s(ab, a_off[j], stage + (unsigned)(lw + ((j + rot_a) % A_DMA) * NL) * 1024u);
+        if constexpr (!B_FIRST) {
 #pragma unroll
-        for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
+          for (int j = 0; j < B_DMA; ++j) dma16s(bb, b_off[j], stage + A_BYTES + (unsigned)(lw + ((j + rot_b) % B_DMA) * NL) * 1024u);
+        }
       }
     } else {
       // ragged last step: chunks past the end of the contraction come from the zero block.  The offsets pass
