@@ -70,9 +70,14 @@ def test_random_small_layers_match_the_oracle(c):
         assert np.array_equal(to_np(got), fwd[name]), (name, c)
     assert int(fwd["counts"].sum()) == T * k
     assert np.allclose(to_np(layer.topk_w), fwd["w"], rtol=2e-6, atol=1e-7)
+    # The gate-weight gradient is a dot product <dy[t], Y[r]> that can cancel to almost nothing, and in the smallest
+    # shapes the whole tensor is one such number: its error (and that of d_logits, which is linear in it) is measured
+    # against the natural scale of the dot products, max ||dy[t]|| * ||Y[r]||, not against the cancelled result.
+    dot_scale = max(np.linalg.norm(inp["dy"], axis=1).max() * np.linalg.norm(fwd["Y"], axis=1).max(), 1e-30)
     errs = {"H": max_norm_err(to_np(layer.h_save), fwd["H"]), "y": max_norm_err(to_np(layer.y), fwd["y"]),
-            "dw": max_norm_err(to_np(layer.d_topk_w), bwd["dw"]), "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
-            "dz": max_norm_err(to_np(layer.d_logits), bwd["dz"])}
+            "dw": float(np.abs(to_np(layer.d_topk_w) - bwd["dw"]).max() / max(np.abs(bwd["dw"]).max(), dot_scale)),
+            "dx": max_norm_err(to_np(layer.dx), bwd["dx"]),
+            "dz": float(np.abs(to_np(layer.d_logits) - bwd["dz"]).max() / max(np.abs(bwd["dz"]).max(), dot_scale))}
     dW1, dW2 = to_np(layer.d_w1), to_np(layer.d_w2)
     for e in range(E):
         if fwd["counts"][e] == 0:
