@@ -22,7 +22,10 @@ logits, ties toward the lower expert id, slot order by descending logit, stable
 order inside an expert's segment, dropless, scale = amax/448; for the FP8 backward
 GEMMs: a second quantisation of the weights along their other axis, and power-of-two
 group scales for the operands whose contraction index is the token) are stated where
-they are used.
+they are used.  The FP8 functions take an optional store="bf16": intermediate tensors are
+then rounded to bfloat16 where one step hands them to the next (Section 5's BF16
+mixed-precision training keeps activations in that type), so that a cast decides on the
+values a bf16 pipeline holds; the default keeps float64 between the casts.
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py against
 brute force, closed forms, finite differences or an independent library routine.
@@ -543,6 +546,24 @@ def fake_quant_rows(v) -> np.ndarray:
     return dequant_rows(*quant_rows(v))
 
 
+def bf16_round(v) -> np.ndarray:
+    """Round to the nearest bfloat16 (ties to even), returned as float64.  Finite inputs only."""
+    b = np.ascontiguousarray(v, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    b = (b + np.uint64(0x7FFF) + ((b >> np.uint64(16)) & np.uint64(1))) & np.uint64(0xFFFF0000)
+    return b.astype(np.uint32).view(np.float32).astype(F64).reshape(np.shape(v))
+
+
+def _stored(v, store):
+    """The value of an intermediate tensor as later steps see it: itself (store None: float64 throughout), or its
+    bfloat16 rounding (store "bf16": the tensor is kept in bf16 between two steps, and a cast that follows it takes
+    its decisions on the kept values)."""
+    if store is None:
+        return v
+    if store == "bf16":
+        return bf16_round(v)
+    raise ValueError(f"unknown storage type {store!r}")
+
+
 def quant_weights(W1, W2):
     """Per-output-channel weight quantisation: each row of W1[e] (2f rows of length d) and of
     W2[e] (d rows of length f) gets one scale.  Returns (W1_hat, W2_hat) dequantised, float64."""
@@ -553,12 +574,17 @@ def quant_weights(W1, W2):
     return W1h, W2h
 
 
-def layer_fwd_fp8(x, logits, W1, W2, k: int, renorm: int = 1) -> dict:
+def layer_fwd_fp8(x, logits, W1, W2, k: int, renorm: int = 1, store=None) -> dict:
     """Forward with the FP8 casts as part of the function (float64 in between).
 
     Quantisation points: x per token before dispatch; W1, W2 per output channel; the
     SwiGLU output A per token; the FC2 output Y per token; the gate weight is applied
     after FC2 on the dequantised Y (Section 7's placement for FP8).
+
+    store = "bf16": the three tensors a step hands to the next one (the FC1 output H, the SwiGLU output before
+    its cast, the FC2 output before its cast) are rounded to bfloat16 where they are handed over, the type the
+    paper's BF16 mixed-precision training keeps activations in (Section 5); each cast then decides on the values a
+    bf16 pipeline really holds.  The sums and SwiGLU themselves stay float64.
     """
     T = x.shape[0]
     r = route(logits, k, renorm)
@@ -575,11 +601,11 @@ def layer_fwd_fp8(x, logits, W1, W2, k: int, renorm: int = 1) -> dict:
         lo, hi = int(r["offsets"][e]), int(r["offsets"][e + 1])
         if hi == lo:
             continue
-        G = xp[lo:hi] @ W1h[e, :f].T
-        U = xp[lo:hi] @ W1h[e, f:].T
+        G = _stored(xp[lo:hi] @ W1h[e, :f].T, store)
+        U = _stored(xp[lo:hi] @ W1h[e, f:].T, store)
         H[lo:hi, :f], H[lo:hi, f:] = G, U
-        A_hat[lo:hi] = fake_quant_rows(silu(G) * U)
-        Y[lo:hi] = A_hat[lo:hi] @ W2h[e].T
+        A_hat[lo:hi] = fake_quant_rows(_stored(silu(G) * U, store))
+        Y[lo:hi] = _stored(A_hat[lo:hi] @ W2h[e].T, store)
     Y_hat = fake_quant_rows(Y)
     y = combine(Y_hat, r["inv_perm"], r["w"], T, k)
     r.update(x_hat=x_hat, xp=xp, H=H, A=A_hat, Y=Y_hat, y=y)
@@ -671,7 +697,7 @@ def quant_weights_transposed(W1, W2):
     return W1th, W2th
 
 
-def expert_ffn_bwd_fp8(xp_hat, H, dYp, A_hat, offsets, W1, W2):
+def expert_ffn_bwd_fp8(xp_hat, H, dYp, A_hat, offsets, W1, W2, store=None):
     """The four backward GEMMs on E4M3 operands (float64 in between), straight-through casts.
 
         dA  = Qrow(dY) * Q(W2^T)^T          per-token dY, per-input-channel W2
@@ -679,6 +705,9 @@ def expert_ffn_bwd_fp8(xp_hat, H, dYp, A_hat, offsets, W1, W2):
         dxp = Qrow(dH) * Q(W1^T)^T          per-token dH, per-input-channel W1
         dW2[e] = Qg(dY_e)^T * Qg(A_e)        both per channel within 128-token groups (power-of-two
         dW1[e] = Qg(dH_e)^T * Qg(xp_e)       scales), A and xp being what the forward GEMMs consumed
+
+    store = "bf16": dH is rounded to bfloat16 where it is handed to its two casts (see layer_fwd_fp8); dA is
+    never kept, SwiGLU' reads it as summed.
     """
     E, two_f, d = W1.shape
     f = two_f // 2
@@ -690,7 +719,7 @@ def expert_ffn_bwd_fp8(xp_hat, H, dYp, A_hat, offsets, W1, W2):
         lo, hi = int(offsets[e]), int(offsets[e + 1])
         dA[lo:hi] = dYr[lo:hi] @ W2th[e].T
     dG, dU = swiglu_bwd(H[:, :f], H[:, f:], dA)
-    dH = np.concatenate([dG, dU], axis=1)
+    dH = _stored(np.concatenate([dG, dU], axis=1), store)
     dHr = fake_quant_rows(dH)
     dxp = np.zeros((M, d), F64)
     for e in range(E):
@@ -709,14 +738,15 @@ def expert_ffn_bwd_fp8(xp_hat, H, dYp, A_hat, offsets, W1, W2):
     return dict(dA=dA, dH=dH, dxp=dxp, dW1=dW1, dW2=dW2)
 
 
-def layer_bwd_fp8_gemm(x, logits, W1, W2, k: int, dy, fwd: dict, renorm: int = 1) -> dict:
+def layer_bwd_fp8_gemm(x, logits, W1, W2, k: int, dy, fwd: dict, renorm: int = 1, store=None) -> dict:
     """Backward of layer_fwd_fp8 with the backward GEMMs on E4M3 operands (expert_ffn_bwd_fp8);
-    everything outside the expert FFN is as in layer_bwd_fp8."""
+    everything outside the expert FFN is as in layer_bwd_fp8.  store = "bf16" (to be paired with a forward
+    made with the same setting): the weighted, dispatched dY and dH are rounded to bfloat16 before their casts."""
     T = x.shape[0]
     dy_hat = dequant_colgroup128(*quant_colgroup128(dy))
-    dYp = dispatch(dy_hat, fwd["perm"], k, row_mul=fwd["w"])
+    dYp = _stored(dispatch(dy_hat, fwd["perm"], k, row_mul=fwd["w"]), store)
     dw = gate_grad(dy_hat, fwd["Y"], fwd["inv_perm"], T, k)
-    g = expert_ffn_bwd_fp8(fwd["xp"], fwd["H"], dYp, fwd["A"], fwd["offsets"], W1, W2)
+    g = expert_ffn_bwd_fp8(fwd["xp"], fwd["H"], dYp, fwd["A"], fwd["offsets"], W1, W2, store=store)
     dx = combine(g["dxp"], fwd["inv_perm"], None, T, k)
     dz = route_bwd(logits, fwd["idx"], fwd["w"], dw, renorm)
     return dict(dy_hat=dy_hat, dYp=dYp, dw=dw, dxp=g["dxp"], dW1=g["dW1"], dW2=g["dW2"], dH=g["dH"], dx=dx, dz=dz)

@@ -327,3 +327,58 @@ def test_fp8_layer_exactness_case_detects_planted_mistakes(monkeypatch):
     monkeypatch.setattr(O, "combine", weight_before_cast)
     q = O.layer_fwd_fp8(x, z, W1, W2, k)
     assert not np.array_equal(q["y"], p["y"])
+
+
+# ---- storage-precision mode: casts decide on what a bf16 pipeline holds ------------------------------------------
+def test_bf16_round_matches_torch_and_breaks_ties_to_even():
+    """Pin: the oracle's bfloat16 rounding against torch's conversion (an independent routine), on random values
+    over many binades and on exact ties, which must go to the even mantissa."""
+    rng = np.random.default_rng(5)
+    v = (rng.standard_normal(200000) * np.exp2(rng.integers(-40, 40, 200000))).astype(np.float32)
+    ref = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(O.bf16_round(v), ref)
+    assert O.bf16_round(v.reshape(400, 500)).shape == (400, 500)
+    # 1 + 2^-8 lies halfway between 1 and 1 + 2^-7: goes to 1 (even); 1 + 3 * 2^-8 goes up to 1 + 2^-6 (even)
+    ties = np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, -(1 + 2.0 ** -8), 1 + 2.0 ** -8 + 2.0 ** -20, 0.0, -0.0])
+    want = np.array([1.0, 1 + 2.0 ** -6, -1.0, 1 + 2.0 ** -7, 0.0, 0.0])
+    assert np.array_equal(O.bf16_round(ties), want)
+    # float64 inputs are first rounded to float32, then to bf16, as a float32 producer would have done
+    assert O.bf16_round(np.array([1 + 2.0 ** -8 + 2.0 ** -40]))[0] == 1.0
+
+
+def test_fp8_layer_in_bf16_storage_mode():
+    """store="bf16" changes nothing but where the three handed-over tensors are rounded:
+    (a) on the lossless case (all of H, A, Y are small integers times powers of two, exact in bf16) it equals the
+        float64 mode, forward and both backwards, bit for bit;
+    (b) on random inputs H is bf16-representable and within half a bf16 ulp of the float64 mode's H, the SwiGLU
+        output fed to its cast is the bf16 rounding of SwiGLU of that H, and y stays within the distance a few
+        flipped e4m3 codes allow;
+    (c) the backward on e4m3 operands casts the bf16 rounding of dH: dH itself comes back bf16-representable."""
+    x, z, W1, W2, k = _exact_fp8_layer_inputs()
+    q0, q1 = O.layer_fwd_fp8(x, z, W1, W2, k), O.layer_fwd_fp8(x, z, W1, W2, k, store="bf16")
+    for name in ("H", "A", "Y", "y"):
+        assert np.array_equal(q0[name], q1[name]), name
+    dy = np.random.default_rng(2).choice([1.0, -2.0, 4.0, 0.5], size=q0["y"].shape)
+    g0, g1 = O.layer_bwd_fp8_gemm(x, z, W1, W2, k, dy, q0), O.layer_bwd_fp8_gemm(x, z, W1, W2, k, dy, q1, store=None)
+    for name in ("dx", "dW1", "dW2", "dz"):
+        assert np.array_equal(g0[name], g1[name]), name
+
+    cfg = MoEConfig("t", T=96, d=64, E=4, k=2, f=48, dtype="bf16", w_std=0.2, wr_std=0.3)
+    inp = make_inputs(cfg, seed=21)
+    inp["logits"] = O.router_logits(inp["x"], inp["W_r"]).astype(np.float32)
+    a = O.layer_fwd_fp8(inp["x"], inp["logits"], inp["W1"], inp["W2"], cfg.k)
+    b = O.layer_fwd_fp8(inp["x"], inp["logits"], inp["W1"], inp["W2"], cfg.k, store="bf16")
+    assert np.array_equal(O.bf16_round(b["H"]), b["H"])
+    assert not np.array_equal(a["H"], b["H"])
+    assert np.all(np.abs(a["H"] - b["H"]) <= np.abs(a["H"]) * 2.0 ** -8 + 1e-300)
+    f = cfg.f
+    pre = O.bf16_round(O.silu(b["H"][:, :f]) * b["H"][:, f:])
+    assert np.array_equal(b["A"], O.fake_quant_rows(pre))
+    assert np.linalg.norm(a["y"] - b["y"]) / np.linalg.norm(a["y"]) < 5e-2
+    with pytest.raises(ValueError):
+        O.layer_fwd_fp8(inp["x"], inp["logits"], inp["W1"], inp["W2"], cfg.k, store="fp16")
+    g = O.layer_bwd_fp8_gemm(inp["x"], inp["logits"], inp["W1"], inp["W2"], cfg.k, inp["dy"], b, store="bf16")
+    assert np.array_equal(O.bf16_round(g["dH"]), g["dH"]) and np.array_equal(O.bf16_round(g["dYp"]), g["dYp"])
+    gs = O.layer_bwd_fp8_gemm(inp["x"], inp["logits"], inp["W1"], inp["W2"], cfg.k, inp["dy"], b)
+    for name in ("dx", "dW1", "dW2"):
+        assert np.linalg.norm(g[name] - gs[name]) / np.linalg.norm(gs[name]) < 5e-2, name
