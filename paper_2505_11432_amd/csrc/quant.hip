@@ -174,9 +174,13 @@ __global__ void tgroup_offsets_kernel(const int32_t* __restrict__ offsets, int E
   }
 }
 
-// One block per (padded 128-token group, 64-channel slab).  Thread (rg, cq) holds rows rg, rg+16, ... (8 rows)
-// of four channels; channel maxima go through LDS; the codes are transposed through LDS so that global
-// memory sees 16-byte lanes forming 128-byte rows (one channel x 128 tokens).
+// One block per (padded 128-token group, 128-channel slab).  Thread (rgrp, cq) holds eight consecutive tokens
+// (rows 8*rgrp .. 8*rgrp+7) of eight consecutive channels: a wave's load touches four rows with 16 bytes per lane,
+// and a channel's eight codes of those tokens are eight consecutive bytes of the transposed output, written to the
+// LDS tile as one 8-byte word (16-byte chunks of a tile row are XOR-swizzled by the channel octet, so the sixteen
+// threads of a row group do not meet in one bank).  Channel maxima are reduced over the wave's four row groups with
+// shuffles and over the four waves through LDS.  Global memory sees 16-byte lanes forming 128-byte rows (one channel
+// x 128 tokens).
 template <typename T>
 __global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__ src,
                                                            const float* __restrict__ src_row_scale, int cols,
@@ -184,8 +188,9 @@ __global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__
                                                            const int32_t* __restrict__ pad_offsets, int E,
                                                            uint8_t* __restrict__ codes_t, long ldt,
                                                            uint8_t* __restrict__ e8m0, int slabs) {
-  __shared__ float cmax[16][64];
-  __shared__ __attribute__((aligned(16))) uint8_t tile[64][128 + 16];
+  constexpr int CH = 128;                           // channels per block
+  __shared__ float cmax[4][CH];
+  __shared__ __attribute__((aligned(16))) uint8_t tile[CH][128 + 16];
   const int g = blockIdx.x / slabs;
   const int tok0 = g * 128;                         // padded token column of this group
   if (tok0 >= pad_offsets[E]) return;
@@ -197,44 +202,62 @@ __global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__
   const int e = lo;
   const int r0 = offsets[e] + (tok0 - pad_offsets[e]);      // first source row of the group
   const int r_end = offsets[e + 1];
-  const int cq = threadIdx.x % 16, rg = threadIdx.x / 16;
-  const int c0 = (blockIdx.x % slabs) * 64;
-  const int c = c0 + cq * 4;
-  const bool col_ok = c < cols;
-  float v[8][4];
-  float amax[4] = {0.f, 0.f, 0.f, 0.f};
+  const int cq = threadIdx.x % 16, rgrp = threadIdx.x / 16;
+  const int c0 = (blockIdx.x % slabs) * CH;
+  const int c = c0 + cq * 8;
+  const bool col_ok = c < cols;                     // cols is a multiple of 16: all eight channels or none
+  float v[8][8];
+  float amax[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) amax[j] = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int r = r0 + rg + 16 * i;
+    const int r = r0 + rgrp * 8 + i;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) v[i][j] = 0.f;
+    for (int j = 0; j < 8; ++j) v[i][j] = 0.f;
     if (col_ok && r < r_end) {
       const T* p = src + (long)r * cols + c;
       if constexpr (sizeof(T) == 1) {
         // e4m3 codes with one scale per source row: the value is code * scale, rounded once to fp32
-        const int w = *reinterpret_cast<const int*>(p);
+        const int2 w = *reinterpret_cast<const int2*>(p);
         const float rs = src_row_scale[r];
-        v[i][0] = __builtin_amdgcn_cvt_f32_fp8(w, 0) * rs;
-        v[i][1] = __builtin_amdgcn_cvt_f32_fp8(w, 1) * rs;
-        v[i][2] = __builtin_amdgcn_cvt_f32_fp8(w, 2) * rs;
-        v[i][3] = __builtin_amdgcn_cvt_f32_fp8(w, 3) * rs;
-      } else {
+        v[i][0] = __builtin_amdgcn_cvt_f32_fp8(w.x, 0) * rs;
+        v[i][1] = __builtin_amdgcn_cvt_f32_fp8(w.x, 1) * rs;
+        v[i][2] = __builtin_amdgcn_cvt_f32_fp8(w.x, 2) * rs;
+        v[i][3] = __builtin_amdgcn_cvt_f32_fp8(w.x, 3) * rs;
+        v[i][4] = __builtin_amdgcn_cvt_f32_fp8(w.y, 0) * rs;
+        v[i][5] = __builtin_amdgcn_cvt_f32_fp8(w.y, 1) * rs;
+        v[i][6] = __builtin_amdgcn_cvt_f32_fp8(w.y, 2) * rs;
+        v[i][7] = __builtin_amdgcn_cvt_f32_fp8(w.y, 3) * rs;
+      } else if constexpr (sizeof(T) == 2) {
+        typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+        const bf16x8v w = *reinterpret_cast<const bf16x8v*>(p);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[i][j] = to_f32(p[j]);
+        for (int j = 0; j < 8; ++j) v[i][j] = static_cast<float>(w[j]);
+      } else {
+        const float4 a = *reinterpret_cast<const float4*>(p);
+        const float4 b = *reinterpret_cast<const float4*>(p + 4);
+        v[i][0] = a.x; v[i][1] = a.y; v[i][2] = a.z; v[i][3] = a.w;
+        v[i][4] = b.x; v[i][5] = b.y; v[i][6] = b.z; v[i][7] = b.w;
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) amax[j] = fmaxf(amax[j], fabsf(v[i][j]));
+      for (int j = 0; j < 8; ++j) amax[j] = fmaxf(amax[j], fabsf(v[i][j]));
     }
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) cmax[rg][cq * 4 + j] = amax[j];
+  for (int j = 0; j < 8; ++j) {
+    amax[j] = fmaxf(amax[j], __shfl_xor(amax[j], 16));
+    amax[j] = fmaxf(amax[j], __shfl_xor(amax[j], 32));
+  }
+  if ((threadIdx.x & 63) < 16) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) cmax[threadIdx.x >> 6][cq * 8 + j] = amax[j];
+  }
   __syncthreads();
-  float inv[4];
+  float inv[8];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    float m = 0.f;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) m = fmaxf(m, cmax[q][cq * 4 + j]);
+  for (int j = 0; j < 8; ++j) {
+    const float m = fmaxf(fmaxf(cmax[0][cq * 8 + j], cmax[1][cq * 8 + j]), fmaxf(cmax[2][cq * 8 + j], cmax[3][cq * 8 + j]));
     int k = 0;
     if (m > 0.f) {
       const unsigned bits = __float_as_uint(m);
@@ -242,22 +265,23 @@ __global__ void __launch_bounds__(256) quant_tgroup_kernel(const T* __restrict__
       k = max(-126, min(127, k));
     }
     inv[j] = __uint_as_float((unsigned)(127 - k) << 23);          // 2^-k, exact
-    if (rg == 0 && col_ok) e8m0[(long)g * cols + c + j] = (uint8_t)(k + 127);
+    if (rgrp == 0 && col_ok) e8m0[(long)g * cols + c + j] = (uint8_t)(k + 127);
   }
+  const int chunk = ((rgrp >> 1) ^ (cq & 7)) << 4;                 // swizzled 16-byte chunk of the tile row
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const unsigned w = pack4_e4m3(v[i][0] * inv[0], v[i][1] * inv[1], v[i][2] * inv[2], v[i][3] * inv[3]);
-    const int t = rg + 16 * i;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) tile[cq * 4 + j][t] = (uint8_t)(w >> (8 * j));
+  for (int j = 0; j < 8; ++j) {
+    uint2 w;
+    w.x = pack4_e4m3(v[0][j] * inv[j], v[1][j] * inv[j], v[2][j] * inv[j], v[3][j] * inv[j]);
+    w.y = pack4_e4m3(v[4][j] * inv[j], v[5][j] * inv[j], v[6][j] * inv[j], v[7][j] * inv[j]);
+    *reinterpret_cast<uint2*>(&tile[cq * 8 + j][chunk + ((rgrp & 1) << 3)]) = w;
   }
   __syncthreads();
 #pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
+  for (int pass = 0; pass < 4; ++pass) {
     const int ch = pass * 32 + threadIdx.x / 8, seg = threadIdx.x % 8;
     if (c0 + ch < cols)
       *reinterpret_cast<uint4*>(codes_t + (long)(c0 + ch) * ldt + tok0 + seg * 16) =
-          *reinterpret_cast<const uint4*>(&tile[ch][seg * 16]);
+          *reinterpret_cast<const uint4*>(&tile[ch][(seg ^ ((ch >> 3) & 7)) << 4]);
   }
 }
 
@@ -321,7 +345,7 @@ int launch_tgroup_offsets(const int32_t* offsets, int E, int32_t* pad_offsets, h
 int launch_quant_tgroup(const void* src, const float* src_row_scale, moe_dtype src_dt, int rows, int cols, const int32_t* offsets,
                         const int32_t* pad_offsets, int E, uint8_t* codes_t, long ldt, uint8_t* e8m0, hipStream_t s) {
   if (cols == 0) return MOE_OK;
-  const int slabs = cdiv(cols, 64);
+  const int slabs = cdiv(cols, 128);
   const int groups = cdiv(rows, 128) + E;              // upper bound on the padded group count
   const long grid = (long)groups * slabs;
   if (grid <= 0 || grid > 0x7fffffffL) return MOE_ERR_UNSUPPORTED;
