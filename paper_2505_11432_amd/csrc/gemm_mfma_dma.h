@@ -737,10 +737,10 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
     // by then), so the first fragment reads of a step, which all eight waves issue at once, overlap MFMAs instead of
     // leaving the matrix cores idle at every step start: -1.6 to -2.2 % on the forward kernels and dgrad1, -4 to -6 %
     // on the weight-gradient kernel with 64-deep steps (with 32-deep steps, two sub-steps each, it gains nothing).
-    // Measured kernel by kernel (builds side by side): no gain in the dgrad2 kernels, whose epilogues need the
-    // registers of the second fragment set (the fused-order one would reload registers inside the loop), and the
-    // e4m3 kernels have no room for a second set of 32-byte fragments.
-    constexpr bool XPIPE = !FP8 && (MODE != KSEG || NSTAGE == 2) && EPI != EPI_SWIGLU_BWD && EPI != EPI_SWIGLU_BWD_W;
+    // The dgrad2 kernels gain from it as well (-2.4 % plain, -0.9 % of the fused-order backward) once their epilogue
+    // ends with an explicit vmcnt wait (see there); before that a build with it measured no gain.  The e4m3 kernels
+    // have no room for a second set of 32-byte fragments.
+    constexpr bool XPIPE = !FP8 && (MODE != KSEG || NSTAGE == 2);
     if constexpr (XPIPE) {
       static_assert(KK % 2 == 0, "fragment sets alternate by sub-step parity");
       // opens step s: its loads have landed (at most the younger steps' loads are outstanding; the first step of a
@@ -1123,6 +1123,15 @@ __global__ void __launch_bounds__(WM * WN * 64) grouped_gemm_dma_kernel(Args p) 
             swiglu_bwd_block(acc[b / TN][b % TN], g, u, mb, nb, rows_valid, cols_valid, w_row, dw_sum);
             if (b % TN == TN - 1) write_dw(b / TN, dw_sum);
           }
+          // Every wave leaves this epilogue with none of its vector memory operations in flight.  The first step of
+          // the next tile would wait for them anyway (more stores than vmcnt can name), so this costs nothing; but
+          // it has to be said here, once, on a path every wave takes.  The k loop has a path without any vmcnt wait
+          // (the touching wave's), and when the compiler cannot rule out that the read-ahead loads of G and U above
+          // are still writing their registers on that path, it guards the registers where they are reused: if the
+          // allocation gives them to the fragments, that is a vmcnt wait in front of the fragment reads of every step
+          // on every wave, which there also waits for the tile loads issued a moment before (seen: dgrad2 +20 % after
+          // a change to the epilogue's arithmetic that moved the allocation).
+          wait_vmcnt<0>();
         }
       }
     }
