@@ -191,6 +191,7 @@ def ceilings(cfg, fp8_path=False):
     P, I, Z = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.moe_ceiling_mfma_loop.argtypes = [I, P, I, I, P, P]
     lib.moe_ceiling_mfma_lds_loop.argtypes = [P, I, I, P, P]
+    lib.moe_ceiling_mfma_lds_dma_loop.argtypes = [P, P, Z, I, I, I, P, P]
     lib.moe_ceiling_copy.argtypes = [P, P, Z, P]
     lib.moe_ceiling_read.argtypes = [P, Z, P, P]
     dev = "cuda:0"
@@ -226,6 +227,13 @@ def ceilings(cfg, fp8_path=False):
     image = torch.randn((65536,), generator=g).to(torch.bfloat16).to(dev)                     # 128 KiB of N(0,1) bf16
     ms = timed(lambda: lib.moe_ceiling_mfma_lds_loop(image.data_ptr(), 40000, wgs, sink.data_ptr(), stream), 3)
     out["mfma_lds_fed_loop_bf16_random_tflops"] = wgs * 8 * 40000 * 8 * 2.0 * 32 * 32 * 16 / ms / 1e9
+    # the same with the kernel's global -> LDS traffic beside it (64 KiB per workgroup and k-step from an L2-resident
+    # 4 MiB buffer): loads only, loads + the loaders' wait at the step end, loads + wait + a barrier per step
+    feed = torch.randn((2 * 1024 * 1024,), generator=g).to(torch.bfloat16).to(dev)
+    for key, flags in (("loads", 1), ("loads_wait", 3), ("loads_wait_barrier", 7)):
+        ms = timed(lambda: lib.moe_ceiling_mfma_lds_dma_loop(image.data_ptr(), feed.data_ptr(), feed.numel() * 2, 40000, flags, wgs,
+                                                             sink.data_ptr(), stream), 3)
+        out[f"mfma_lds_fed_loop_with_{key}_tflops"] = wgs * 8 * 40000 * 8 * 2.0 * 32 * 32 * 16 / ms / 1e9
     codes = torch.randint(0, 0x7f, (n_lane_slots, 32), generator=g, dtype=torch.int16)          # finite e4m3 magnitudes
     codes = (codes | (torch.randint(0, 2, (n_lane_slots, 32), generator=g, dtype=torch.int16) << 7)).to(torch.uint8)
     out["mfma_loop_fp8_const_tflops"] = mfma(True, torch.full((n_lane_slots, 32), 0x38, dtype=torch.uint8).to(dev))
@@ -256,7 +264,9 @@ def ceilings(cfg, fp8_path=False):
     del dh, xe, c
     out["note"] = ("mfma_loop_*: register-only loop of 32x32 MFMAs, 8 waves per CU; const = all-ones operands, random = "
                    "N(0,1) bf16 / uniformly random finite e4m3 codes, weightlike = N(0, 0.02); mfma_lds_fed_loop: the bf16 loop with "
-                   "its fragments read from LDS (N(0,1) data) at the grouped GEMM's ratio; library_gemm_*: "
+                   "its fragments read from LDS (N(0,1) data) at the grouped GEMM's ratio; _with_loads / _loads_wait / _loads_wait_barrier: "
+                   "plus 64 KiB of direct-to-LDS loads per workgroup and 64-deep k-step from an L2-resident buffer, the loading waves' "
+                   "wait at the end of each step, and a workgroup barrier per step; library_gemm_*: "
                    f"torch.matmul on the FC1 shape [rows,{cfg.d}] x [{cfg.d},{2 * cfg.f}] and on one expert's weight-gradient "
                    "shape, bf16, context only")
     return out

@@ -39,6 +39,16 @@ int moe_ceiling_mfma_loop(int fp8, const void* operands, int iters, int workgrou
 int moe_ceiling_mfma_lds_loop(const void* lds_image, int iters, int workgroups, float* sink,
                               void* stream);
 
+/* The LDS-fed loop with the grouped GEMM's global -> LDS traffic beside it.  Every four iterations
+ * (one k-step) the lower four waves of a workgroup issue sixteen 1 KiB direct-to-LDS loads each
+ * (64 KiB per workgroup and step) from slice (step mod src_bytes/64 KiB) of src, which all workgroups
+ * read alike (L2 hits after the first touch), into the half of the LDS image given by the step's
+ * parity.  flags: 1 = issue the loads; 2 = the loading waves wait for their loads at the end of each
+ * step; 4 = a workgroup barrier per step.  src [src_bytes] bf16 values, src_bytes a multiple of
+ * 64 KiB, at most 1 GiB; iters a multiple of 4.  Same FLOP count as the loops above (K = 16). */
+int moe_ceiling_mfma_lds_dma_loop(const void* lds_image, const void* src, size_t src_bytes, int iters,
+                                  int flags, int workgroups, float* sink, void* stream);
+
 /* dst[i] = src[i] for `bytes` bytes (multiple of 16), 16 bytes per lane, streaming loads/stores. */
 int moe_ceiling_copy(const void* src, void* dst, size_t bytes, void* stream);
 

@@ -105,6 +105,82 @@ __global__ void __launch_bounds__(512) mfma_lds_loop_kernel(const uint4* __restr
   sink[(size_t)blockIdx.x * 512 + threadIdx.x] = total;
 }
 
+// The LDS-fed loop with the grouped GEMM's global -> LDS traffic beside it: every four sub-steps (one k-step of 64)
+// the lower four waves issue sixteen 1 KiB direct-to-LDS loads each (64 KiB per workgroup and step) from a small
+// buffer that all workgroups read alike, so the loads hit in L2 after the first touch: the address unit, the L2 -> LDS
+// path and the LDS write port run at the kernel's rate, without its miss latency.  flags: 1 = issue the loads,
+// 2 = the loading waves wait for their loads at the end of the step (one stage in flight, as in the kernel),
+// 4 = a workgroup barrier per step.  The loads overwrite the LDS image the fragments are read from (with values of
+// the same distribution; which of the two a fragment read sees does not matter here).
+__global__ void __launch_bounds__(512) mfma_lds_dma_loop_kernel(const uint4* __restrict__ lds_image, const char* __restrict__ src,
+                                                                unsigned src_bytes, int iters, int flags, float* __restrict__ sink) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int LDS_BYTES = 131072;
+  for (int i = threadIdx.x; i < LDS_BYTES / 16; i += 512) reinterpret_cast<uint4*>(smem)[i] = lds_image[i];
+  __syncthreads();
+  const unsigned smem_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  bf16x8 a[2][2], b[2][4];
+  auto read_set = [&](int set, int step) __attribute__((always_inline)) {
+    const int base = ((step * 1031 + wave * 67) & 63) * 2048;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a[set][i] = *reinterpret_cast<const bf16x8*>(smem + ((base + i * 1024 + lane * 16) & (LDS_BYTES - 1)));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) b[set][j] = *reinterpret_cast<const bf16x8*>(smem + ((base + (2 + j) * 1024 + lane * 16) & (LDS_BYTES - 1)));
+  };
+  const bool loader = wave < 4;
+  const unsigned voff = (unsigned)lane * 16u;
+  read_set(0, 0);
+  read_set(1, 1);
+  for (int it = 0; it < iters; it += 4) {            // one k-step: four sub-steps of 8 MFMAs per wave
+    const int kstep = it >> 2;
+    if ((flags & 1) && loader) {
+      // 64 KiB of this step: slice (kstep mod slices) of src, ring half (kstep & 1) of the LDS image
+      const unsigned slices = src_bytes >> 16;
+      const char* sbase = src + (size_t)((unsigned)kstep % slices) * 65536u + (unsigned)wave * 16384u;
+      const unsigned dst = smem_lds + (unsigned)(kstep & 1) * 65536u + (unsigned)wave * 16384u;
+#pragma unroll
+      for (int j = 0; j < 16; ++j)
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff + (unsigned)j * 1024u), "s"(sbase),
+                     "s"(dst + (unsigned)j * 1024u)
+                     : "m0");
+    }
+#pragma unroll
+    for (int ss = 0; ss < 4; ++ss) {
+      const int s = ss & 1;
+      bf16x8 ca[2], cb[4];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) ca[i] = a[s][i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) cb[j] = b[s][j];
+      read_set(s, it + ss + 2);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[j], ca[i], acc[i][j], 0, 0, 0);
+    }
+    if ((flags & 2) && loader) __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));      // vmcnt(0), other counters open
+    if (flags & 4) __syncthreads();
+  }
+  __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));       // no load may still be on its way into LDS at the end
+  float total = 0.f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) total += acc[i][j][r];
+  sink[(size_t)blockIdx.x * 512 + threadIdx.x] = total;
+}
+
 __global__ void __launch_bounds__(256) copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
@@ -141,6 +217,17 @@ int moe_ceiling_mfma_lds_loop(const void* lds_image, int iters, int workgroups, 
   if (e != hipSuccess) return -4;
   mfma_lds_loop_kernel<<<dim3((unsigned)workgroups), dim3(512), 131072, reinterpret_cast<hipStream_t>(stream)>>>(
       static_cast<const uint4*>(lds_image), iters, sink);
+  return status(hipGetLastError());
+}
+
+int moe_ceiling_mfma_lds_dma_loop(const void* lds_image, const void* src, size_t src_bytes, int iters, int flags, int workgroups,
+                                  float* sink, void* stream) {
+  if (!lds_image || !src || !sink || iters < 0 || iters % 4 != 0 || workgroups < 1 || workgroups > 65535) return -1;
+  if (src_bytes < 65536 || src_bytes % 65536 != 0 || src_bytes > (1u << 30) || flags < 0 || flags > 7) return -1;
+  hipError_t e = hipFuncSetAttribute((const void*)mfma_lds_dma_loop_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+  if (e != hipSuccess) return -4;
+  mfma_lds_dma_loop_kernel<<<dim3((unsigned)workgroups), dim3(512), 131072, reinterpret_cast<hipStream_t>(stream)>>>(
+      static_cast<const uint4*>(lds_image), static_cast<const char*>(src), (unsigned)src_bytes, iters, flags, sink);
   return status(hipGetLastError());
 }
 

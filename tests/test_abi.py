@@ -200,12 +200,20 @@ def test_ceilings_library_exports_its_header():
     build.ensure_built()
     text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "moe_ceilings.h")).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(moe_ceiling_[a-z0-9_]+)\s*\(", text)))
-    assert names == ["moe_ceiling_copy", "moe_ceiling_mfma_lds_loop", "moe_ceiling_mfma_loop", "moe_ceiling_read"]
+    assert names == ["moe_ceiling_copy", "moe_ceiling_mfma_lds_dma_loop", "moe_ceiling_mfma_lds_loop", "moe_ceiling_mfma_loop",
+                     "moe_ceiling_read"]
     lib2 = ctypes.CDLL(build.CEILINGS_LIB_PATH)
     for n in names:
         assert hasattr(lib2, n), n
     assert lib2.moe_ceiling_copy(None, None, ctypes.c_size_t(16), None) == -1
     assert lib2.moe_ceiling_mfma_loop(0, None, 10, 1, None, None) == -1
+    lib2.moe_ceiling_mfma_lds_dma_loop.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int,
+                                                   ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib2.moe_ceiling_mfma_lds_dma_loop(None, None, 65536, 8, 7, 1, None, None) == -1
+    one = ctypes.c_void_p(16)                  # never dereferenced: the argument checks come first
+    assert lib2.moe_ceiling_mfma_lds_dma_loop(one, one, 65536, 6, 7, 1, one, None) == -1      # iters not a multiple of 4
+    assert lib2.moe_ceiling_mfma_lds_dma_loop(one, one, 65536 + 16, 8, 7, 1, one, None) == -1  # src not whole 64 KiB slices
+    assert lib2.moe_ceiling_mfma_lds_dma_loop(one, one, 65536, 8, 8, 1, one, None) == -1       # unknown flag
 
 
 def test_profile_labels():

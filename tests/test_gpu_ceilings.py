@@ -16,6 +16,7 @@ def lib():
     lib = ctypes.CDLL(build.CEILINGS_LIB_PATH)
     lib.moe_ceiling_mfma_loop.argtypes = [I, P, I, I, P, P]
     lib.moe_ceiling_mfma_lds_loop.argtypes = [P, I, I, P, P]
+    lib.moe_ceiling_mfma_lds_dma_loop.argtypes = [P, P, Z, I, I, I, P, P]
     lib.moe_ceiling_copy.argtypes = [P, P, Z, P]
     lib.moe_ceiling_read.argtypes = [P, Z, P, P]
     return lib
@@ -43,6 +44,15 @@ def test_mfma_loop_counts_every_mfma(lib):
     assert lib.moe_ceiling_mfma_lds_loop(image.data_ptr(), iters, wgs, sink.data_ptr(), stream) == 0
     torch.cuda.synchronize()
     assert torch.all(sink == 8 * 16 * iters * 16)
+    # the same with the direct-to-LDS loads beside it, in every combination of loads / waits / barriers: the loads
+    # bring in ones as well, so whatever a fragment read sees, the count stays
+    src = torch.ones((3 * 32768,), dtype=torch.bfloat16, device="cuda")                       # three 64 KiB slices
+    for flags in range(8):
+        sink.zero_()
+        assert lib.moe_ceiling_mfma_lds_dma_loop(image.data_ptr(), src.data_ptr(), src.numel() * 2, iters, flags, wgs,
+                                                 sink.data_ptr(), stream) == 0
+        torch.cuda.synchronize()
+        assert torch.all(sink == 8 * 16 * iters * 16), flags
 
 
 def test_copy_kernel_copies(lib):
