@@ -455,6 +455,11 @@ def main():
         key = "mfma_loop_fp8_random_tflops" if (fp8 and args.fp8_backward) else "mfma_loop_bf16_random_tflops"
         out["roofline"]["measured_ceiling"] = out["ceilings"][key]
         out["roofline"]["frac_of_measured_ceiling"] = gemm_tflops / out["ceilings"][key]
+        if not fp8:
+            # the same loop fed from LDS with the kernel's direct-to-LDS loads, waits and barriers beside it
+            k_loop = out["ceilings"]["mfma_lds_fed_loop_with_loads_wait_barrier_tflops"]
+            out["roofline"]["k_loop_ceiling"] = k_loop
+            out["roofline"]["frac_of_k_loop_ceiling"] = gemm_tflops / k_loop
     if not args.no_cpu_baseline:
         tokens = args.cpu_tokens or max(cfg.T // 4, 1)
         out["cpu_baseline"] = (cpu_baseline_fp8(cfg, inp, tokens, args.fp8_backward) if fp8
